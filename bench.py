@@ -1,0 +1,177 @@
+#!/usr/bin/env python3
+"""Benchmark of the SpMM + SDDMM hot path on one MI355X.
+
+A step is one pass of the whole path on the power-law workload: SpMM with
+N=128 followed by SDDMM with K=32, both on the same plan (the plan is built
+and uploaded once, outside the timed region, as the method prescribes).
+Prints ONE JSON line.
+
+  value      effective GFLOP/s of the step, (2*nnz*N + 2*nnz*K) / t
+  roofline   the dominant kernel (the SpMM task kernel, N=128): algorithmic
+             bytes of one SpMM / average duration of libra_spmm measured with
+             events on the launch stream inside the timed region
+  cpu_baseline  the CPU oracle timed on the host cores on the same workload
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def spmm_algorithmic_bytes(A, N: int, kref: int) -> int:
+    """Every array of the method once: col + val, rowptr, referenced rows of B, C."""
+    return A.nnz * (4 + 2) + 4 * (A.M + 1) + kref * N * 2 + A.M * N * 4
+
+
+def sddmm_algorithmic_bytes(A, K: int, mref: int, kref: int) -> int:
+    return A.nnz * (4 + 2 + 4) + 4 * (A.M + 1) + (mref + kref) * K * 2
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="powerlaw", choices=["powerlaw", "tiny", "community", "irregular", "gat"])
+    ap.add_argument("--N", type=int, default=0)
+    ap.add_argument("--K", type=int, default=0)
+    ap.add_argument("--small", action="store_true", help="reduced instance (smoke runs)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--mode", type=int, default=0)
+    ap.add_argument("--tau-spmm", type=int, default=0)
+    ap.add_argument("--tau-sddmm", type=int, default=0)
+    ap.add_argument("--ts", type=int, default=0)
+    ap.add_argument("--cs", type=int, default=0)
+    ap.add_argument("--natural-order", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (the path has no multi-GPU part); use --gpus 1", file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2506_22714_amd import binding as lb
+    from paper_2506_22714_amd import workloads as wl
+
+    if not os.path.exists(lb.LIB_PATH):
+        from paper_2506_22714_amd.build import build_library
+        build_library()
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+
+    defaults = {"powerlaw": (128, 32), "tiny": (32, 32), "community": (128, 32), "irregular": (32, 32), "gat": (64, 64)}
+    N = args.N or defaults[args.workload][0]
+    K = args.K or defaults[args.workload][1]
+    A = wl.make(args.workload, small=args.small)
+    B = wl.dense_normal(A.Kc, N, seed=wl.BASE_SEED + 201)
+    X = wl.dense_normal(A.M, K, seed=wl.BASE_SEED + 202)
+    Y = wl.dense_normal(A.Kc, K, seed=wl.BASE_SEED + 203)
+
+    t0 = time.perf_counter()
+    plan = lb.Plan.from_csr(A, mode=args.mode, spmm_min_vec_nnz=args.tau_spmm, sddmm_min_blk_nnz=args.tau_sddmm,
+                            ts=args.ts, cs=args.cs, flags=lb.FLAG_NATURAL_ORDER if args.natural_order else 0)
+    plan_s = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    plan.upload()
+    upload_s = time.perf_counter() - t0
+    st = plan.stats()
+
+    Bd, Xd, Yd = (torch.from_numpy(a).cuda() for a in (B, X, Y))
+    Cd = torch.empty((A.M, N), dtype=torch.float32, device="cuda")
+    od = torch.empty(A.nnz, dtype=torch.float32, device="cuda")
+
+    def step():
+        plan.spmm(Bd, out=Cd)
+        plan.sddmm(Xd, Yd, out=od)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    for i in range(args.steps):
+        ev[i][0].record()
+        plan.spmm(Bd, out=Cd)
+        ev[i][1].record()
+        plan.sddmm(Xd, Yd, out=od)
+        ev[i][2].record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t_start
+    ms_per_step = wall * 1e3 / args.steps
+    spmm_ms = np.array([e[0].elapsed_time(e[1]) for e in ev])
+    sddmm_ms = np.array([e[1].elapsed_time(e[2]) for e in ev])
+
+    flops_spmm = 2.0 * A.nnz * N
+    flops_sddmm = 2.0 * A.nnz * K
+    value = (flops_spmm + flops_sddmm) / (ms_per_step * 1e-3) / 1e9
+
+    kref = int(np.unique(A.col).size)
+    mref = int((np.diff(A.rowptr) > 0).sum())
+    bytes_spmm = spmm_algorithmic_bytes(A, N, kref)
+    bytes_sddmm = sddmm_algorithmic_bytes(A, K, mref, kref)
+    spmm_avg_s = float(spmm_ms.mean()) * 1e-3
+    achieved = bytes_spmm / spmm_avg_s / 1e9
+
+    out = {
+        "metric": "SpMM/SDDMM effective GFLOP/s (2*nnz*N + 2*nnz*K per step)",
+        "value": round(value, 1),
+        "unit": "GFLOP/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f16 in, f32 accumulate",
+        "data": "synthetic",
+        "config": {"workload": f"{args.workload}{'-small' if args.small else ''}: M={A.M} nnz={A.nnz} SpMM N={N} + SDDMM K={K}",
+                   "M": A.M, "nnz": A.nnz, "N": N, "K": K, "mode": args.mode,
+                   "tau_spmm": args.tau_spmm or 2, "tau_sddmm": args.tau_sddmm or 32},
+        "roofline": {"bound": "hbm", "kernel": f"spmm_task_kernel<f16,{min(N, 256)}>", "achieved": round(achieved, 1),
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                     "algorithmic_bytes": bytes_spmm, "avg_us": round(spmm_avg_s * 1e6, 2)},
+        "spmm": {"gflops": round(flops_spmm / spmm_avg_s / 1e9, 1), "median_us": round(float(np.median(spmm_ms)) * 1e3, 2),
+                 "min_us": round(float(spmm_ms.min()) * 1e3, 2), "bytes": bytes_spmm},
+        "sddmm": {"gflops": round(flops_sddmm / (float(sddmm_ms.mean()) * 1e-3) / 1e9, 1),
+                  "median_us": round(float(np.median(sddmm_ms)) * 1e3, 2), "min_us": round(float(sddmm_ms.min()) * 1e3, 2),
+                  "bytes": bytes_sddmm,
+                  "hbm_frac": round(bytes_sddmm / (float(sddmm_ms.mean()) * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)},
+        "plan": {"plan_s": round(plan_s, 4), "upload_s": round(upload_s, 4),
+                 "spmm_dense_share": round(st["spmm_dense_nnz"] / max(A.nnz, 1), 4),
+                 "sddmm_dense_share": round(st["sddmm_dense_nnz"] / max(A.nnz, 1), 4),
+                 "nnz1_vector_ratio": round(st["n_vectors_nnz1"] / max(st["n_vectors"], 1), 4),
+                 "spmm_tasks": st["spmm_tasks"], "spmm_chunk_tasks": st["spmm_chunk_tasks"],
+                 "spmm_gather_rows": st["spmm_gather_rows"]},
+    }
+
+    if not args.no_cpu_baseline:
+        import oracle
+        nt = oracle.max_threads()
+        t0 = time.perf_counter()
+        oracle.spmm(A.rowptr, A.col, A.val, B, want_scale=False)
+        t_sp = time.perf_counter() - t0
+        t0 = time.perf_counter()
+        oracle.sddmm(A.rowptr, A.col, A.val, X, Y, want_scale=False)
+        t_sd = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": round((flops_spmm + flops_sddmm) / (t_sp + t_sd) / 1e9, 2), "unit": "GFLOP/s",
+                               "cores": nt, "kind": "oracle",
+                               "sample": f"the whole workload once (SpMM {t_sp:.2f} s + SDDMM {t_sd:.2f} s)"}
+    print(json.dumps(out))
+    plan.close()
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -1,0 +1,224 @@
+/*
+ * libra.h - C ABI of the MI355X (gfx950) hybrid SpMM / SDDMM library.
+ *
+ * The method follows arXiv 2506.22714 ("Libra"):
+ *   - Section 2.2: rows are cut into windows of m rows; inside a window each
+ *     column that holds a nonzero is an m x 1 nonzero column vector, and
+ *     vectors are condensed k at a time into dense blocks.
+ *   - Section 4.2 (Eq. 2-6): nonzeros are split between a matrix-unit path
+ *     (here MFMA) and a scalar path (here VALU) by data reuse and utilisation.
+ *   - Section 4.3: heavy windows and long rows are decomposed into bounded
+ *     segments; decomposed segments accumulate with atomics.
+ *   - Section 4.4: bitmap-encoded dense blocks decoded in registers, popcount
+ *     offsets for SDDMM write-back, coalesced vector loads on the scalar path.
+ *
+ * Conventions
+ *   - Every function returns LIBRA_OK (0) or a negative LIBRA_ERR_* code.
+ *     Nothing throws or aborts across this boundary.
+ *   - "host" pointers are ordinary CPU memory; "device" pointers are HIP device
+ *     memory on the current device.  The library never allocates device
+ *     memory: the caller provides every device buffer and keeps it alive while
+ *     any call that uses it may still be running.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Compute calls are asynchronous on that stream.
+ *   - A is M x Kc in CSR (rowptr[M+1], col[nnz], val[nnz]); column indices are
+ *     strictly increasing inside a row (no duplicates).
+ */
+#ifndef LIBRA_H
+#define LIBRA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define LIBRA_VERSION 1
+
+/* ---- error codes ---- */
+#define LIBRA_OK                  0
+#define LIBRA_ERR_NULL           -1   /* a required pointer is NULL */
+#define LIBRA_ERR_SHAPE          -2   /* M, Kc, N, K, ld* out of range */
+#define LIBRA_ERR_ROWPTR         -3   /* rowptr[0] != 0 or rowptr decreases */
+#define LIBRA_ERR_COLUMN         -4   /* a column index is outside [0, Kc) */
+#define LIBRA_ERR_UNSORTED       -5   /* columns in a row not strictly increasing */
+#define LIBRA_ERR_TOO_LARGE      -6   /* nnz, M or Kc does not fit in 31 bits */
+#define LIBRA_ERR_DTYPE          -7   /* unknown or unsupported value type */
+#define LIBRA_ERR_OPTION         -8   /* an option is out of its documented range */
+#define LIBRA_ERR_UNSUPPORTED    -9   /* valid request the kernels do not cover (e.g. N not a multiple of 32) */
+#define LIBRA_ERR_NOT_UPLOADED  -10   /* compute call on a plan that has no device copy */
+#define LIBRA_ERR_BUFFER        -11   /* device buffer too small or misaligned */
+#define LIBRA_ERR_NOT_BUILT     -12   /* the sub-plan needed by the call was not built */
+#define LIBRA_ERR_HIP           -13   /* a HIP runtime call or kernel launch failed */
+#define LIBRA_ERR_NOMEM         -14   /* host allocation failed */
+
+/* ---- value types (storage type of A's values and of the dense operands) ---- */
+#define LIBRA_F16   0    /* IEEE binary16 in, fp32 accumulate (MFMA + VALU) */
+#define LIBRA_BF16  1    /* reserved; not yet accepted */
+#define LIBRA_F32   2    /* binary32 in, fp32 accumulate; scalar (VALU) path only */
+
+/* ---- distribution modes (Section 5.3.2: matrix-unit-only, scalar-only, hybrid) ---- */
+#define LIBRA_MODE_HYBRID       0
+#define LIBRA_MODE_DENSE_ONLY   1
+#define LIBRA_MODE_SCALAR_ONLY  2
+
+/* ---- option flags ---- */
+#define LIBRA_FLAG_NO_FILL_PADDING  1u  /* do not promote scalar-bound vectors into free slots of a window's last SpMM block */
+#define LIBRA_FLAG_NO_SPMM          2u  /* skip the SpMM sub-plan */
+#define LIBRA_FLAG_NO_SDDMM         4u  /* skip the SDDMM sub-plan */
+#define LIBRA_FLAG_NATURAL_ORDER    8u  /* keep tasks in window order instead of heaviest-first */
+
+typedef struct libra_plan_s libra_plan_t;   /* opaque; immutable after libra_plan() except for its values */
+
+/*
+ * Planner options.  A zero in any numeric field selects the default.
+ * struct_size must be sizeof(libra_plan_opts_t) (versioning).
+ */
+typedef struct {
+    uint32_t struct_size;
+    int32_t  mode;               /* LIBRA_MODE_*                                                         */
+    int32_t  window_rows;        /* m of Section 2.2. default 16; planner accepts 1..32, kernels need 16 */
+    int32_t  block_cols;         /* k (SpMM) / n (SDDMM) of Section 2.2. default 16; planner accepts 1..64, kernels need 16 */
+    int32_t  spmm_min_vec_nnz;   /* tau_spmm = ceil(eta_thr * m), Eq. 6: vector is dense iff NNZ_vector >= tau. default 2 */
+    int32_t  sddmm_min_blk_nnz;  /* tau_sddmm = ceil(eta_thr * m * n), Eq. 6: block is dense iff NNZ_block >= tau. default 32 */
+    int32_t  ts;                 /* Ts of Section 4.3: a window's dense part is decomposed iff it has more than ts blocks. default 8 */
+    int32_t  cs;                 /* Cs of Section 4.3: a residual row is decomposed iff it has more than cs nonzeros. default 128 */
+    int32_t  short_len;          /* Short_len of Section 4.3: a residual row with fewer nonzeros is "short". default 3 */
+    int32_t  sddmm_cs;           /* SDDMM residual nonzeros per scalar segment. default 1024 */
+    uint32_t flags;              /* LIBRA_FLAG_* */
+    int32_t  threads;            /* host threads for planning; 0 = hardware concurrency */
+} libra_plan_opts_t;
+
+/* ---- task table entry (Section 4.3: WindowOffset/RowOffset, CurWindow/CurRow, Atomic) ---- */
+#define LIBRA_TASK_WINDOW 0   /* dense blocks [begin,end) of window `id` plus the residual rows in scalar_mask */
+#define LIBRA_TASK_CHUNK  1   /* SpMM: residual nonzeros [begin,end) of the decomposed row `id`
+                                 SDDMM: residual nonzeros [begin,end) of the flat residual list (id = 0) */
+typedef struct {
+    int32_t  kind;
+    int32_t  id;
+    int32_t  begin, end;
+    uint32_t scalar_mask;   /* SpMM window task: bit r set = this task adds the residual nonzeros of row id*m + r  */
+    uint32_t atomic_mask;   /* SpMM window task: rows this task adds to C with atomics (they are zero-initialised first) */
+    uint32_t store_mask;    /* SpMM window task: rows this task alone owns and writes with plain stores (zeros included) */
+    uint32_t cost;          /* modelled rows of the dense operand this task fetches (ordering key) */
+} libra_task_t;
+
+/* ---- read-only host view of one sub-plan, for checkers ---- */
+typedef struct {
+    int64_t n_windows, n_blocks, n_dense_nnz, n_res_nnz, n_tasks, n_zero_rows;
+    int32_t window_rows, block_cols, words_per_block, value_dtype;
+    const int32_t  *win_blkptr;   /* [n_windows+1] first block of each window                                   */
+    const int32_t  *blk_cols;     /* [n_blocks*block_cols] column of each slot, -1 = padding                     */
+    const uint64_t *blk_bitmap;   /* [n_blocks*words_per_block] bit r*block_cols+s = nonzero at (row r, slot s)  */
+    const int32_t  *blk_valptr;   /* [n_blocks+1] first packed value of each block                               */
+    const void     *dense_val;    /* [n_dense_nnz] packed values in bit order, value_dtype                       */
+    const int32_t  *dense_perm;   /* [n_dense_nnz] CSR position of each packed value                             */
+    const int32_t  *res_rowptr;   /* SpMM: [M+1] residual CSR row pointer; SDDMM: NULL                           */
+    const int32_t  *res_row;      /* SDDMM: [n_res_nnz] row of each residual nonzero; SpMM: NULL                 */
+    const int32_t  *res_col;      /* [n_res_nnz]                                                                 */
+    const void     *res_val;      /* [n_res_nnz] value_dtype                                                     */
+    const int32_t  *res_perm;     /* [n_res_nnz] CSR position, increasing                                        */
+    const libra_task_t *tasks;    /* [n_tasks] in launch order                                                   */
+    const int32_t  *zero_rows;    /* SpMM: [n_zero_rows] rows cleared before the kernel (rows with >1 writer)    */
+} libra_subplan_view_t;
+
+/* ---- planner statistics (Section 4.2 cost model evaluated on the plan) ---- */
+typedef struct {
+    int64_t M, Kc, nnz;
+    int64_t n_windows;
+    int64_t n_vectors;            /* nonzero column vectors over all windows                         */
+    int64_t n_vectors_nnz1;       /* of which hold exactly one nonzero (Fig. 1's NNZ-1 ratio)        */
+    /* SpMM sub-plan */
+    int64_t spmm_dense_vectors, spmm_blocks, spmm_pad_slots, spmm_dense_nnz, spmm_res_nnz;
+    int64_t spmm_tasks, spmm_chunk_tasks, spmm_zero_rows;
+    int64_t spmm_short_rows, spmm_long_rows, spmm_split_rows;
+    int64_t spmm_gather_rows;     /* dense vectors + residual nonzeros: dense-operand rows fetched (Eq. 2 numerator vs denominator, summed) */
+    /* SDDMM sub-plan */
+    int64_t sddmm_dense_vectors, sddmm_blocks, sddmm_pad_slots, sddmm_dense_nnz, sddmm_res_nnz;
+    int64_t sddmm_tasks;
+    int64_t sddmm_gather_rows;    /* per dense block m + real columns, per residual nonzero 2 (Eq. 4, summed) */
+    double  plan_seconds;
+} libra_stats_t;
+
+/*
+ * libra_plan - build the distribution plan of A (Sections 4.2-4.3, host work only).
+ *   M, Kc        in   matrix shape, 1 <= M, Kc < 2^31
+ *   rowptr       in   host, int32[M+1], rowptr[0] = 0, non-decreasing, rowptr[M] = nnz < 2^31
+ *   col          in   host, int32[nnz], strictly increasing inside each row, 0 <= col < Kc
+ *   val          in   host, nnz values of type val_dtype (LIBRA_F16 or LIBRA_F32).  LIBRA_F32 forces
+ *                     LIBRA_MODE_SCALAR_ONLY (CDNA4 has no reduced-precision-free fp32 matrix path worth using).
+ *   opts         in   host, may be NULL (all defaults)
+ *   out          out  receives a new plan; release with libra_plan_destroy.  The inputs are copied,
+ *                     the caller may free them after the call.
+ * Errors: NULL, SHAPE, ROWPTR, COLUMN, UNSORTED, TOO_LARGE, DTYPE, OPTION, NOMEM.
+ */
+int libra_plan(int64_t M, int64_t Kc, const int32_t *rowptr, const int32_t *col,
+               const void *val, int val_dtype, const libra_plan_opts_t *opts, libra_plan_t **out);
+
+/* Bytes of device memory the plan's arrays need (256-byte aligned layout). */
+int libra_plan_device_bytes(const libra_plan_t *plan, size_t *bytes);
+
+/*
+ * libra_plan_upload - copy the plan's arrays into caller-owned device memory.
+ *   dev_buf  device pointer, 256-byte aligned, at least libra_plan_device_bytes() bytes;
+ *            the plan borrows it until libra_plan_destroy or the next upload.
+ * The copies are enqueued on `stream` and the stream is synchronised before returning
+ * (the sources are pageable host memory).  Errors: NULL, BUFFER, HIP.
+ */
+int libra_plan_upload(libra_plan_t *plan, void *dev_buf, size_t bytes, void *stream);
+
+/*
+ * libra_spmm - C = A * B (Section 2.2; Eq. 2 for what each path fetches).
+ *   B    device, Kc x N row-major with row stride ldb elements (ldb >= N, ldb % 8 == 0), plan's value type
+ *   C    device, M x N row-major fp32 with row stride ldc (ldc >= N, ldc % 4 == 0); fully overwritten
+ *        (rows of A without nonzeros become zeros); must not alias B.
+ *   N    multiple of 32 (fp16) or of 16 (fp32), 32 <= N <= 512
+ * Dense blocks run on MFMA (fp16 operands, fp32 accumulate), residual nonzeros on the VALU (fp32 FMA);
+ * rows with one writer are stored once, rows with several writers are cleared and accumulated with
+ * fp32 atomics (their summation order is not deterministic).
+ * Errors: NULL, SHAPE, UNSUPPORTED, NOT_UPLOADED, NOT_BUILT, HIP.
+ */
+int libra_spmm(const libra_plan_t *plan, const void *B, int32_t N, int64_t ldb,
+               float *C, int64_t ldc, void *stream);
+
+/*
+ * libra_sddmm - out[p] = val[p] * <X[i,:], Y[col[p],:]> for every nonzero p of row i (Section 2.2; Eq. 4).
+ *   X    device, M x K row-major, contiguous, plan's value type
+ *   Y    device, Kc x K row-major, contiguous, plan's value type
+ *   out  device, fp32[nnz] in A's CSR order; fully overwritten
+ *   K    32, 64 or 128
+ * Errors: NULL, UNSUPPORTED, NOT_UPLOADED, NOT_BUILT, HIP.
+ */
+int libra_sddmm(const libra_plan_t *plan, const void *X, const void *Y, int32_t K,
+                float *out, void *stream);
+
+/*
+ * libra_edge_softmax - row-wise softmax over CSR-ordered scores (the step between SDDMM and SpMM in an
+ * attention layer, Section 5.5): vals_out[p] = exp(scale*s[p] - mx_i) / sum_row exp(scale*s[q] - mx_i).
+ *   scores    device, fp32[nnz], CSR order
+ *   vals_out  device, nnz values of out_dtype (LIBRA_F16 or LIBRA_F32), CSR order; may not alias scores
+ * Errors: NULL, DTYPE, NOT_UPLOADED, HIP.
+ */
+int libra_edge_softmax(const libra_plan_t *plan, const float *scores, float scale,
+                       void *vals_out, int out_dtype, void *stream);
+
+/*
+ * libra_plan_set_values - replace A's values (same pattern): scatters CSR-ordered device values into the
+ * packed dense-block and residual arrays of both sub-plans' device copies.  The host copy keeps the old
+ * values.  `dtype` must equal the plan's value type.  Errors: NULL, DTYPE, NOT_UPLOADED, HIP.
+ */
+int libra_plan_set_values(libra_plan_t *plan, const void *vals_csr_dev, int dtype, void *stream);
+
+/* Host views for checkers; pointers stay valid until libra_plan_destroy.  which: 0 = SpMM, 1 = SDDMM. */
+int libra_plan_export(const libra_plan_t *plan, int which, libra_subplan_view_t *view);
+int libra_plan_stats(const libra_plan_t *plan, libra_stats_t *stats);
+
+void        libra_plan_destroy(libra_plan_t *plan);
+const char *libra_strerror(int code);
+int         libra_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LIBRA_H */

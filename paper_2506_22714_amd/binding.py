@@ -1,0 +1,300 @@
+"""ctypes binding of the C ABI in ``include/libra.h``.
+
+Argument marshalling only: every step of the SpMM / SDDMM path runs inside
+``liblibra.so``.  The module-level functions carry the same names as the C
+entry points; :class:`Plan` bundles a plan handle with the device buffer that
+backs it.  There is no fallback: if the shared library is missing, loading
+raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "liblibra.so")
+
+F16, BF16, F32 = 0, 1, 2
+MODE_HYBRID, MODE_DENSE_ONLY, MODE_SCALAR_ONLY = 0, 1, 2
+FLAG_NO_FILL_PADDING, FLAG_NO_SPMM, FLAG_NO_SDDMM, FLAG_NATURAL_ORDER = 1, 2, 4, 8
+TASK_WINDOW, TASK_CHUNK = 0, 1
+OK = 0
+ERR = dict(NULL=-1, SHAPE=-2, ROWPTR=-3, COLUMN=-4, UNSORTED=-5, TOO_LARGE=-6, DTYPE=-7, OPTION=-8,
+           UNSUPPORTED=-9, NOT_UPLOADED=-10, BUFFER=-11, NOT_BUILT=-12, HIP=-13, NOMEM=-14)
+
+
+class LibraError(RuntimeError):
+    def __init__(self, code: int, what: str):
+        self.code = code
+        super().__init__(f"{what}: {strerror(code)} ({code})")
+
+
+class PlanOpts(C.Structure):
+    _fields_ = [("struct_size", C.c_uint32), ("mode", C.c_int32), ("window_rows", C.c_int32),
+                ("block_cols", C.c_int32), ("spmm_min_vec_nnz", C.c_int32), ("sddmm_min_blk_nnz", C.c_int32),
+                ("ts", C.c_int32), ("cs", C.c_int32), ("short_len", C.c_int32), ("sddmm_cs", C.c_int32),
+                ("flags", C.c_uint32), ("threads", C.c_int32)]
+
+    def __init__(self, **kw):
+        super().__init__(**kw)
+        self.struct_size = C.sizeof(PlanOpts)
+
+
+class Task(C.Structure):
+    _fields_ = [("kind", C.c_int32), ("id", C.c_int32), ("begin", C.c_int32), ("end", C.c_int32),
+                ("scalar_mask", C.c_uint32), ("atomic_mask", C.c_uint32), ("store_mask", C.c_uint32),
+                ("cost", C.c_uint32)]
+
+
+TASK_DTYPE = np.dtype([("kind", "<i4"), ("id", "<i4"), ("begin", "<i4"), ("end", "<i4"),
+                       ("scalar_mask", "<u4"), ("atomic_mask", "<u4"), ("store_mask", "<u4"), ("cost", "<u4")])
+
+
+class SubplanView(C.Structure):
+    _fields_ = [("n_windows", C.c_int64), ("n_blocks", C.c_int64), ("n_dense_nnz", C.c_int64),
+                ("n_res_nnz", C.c_int64), ("n_tasks", C.c_int64), ("n_zero_rows", C.c_int64),
+                ("window_rows", C.c_int32), ("block_cols", C.c_int32), ("words_per_block", C.c_int32),
+                ("value_dtype", C.c_int32),
+                ("win_blkptr", C.c_void_p), ("blk_cols", C.c_void_p), ("blk_bitmap", C.c_void_p),
+                ("blk_valptr", C.c_void_p), ("dense_val", C.c_void_p), ("dense_perm", C.c_void_p),
+                ("res_rowptr", C.c_void_p), ("res_row", C.c_void_p), ("res_col", C.c_void_p),
+                ("res_val", C.c_void_p), ("res_perm", C.c_void_p), ("tasks", C.c_void_p),
+                ("zero_rows", C.c_void_p)]
+
+
+_STATS_I64 = ["M", "Kc", "nnz", "n_windows", "n_vectors", "n_vectors_nnz1",
+              "spmm_dense_vectors", "spmm_blocks", "spmm_pad_slots", "spmm_dense_nnz", "spmm_res_nnz",
+              "spmm_tasks", "spmm_chunk_tasks", "spmm_zero_rows",
+              "spmm_short_rows", "spmm_long_rows", "spmm_split_rows", "spmm_gather_rows",
+              "sddmm_dense_vectors", "sddmm_blocks", "sddmm_pad_slots", "sddmm_dense_nnz", "sddmm_res_nnz",
+              "sddmm_tasks", "sddmm_gather_rows"]
+
+
+class Stats(C.Structure):
+    _fields_ = [(n, C.c_int64) for n in _STATS_I64] + [("plan_seconds", C.c_double)]
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """Load liblibra.so (built by ``paper_2506_22714_amd.build``).  Raises if absent."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is not built; run `python -m paper_2506_22714_amd.build` "
+                               "(or __graft_entry__.build()) first")
+        L = C.CDLL(LIB_PATH)
+        vp, i32, i64, sz = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t
+        L.libra_plan.argtypes = [i64, i64, vp, vp, vp, C.c_int, C.POINTER(PlanOpts), C.POINTER(vp)]
+        L.libra_plan_device_bytes.argtypes = [vp, C.POINTER(sz)]
+        L.libra_plan_upload.argtypes = [vp, vp, sz, vp]
+        L.libra_spmm.argtypes = [vp, vp, i32, i64, vp, i64, vp]
+        L.libra_sddmm.argtypes = [vp, vp, vp, i32, vp, vp]
+        L.libra_edge_softmax.argtypes = [vp, vp, C.c_float, vp, C.c_int, vp]
+        L.libra_plan_set_values.argtypes = [vp, vp, C.c_int, vp]
+        L.libra_plan_export.argtypes = [vp, C.c_int, C.POINTER(SubplanView)]
+        L.libra_plan_stats.argtypes = [vp, C.POINTER(Stats)]
+        L.libra_plan_destroy.argtypes = [vp]
+        L.libra_plan_destroy.restype = None
+        L.libra_strerror.argtypes = [C.c_int]
+        L.libra_strerror.restype = C.c_char_p
+        L.libra_version.restype = C.c_int
+        for n in ("libra_plan", "libra_plan_device_bytes", "libra_plan_upload", "libra_spmm", "libra_sddmm",
+                  "libra_edge_softmax", "libra_plan_set_values", "libra_plan_export", "libra_plan_stats"):
+            getattr(L, n).restype = C.c_int
+        _lib = L
+    return _lib
+
+
+def strerror(code: int) -> str:
+    return lib().libra_strerror(code).decode()
+
+
+def libra_version() -> int:
+    return int(lib().libra_version())
+
+
+def _np_ptr(a):
+    return None if a is None else C.c_void_p(a.ctypes.data)
+
+
+def _np_dtype_code(a: np.ndarray) -> int:
+    if a.dtype == np.float16:
+        return F16
+    if a.dtype == np.float32:
+        return F32
+    raise TypeError(f"unsupported value dtype {a.dtype}")
+
+
+def _check(rc: int, what: str):
+    if rc != OK:
+        raise LibraError(rc, what)
+
+
+# ---- entry points, same names as the C ABI (raw pointers / numpy host arrays in, codes checked) ----
+def libra_plan(M: int, Kc: int, rowptr: np.ndarray, col: np.ndarray, val: np.ndarray, opts: PlanOpts | None = None,
+               val_dtype: int | None = None) -> C.c_void_p:
+    rowptr = np.ascontiguousarray(rowptr, dtype=np.int32)
+    col = np.ascontiguousarray(col, dtype=np.int32)
+    val = np.ascontiguousarray(val)
+    handle = C.c_void_p()
+    rc = lib().libra_plan(M, Kc, _np_ptr(rowptr), _np_ptr(col), _np_ptr(val),
+                          _np_dtype_code(val) if val_dtype is None else val_dtype,
+                          C.byref(opts) if opts is not None else None, C.byref(handle))
+    _check(rc, "libra_plan")
+    return handle
+
+
+def libra_plan_device_bytes(plan) -> int:
+    n = C.c_size_t()
+    _check(lib().libra_plan_device_bytes(plan, C.byref(n)), "libra_plan_device_bytes")
+    return int(n.value)
+
+
+def libra_plan_upload(plan, dev_ptr: int, nbytes: int, stream: int = 0):
+    _check(lib().libra_plan_upload(plan, C.c_void_p(dev_ptr), nbytes, C.c_void_p(stream)), "libra_plan_upload")
+
+
+def libra_spmm(plan, B_ptr: int, N: int, ldb: int, C_ptr: int, ldc: int, stream: int = 0):
+    _check(lib().libra_spmm(plan, C.c_void_p(B_ptr), N, ldb, C.c_void_p(C_ptr), ldc, C.c_void_p(stream)), "libra_spmm")
+
+
+def libra_sddmm(plan, X_ptr: int, Y_ptr: int, K: int, out_ptr: int, stream: int = 0):
+    _check(lib().libra_sddmm(plan, C.c_void_p(X_ptr), C.c_void_p(Y_ptr), K, C.c_void_p(out_ptr), C.c_void_p(stream)),
+           "libra_sddmm")
+
+
+def libra_edge_softmax(plan, scores_ptr: int, scale: float, out_ptr: int, out_dtype: int, stream: int = 0):
+    _check(lib().libra_edge_softmax(plan, C.c_void_p(scores_ptr), C.c_float(scale), C.c_void_p(out_ptr), out_dtype,
+                                    C.c_void_p(stream)), "libra_edge_softmax")
+
+
+def libra_plan_set_values(plan, vals_ptr: int, dtype: int, stream: int = 0):
+    _check(lib().libra_plan_set_values(plan, C.c_void_p(vals_ptr), dtype, C.c_void_p(stream)), "libra_plan_set_values")
+
+
+def libra_plan_destroy(plan):
+    lib().libra_plan_destroy(plan)
+
+
+def _arr(ptr, n, dtype):
+    if not ptr or n == 0:
+        return np.zeros(0, dtype=dtype)
+    buf = (C.c_char * (n * np.dtype(dtype).itemsize)).from_address(ptr)
+    return np.frombuffer(buf, dtype=dtype).copy()
+
+
+def libra_plan_export(plan, which: int) -> dict:
+    """Copies of one sub-plan's host arrays as numpy arrays (0 = SpMM, 1 = SDDMM)."""
+    v = SubplanView()
+    _check(lib().libra_plan_export(plan, which, C.byref(v)), "libra_plan_export")
+    vt = np.float16 if v.value_dtype == F16 else np.float32
+    nb, KB, wpb = v.n_blocks, v.block_cols, v.words_per_block
+    out = dict(n_windows=v.n_windows, n_blocks=nb, n_dense_nnz=v.n_dense_nnz, n_res_nnz=v.n_res_nnz,
+               n_tasks=v.n_tasks, window_rows=v.window_rows, block_cols=KB, words_per_block=wpb,
+               win_blkptr=_arr(v.win_blkptr, v.n_windows + 1, np.int32),
+               blk_cols=_arr(v.blk_cols, nb * KB, np.int32).reshape(nb, KB),
+               blk_bitmap=_arr(v.blk_bitmap, nb * wpb, np.uint64).reshape(nb, wpb),
+               blk_valptr=_arr(v.blk_valptr, nb + 1, np.int32),
+               dense_val=_arr(v.dense_val, v.n_dense_nnz, vt),
+               dense_perm=_arr(v.dense_perm, v.n_dense_nnz, np.int32),
+               res_col=_arr(v.res_col, v.n_res_nnz, np.int32),
+               res_val=_arr(v.res_val, v.n_res_nnz, vt),
+               res_perm=_arr(v.res_perm, v.n_res_nnz, np.int32),
+               tasks=_arr(v.tasks, v.n_tasks, TASK_DTYPE),
+               zero_rows=_arr(v.zero_rows, v.n_zero_rows, np.int32))
+    st = libra_plan_stats(plan)
+    if which == 0:
+        out["res_rowptr"] = _arr(v.res_rowptr, st["M"] + 1, np.int32)
+    else:
+        out["res_row"] = _arr(v.res_row, v.n_res_nnz, np.int32)
+    return out
+
+
+def libra_plan_stats(plan) -> dict:
+    s = Stats()
+    _check(lib().libra_plan_stats(plan, C.byref(s)), "libra_plan_stats")
+    return {n: getattr(s, n) for n, _t in Stats._fields_}
+
+
+# ---- convenience wrapper: a plan handle plus the torch buffer that backs its device copy ----
+class Plan:
+    def __init__(self, M, Kc, rowptr, col, val, **opts):
+        self.M, self.Kc = int(M), int(Kc)
+        self.val_dtype = _np_dtype_code(np.asarray(val))
+        self.handle = libra_plan(self.M, self.Kc, rowptr, col, val, PlanOpts(**opts) if opts else None)
+        self.nnz = libra_plan_stats(self.handle)["nnz"]
+        self._buf = None
+
+    @classmethod
+    def from_csr(cls, csr, val=None, **opts):
+        return cls(csr.M, csr.Kc, csr.rowptr, csr.col, csr.val if val is None else val, **opts)
+
+    def close(self):
+        if self.handle is not None:
+            libra_plan_destroy(self.handle)
+            self.handle = None
+            self._buf = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def stats(self) -> dict:
+        return libra_plan_stats(self.handle)
+
+    def export(self, which: int) -> dict:
+        return libra_plan_export(self.handle, which)
+
+    def upload(self, device="cuda"):
+        import torch
+        n = libra_plan_device_bytes(self.handle)
+        self._buf = torch.empty(n, dtype=torch.uint8, device=device)
+        libra_plan_upload(self.handle, self._buf.data_ptr(), n, torch.cuda.current_stream().cuda_stream)
+        return self
+
+    def _torch_dtype(self):
+        import torch
+        return torch.float16 if self.val_dtype == F16 else torch.float32
+
+    def spmm(self, B, out=None):
+        import torch
+        assert B.is_cuda and B.dtype == self._torch_dtype() and B.dim() == 2 and B.stride(1) == 1
+        N = B.shape[1]
+        if out is None:
+            out = torch.empty((self.M, N), dtype=torch.float32, device=B.device)
+        assert out.is_cuda and out.dtype == torch.float32 and out.shape == (self.M, N) and out.stride(1) == 1
+        libra_spmm(self.handle, B.data_ptr(), N, B.stride(0), out.data_ptr(), out.stride(0),
+                   torch.cuda.current_stream().cuda_stream)
+        return out
+
+    def sddmm(self, X, Y, out=None):
+        import torch
+        assert X.is_cuda and Y.is_cuda and X.dtype == Y.dtype == self._torch_dtype()
+        assert X.is_contiguous() and Y.is_contiguous() and X.shape[1] == Y.shape[1]
+        if out is None:
+            out = torch.empty(self.nnz, dtype=torch.float32, device=X.device)
+        assert out.is_cuda and out.dtype == torch.float32 and out.numel() == self.nnz and out.is_contiguous()
+        libra_sddmm(self.handle, X.data_ptr(), Y.data_ptr(), X.shape[1], out.data_ptr(),
+                    torch.cuda.current_stream().cuda_stream)
+        return out
+
+    def edge_softmax(self, scores, scale: float, out=None):
+        import torch
+        assert scores.is_cuda and scores.dtype == torch.float32 and scores.is_contiguous()
+        if out is None:
+            out = torch.empty(self.nnz, dtype=self._torch_dtype(), device=scores.device)
+        code = F16 if out.dtype == torch.float16 else F32
+        libra_edge_softmax(self.handle, scores.data_ptr(), scale, out.data_ptr(), code,
+                           torch.cuda.current_stream().cuda_stream)
+        return out
+
+    def set_values(self, vals):
+        import torch
+        assert vals.is_cuda and vals.dtype == self._torch_dtype() and vals.is_contiguous() and vals.numel() == self.nnz
+        libra_plan_set_values(self.handle, vals.data_ptr(), self.val_dtype, torch.cuda.current_stream().cuda_stream)

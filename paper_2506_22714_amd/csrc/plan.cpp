@@ -1,0 +1,506 @@
+// Host planner: 2D-aware workload distribution (Section 4.2), hybrid load
+// balancing (Section 4.3) and format translation (bitmap blocks + residual CSR,
+// Section 4.1 item 3) for the SpMM and SDDMM sub-plans.  Pure host C++; windows
+// are processed independently on a pool of std::threads and concatenated in
+// window order, so the result does not depend on the thread count.
+#include <algorithm>
+#include <chrono>
+#include <cstring>
+#include <new>
+#include <thread>
+
+#include "plan_internal.h"
+
+using namespace libra;
+
+namespace {
+
+struct Entry {
+    uint64_t key;   // col << 32 | csr position  (position order = row order inside a window)
+    int32_t r;      // row inside the window
+};
+struct Vec {
+    int32_t col, cnt, first;   // entries [first, first+cnt) of the sorted window
+};
+
+// Output of one contiguous range of windows, indices local to the range.
+struct Part {
+    SubPlan spmm, sddmm;
+    int64_t n_vectors = 0, n_vectors_nnz1 = 0;
+};
+
+struct Ctx {
+    int64_t M, nnz;
+    const int32_t *rowptr, *col;
+    const uint8_t *val;
+    int vsize;
+    Resolved o;
+    int words;
+};
+
+inline void push_val(std::vector<uint8_t> &dst, const Ctx &c, int32_t p) {
+    const uint8_t *s = c.val + (size_t)p * c.vsize;
+    dst.insert(dst.end(), s, s + c.vsize);
+}
+
+// Emit one bitmap block made of the vectors `ids` (slot order) of the current window.
+// Returns the mask of window rows that hold a nonzero of the block.
+uint32_t emit_block(const Ctx &c, SubPlan &sp, const std::vector<Entry> &ent, const std::vector<Vec> &vecs,
+                    const int32_t *ids, int n, std::vector<std::pair<int32_t, int32_t>> &tmp) {
+    const int KB = c.o.KB;
+    tmp.clear();
+    uint32_t rowmask = 0;
+    for (int s = 0; s < n; ++s) {
+        const Vec &v = vecs[ids[s]];
+        sp.blk_cols.push_back(v.col);
+        for (int e = v.first; e < v.first + v.cnt; ++e) {
+            tmp.emplace_back(ent[e].r * KB + s, (int32_t)(ent[e].key & 0xffffffffu));
+            rowmask |= 1u << ent[e].r;
+        }
+    }
+    for (int s = n; s < KB; ++s) sp.blk_cols.push_back(-1);
+    std::sort(tmp.begin(), tmp.end());
+    size_t w0 = sp.blk_bitmap.size();
+    sp.blk_bitmap.resize(w0 + c.words, 0);
+    for (auto &bp : tmp) {
+        sp.blk_bitmap[w0 + bp.first / 64] |= 1ull << (bp.first % 64);
+        sp.dense_perm.push_back(bp.second);
+        push_val(sp.dense_val, c, bp.second);
+    }
+    sp.blk_valptr.push_back((int32_t)sp.dense_perm.size());
+    sp.dense_vectors += n;
+    sp.pad_slots += KB - n;
+    return rowmask;
+}
+
+void plan_range(const Ctx &c, int64_t w0, int64_t w1, Part &out) {
+    const Resolved &o = c.o;
+    const int W = o.W, KB = o.KB;
+    std::vector<Entry> ent;
+    std::vector<Vec> vecs;
+    std::vector<int32_t> ids, cand, resp;
+    std::vector<uint8_t> is_dense;
+    std::vector<std::pair<int32_t, int32_t>> tmp;
+    std::vector<uint32_t> blk_rowmask;
+    SubPlan &sa = out.spmm, &sd = out.sddmm;
+    sa.win_blkptr.push_back(0);
+    sa.blk_valptr.push_back(0);
+    sd.win_blkptr.push_back(0);
+    sd.blk_valptr.push_back(0);
+    const int64_t row_base = w0 * W;
+    const int64_t row_end_all = std::min<int64_t>(c.M, w1 * W);
+    if (o.build_spmm) sa.res_rowptr.assign((size_t)(row_end_all - row_base) + 1, 0);
+
+    for (int64_t w = w0; w < w1; ++w) {
+        const int64_t r0 = w * W, r1 = std::min<int64_t>(c.M, r0 + W);
+        // ---- census: nonzero column vectors of the window (Section 2.2) ----
+        ent.clear();
+        for (int64_t i = r0; i < r1; ++i)
+            for (int32_t p = c.rowptr[i]; p < c.rowptr[i + 1]; ++p)
+                ent.push_back({((uint64_t)(uint32_t)c.col[p] << 32) | (uint32_t)p, (int32_t)(i - r0)});
+        std::sort(ent.begin(), ent.end(), [](const Entry &a, const Entry &b) { return a.key < b.key; });
+        vecs.clear();
+        for (int e = 0; e < (int)ent.size();) {
+            int32_t cc = (int32_t)(ent[e].key >> 32);
+            int f = e;
+            while (e < (int)ent.size() && (int32_t)(ent[e].key >> 32) == cc) ++e;
+            vecs.push_back({cc, e - f, f});
+        }
+        out.n_vectors += (int64_t)vecs.size();
+        for (auto &v : vecs) out.n_vectors_nnz1 += v.cnt == 1;
+
+        // =================== SpMM sub-plan ===================
+        if (o.build_spmm) {
+            is_dense.assign(vecs.size(), 0);
+            ids.clear();
+            if (o.mode != LIBRA_MODE_SCALAR_ONLY) {
+                const int tau = o.mode == LIBRA_MODE_DENSE_ONLY ? 1 : o.tau_spmm;
+                for (int v = 0; v < (int)vecs.size(); ++v)
+                    if (vecs[v].cnt >= tau) ids.push_back(v);           // ascending column
+                if (!ids.empty() && o.fill && o.mode == LIBRA_MODE_HYBRID && ids.size() % KB) {
+                    // free slots of the last block take scalar-bound vectors, densest first
+                    size_t free_slots = KB - ids.size() % KB;
+                    cand.clear();
+                    for (int v = 0; v < (int)vecs.size(); ++v)
+                        if (vecs[v].cnt < tau) cand.push_back(v);
+                    std::stable_sort(cand.begin(), cand.end(),
+                                     [&](int a, int b) { return vecs[a].cnt > vecs[b].cnt; });
+                    for (size_t q = 0; q < cand.size() && q < free_slots; ++q) ids.push_back(cand[q]);
+                }
+            }
+            for (int v : ids) is_dense[v] = 1;
+            const int32_t b0 = (int32_t)sa.n_blocks();
+            blk_rowmask.clear();
+            for (size_t s = 0; s < ids.size(); s += KB)
+                blk_rowmask.push_back(emit_block(c, sa, ent, vecs, ids.data() + s,
+                                                 (int)std::min<size_t>(KB, ids.size() - s), tmp));
+            const int32_t b1 = (int32_t)sa.n_blocks();
+            sa.win_blkptr.push_back(b1);
+            // residual nonzeros in CSR order
+            resp.clear();
+            for (int v = 0; v < (int)vecs.size(); ++v)
+                if (!is_dense[v])
+                    for (int e = vecs[v].first; e < vecs[v].first + vecs[v].cnt; ++e)
+                        resp.push_back((int32_t)(ent[e].key & 0xffffffffu));
+            std::sort(resp.begin(), resp.end());
+            int32_t rlen[32] = {0};
+            {
+                int64_t i = r0;
+                for (int32_t p : resp) {
+                    while (p >= c.rowptr[i + 1]) ++i;
+                    ++rlen[i - r0];
+                    sa.res_perm.push_back(p);
+                    sa.res_col.push_back(c.col[p]);
+                    push_val(sa.res_val, c, p);
+                }
+            }
+            for (int64_t i = r0; i < r1; ++i)
+                sa.res_rowptr[(size_t)(i - row_base) + 1] = sa.res_rowptr[(size_t)(i - row_base)] + rlen[i - r0];
+
+            // ---- hybrid load balancing (Section 4.3) ----
+            uint32_t valid = 0, split_mask = 0, scalar_mask = 0;
+            for (int r = 0; r < (int)(r1 - r0); ++r) {
+                valid |= 1u << r;
+                if (rlen[r] == 0) continue;
+                if (rlen[r] < o.short_len) {
+                    ++sa.short_rows;
+                } else {
+                    ++sa.long_rows;
+                    if (rlen[r] > o.Cs) split_mask |= 1u << r;
+                }
+                if (!(split_mask >> r & 1)) scalar_mask |= 1u << r;
+            }
+            sa.split_rows += __builtin_popcount(split_mask);
+            auto touched = [&](int32_t g0, int32_t g1) {
+                uint32_t m = 0;
+                for (int32_t b = g0; b < g1; ++b) m |= blk_rowmask[b - b0];
+                return m;
+            };
+            auto cols_in = [&](int32_t g0, int32_t g1) {
+                uint32_t n = 0;
+                for (int32_t b = g0; b < g1; ++b)
+                    for (int s = 0; s < KB; ++s) n += sa.blk_cols[(size_t)b * KB + s] >= 0;
+                return n;
+            };
+            uint32_t res_unsplit = 0;
+            for (int r = 0; r < (int)(r1 - r0); ++r)
+                if (scalar_mask >> r & 1) res_unsplit += rlen[r];
+            if (b1 - b0 > o.Ts) {
+                for (int32_t g0 = b0; g0 < b1; g0 += o.Ts) {
+                    int32_t g1 = std::min(b1, g0 + o.Ts);
+                    sa.tasks.push_back({LIBRA_TASK_WINDOW, (int32_t)w, g0, g1, 0u, touched(g0, g1), 0u, cols_in(g0, g1)});
+                }
+                if (scalar_mask)
+                    sa.tasks.push_back({LIBRA_TASK_WINDOW, (int32_t)w, b1, b1, scalar_mask, scalar_mask, 0u, res_unsplit});
+                for (int64_t i = r0; i < r1; ++i) sa.zero_rows.push_back((int32_t)i);
+            } else {
+                sa.tasks.push_back({LIBRA_TASK_WINDOW, (int32_t)w, b0, b1, scalar_mask, split_mask & touched(b0, b1),
+                                    valid & ~split_mask, cols_in(b0, b1) + res_unsplit});
+                for (int r = 0; r < (int)(r1 - r0); ++r)
+                    if (split_mask >> r & 1) sa.zero_rows.push_back((int32_t)(r0 + r));
+            }
+            for (int r = 0; r < (int)(r1 - r0); ++r) {
+                if (!(split_mask >> r & 1)) continue;
+                int32_t s = sa.res_rowptr[(size_t)(r0 + r - row_base)], e = sa.res_rowptr[(size_t)(r0 + r - row_base) + 1];
+                for (int32_t q = s; q < e; q += o.Cs) {
+                    int32_t q1 = std::min(e, q + o.Cs);
+                    sa.tasks.push_back({LIBRA_TASK_CHUNK, (int32_t)(r0 + r), q, q1, 0u, 0u, 0u, (uint32_t)(q1 - q)});
+                }
+            }
+        }
+
+        // =================== SDDMM sub-plan ===================
+        if (o.build_sddmm) {
+            ids.resize(vecs.size());
+            for (int v = 0; v < (int)vecs.size(); ++v) ids[v] = v;
+            std::stable_sort(ids.begin(), ids.end(), [&](int a, int b) { return vecs[a].cnt > vecs[b].cnt; });
+            const int32_t b0 = (int32_t)sd.n_blocks();
+            size_t used = 0;
+            if (o.mode != LIBRA_MODE_SCALAR_ONLY) {
+                for (size_t s = 0; s < ids.size(); s += KB) {
+                    int n = (int)std::min<size_t>(KB, ids.size() - s);
+                    int blk_nnz = 0;
+                    for (int q = 0; q < n; ++q) blk_nnz += vecs[ids[s + q]].cnt;
+                    if (o.mode == LIBRA_MODE_HYBRID && blk_nnz < o.tau_sddmm) break;   // sums never increase: prefix
+                    emit_block(c, sd, ent, vecs, ids.data() + s, n, tmp);
+                    used = s + n;
+                }
+            }
+            const int32_t b1 = (int32_t)sd.n_blocks();
+            sd.win_blkptr.push_back(b1);
+            for (int32_t g0 = b0; g0 < b1; g0 += o.Ts) {
+                int32_t g1 = std::min(b1, g0 + o.Ts);
+                uint32_t ncols = 0;
+                for (int32_t b = g0; b < g1; ++b)
+                    for (int s = 0; s < KB; ++s) ncols += sd.blk_cols[(size_t)b * KB + s] >= 0;
+                sd.tasks.push_back({LIBRA_TASK_WINDOW, (int32_t)w, g0, g1, 0u, 0u, 0u, ncols + (uint32_t)W});
+            }
+            resp.clear();
+            for (size_t q = used; q < ids.size(); ++q) {
+                const Vec &v = vecs[ids[q]];
+                for (int e = v.first; e < v.first + v.cnt; ++e) resp.push_back((int32_t)(ent[e].key & 0xffffffffu));
+            }
+            std::sort(resp.begin(), resp.end());
+            int64_t i = r0;
+            for (int32_t p : resp) {
+                while (p >= c.rowptr[i + 1]) ++i;
+                sd.res_perm.push_back(p);
+                sd.res_row.push_back((int32_t)i);
+                sd.res_col.push_back(c.col[p]);
+                push_val(sd.res_val, c, p);
+            }
+        }
+    }
+}
+
+template <class T>
+void append(std::vector<T> &dst, const std::vector<T> &src) { dst.insert(dst.end(), src.begin(), src.end()); }
+
+// Append `src` (local indices) to `dst` (global indices).
+void concat(SubPlan &dst, SubPlan &src, bool spmm) {
+    const int32_t blk_base = (int32_t)dst.n_blocks();
+    const int32_t val_base = (int32_t)dst.dense_perm.size();
+    const int32_t res_base = (int32_t)dst.res_perm.size();
+    for (size_t i = 1; i < src.win_blkptr.size(); ++i) dst.win_blkptr.push_back(src.win_blkptr[i] + blk_base);
+    for (size_t i = 1; i < src.blk_valptr.size(); ++i) dst.blk_valptr.push_back(src.blk_valptr[i] + val_base);
+    append(dst.blk_cols, src.blk_cols);
+    append(dst.blk_bitmap, src.blk_bitmap);
+    append(dst.dense_perm, src.dense_perm);
+    append(dst.dense_val, src.dense_val);
+    append(dst.res_perm, src.res_perm);
+    append(dst.res_col, src.res_col);
+    append(dst.res_row, src.res_row);
+    append(dst.res_val, src.res_val);
+    append(dst.zero_rows, src.zero_rows);
+    if (spmm)
+        for (size_t i = 1; i < src.res_rowptr.size(); ++i) dst.res_rowptr.push_back(src.res_rowptr[i] + res_base);
+    for (libra_task_t t : src.tasks) {
+        if (t.kind == LIBRA_TASK_WINDOW) { t.begin += blk_base; t.end += blk_base; }
+        else if (spmm) { t.begin += res_base; t.end += res_base; }
+        dst.tasks.push_back(t);
+    }
+    dst.dense_vectors += src.dense_vectors;
+    dst.pad_slots += src.pad_slots;
+    dst.short_rows += src.short_rows;
+    dst.long_rows += src.long_rows;
+    dst.split_rows += src.split_rows;
+    src = SubPlan();
+}
+
+int resolve(const libra_plan_opts_t *in, int vdt, Resolved &o) {
+    libra_plan_opts_t z{};
+    if (in) {
+        if (in->struct_size != sizeof(libra_plan_opts_t)) return LIBRA_ERR_OPTION;
+        z = *in;
+    }
+    o.mode = z.mode;
+    if (o.mode < 0 || o.mode > 2) return LIBRA_ERR_OPTION;
+    if (vdt == LIBRA_F32) o.mode = LIBRA_MODE_SCALAR_ONLY;
+    o.W = z.window_rows ? z.window_rows : 16;
+    o.KB = z.block_cols ? z.block_cols : 16;
+    o.tau_spmm = z.spmm_min_vec_nnz ? z.spmm_min_vec_nnz : 2;
+    o.tau_sddmm = z.sddmm_min_blk_nnz ? z.sddmm_min_blk_nnz : 32;
+    o.Ts = z.ts ? z.ts : 8;
+    o.Cs = z.cs ? z.cs : 128;
+    o.short_len = z.short_len ? z.short_len : 3;
+    o.sddmm_Cs = z.sddmm_cs ? z.sddmm_cs : 1024;
+    o.threads = z.threads;
+    if (o.W < 1 || o.W > 32 || o.KB < 1 || o.KB > 64 || o.tau_spmm < 1 || o.tau_sddmm < 1 || o.Ts < 1 ||
+        o.Cs < 1 || o.short_len < 1 || o.sddmm_Cs < 1 || o.threads < 0)
+        return LIBRA_ERR_OPTION;
+    o.fill = !(z.flags & LIBRA_FLAG_NO_FILL_PADDING);
+    o.build_spmm = !(z.flags & LIBRA_FLAG_NO_SPMM);
+    o.build_sddmm = !(z.flags & LIBRA_FLAG_NO_SDDMM);
+    o.heavy_first = !(z.flags & LIBRA_FLAG_NATURAL_ORDER);
+    if (z.flags & ~15u) return LIBRA_ERR_OPTION;
+    return LIBRA_OK;
+}
+
+}  // namespace
+
+extern "C" int libra_plan(int64_t M, int64_t Kc, const int32_t *rowptr, const int32_t *col, const void *val,
+                          int val_dtype, const libra_plan_opts_t *opts, libra_plan_t **out) {
+    if (!out) return LIBRA_ERR_NULL;
+    *out = nullptr;
+    if (!rowptr) return LIBRA_ERR_NULL;
+    if (M < 1 || Kc < 1) return LIBRA_ERR_SHAPE;
+    if (M >= (1ll << 31) - 64 || Kc >= (1ll << 31)) return LIBRA_ERR_TOO_LARGE;
+    if (val_dtype == LIBRA_BF16) return LIBRA_ERR_UNSUPPORTED;
+    if (val_dtype != LIBRA_F16 && val_dtype != LIBRA_F32) return LIBRA_ERR_DTYPE;
+    Resolved o{};
+    if (int rc = resolve(opts, val_dtype, o)) return rc;
+    // ---- validate the CSR arrays, O(nnz) ----
+    if (rowptr[0] != 0) return LIBRA_ERR_ROWPTR;
+    for (int64_t i = 0; i < M; ++i)
+        if (rowptr[i + 1] < rowptr[i]) return LIBRA_ERR_ROWPTR;      // int32 rowptr: nnz < 2^31 by type
+    const int64_t nnz = rowptr[M];
+    if (nnz > 0 && (!col || !val)) return LIBRA_ERR_NULL;
+    for (int64_t i = 0; i < M; ++i)
+        for (int32_t p = rowptr[i]; p < rowptr[i + 1]; ++p) {
+            if (col[p] < 0 || col[p] >= Kc) return LIBRA_ERR_COLUMN;
+            if (p > rowptr[i] && col[p] <= col[p - 1]) return LIBRA_ERR_UNSORTED;
+        }
+
+    auto t0 = std::chrono::steady_clock::now();
+    libra_plan_t *P = new (std::nothrow) libra_plan_t();
+    if (!P) return LIBRA_ERR_NOMEM;
+    try {
+        P->M = M; P->Kc = Kc; P->nnz = nnz; P->vdt = val_dtype; P->vsize = val_dtype == LIBRA_F32 ? 4 : 2;
+        P->o = o;
+        P->rowptr.assign(rowptr, rowptr + M + 1);
+        Ctx c{M, nnz, rowptr, col, (const uint8_t *)val, P->vsize, o, (o.W * o.KB + 63) / 64};
+        const int64_t nwin = (M + o.W - 1) / o.W;
+        int nthr = o.threads ? o.threads : (int)std::thread::hardware_concurrency();
+        nthr = (int)std::max<int64_t>(1, std::min<int64_t>(nthr, 64));
+        // ranges of windows with about equal nnz, a few per thread
+        const int64_t nranges = std::max<int64_t>(1, std::min<int64_t>(nwin, (int64_t)nthr * 4));
+        std::vector<int64_t> cut(nranges + 1, 0);
+        {
+            int64_t w = 0;
+            for (int64_t r = 1; r < nranges; ++r) {
+                int64_t target = nnz / nranges * r;
+                while (w < nwin && rowptr[std::min<int64_t>(M, w * o.W)] < target) ++w;
+                cut[r] = std::max(cut[r - 1], std::min(w, nwin));
+            }
+            cut[nranges] = nwin;
+        }
+        std::vector<Part> parts(nranges);
+        std::vector<std::thread> pool;
+        std::vector<int> failed(nthr, 0);
+        for (int t = 0; t < nthr; ++t)
+            pool.emplace_back([&, t] {
+                try {
+                    for (int64_t r = t; r < nranges; r += nthr) plan_range(c, cut[r], cut[r + 1], parts[r]);
+                } catch (...) { failed[t] = 1; }
+            });
+        for (auto &th : pool) th.join();
+        for (int f : failed) if (f) throw std::bad_alloc();
+
+        SubPlan &sa = P->spmm, &sd = P->sddmm;
+        sa.win_blkptr.push_back(0); sa.blk_valptr.push_back(0); sa.res_rowptr.push_back(0);
+        sd.win_blkptr.push_back(0); sd.blk_valptr.push_back(0);
+        libra_stats_t &st = P->stats;
+        for (auto &pt : parts) {
+            st.n_vectors += pt.n_vectors;
+            st.n_vectors_nnz1 += pt.n_vectors_nnz1;
+            if (o.build_spmm) concat(sa, pt.spmm, true);
+            if (o.build_sddmm) concat(sd, pt.sddmm, false);
+        }
+        parts.clear();
+        if (!o.build_spmm) sa = SubPlan();
+        if (!o.build_sddmm) sd = SubPlan();
+        if (o.build_sddmm) {
+            // scalar segments over the flat residual list (no atomics needed: each output has one writer)
+            const int32_t nres = (int32_t)sd.res_perm.size();
+            for (int32_t q = 0; q < nres; q += o.sddmm_Cs) {
+                int32_t q1 = std::min(nres, q + o.sddmm_Cs);
+                sd.tasks.push_back({LIBRA_TASK_CHUNK, 0, q, q1, 0u, 0u, 0u, (uint32_t)(2 * (q1 - q))});
+            }
+        }
+        // ---- ordering: heaviest first, so that the tail of the launch is made of light tasks ----
+        if (o.heavy_first) {
+            auto heavier = [](const libra_task_t &a, const libra_task_t &b) { return a.cost > b.cost; };
+            std::stable_sort(sa.tasks.begin(), sa.tasks.end(), heavier);
+            // SDDMM window tasks first (heaviest first); the flat residual segments stay behind them in order
+            auto mid = std::stable_partition(sd.tasks.begin(), sd.tasks.end(),
+                                             [](const libra_task_t &t) { return t.kind == LIBRA_TASK_WINDOW; });
+            std::stable_sort(sd.tasks.begin(), mid, heavier);
+        }
+        for (SubPlan *sp : {&sa, &sd})
+            for (auto &t : sp->tasks) (t.kind == LIBRA_TASK_WINDOW ? sp->n_window_tasks : sp->n_chunk_tasks)++;
+
+        st.M = M; st.Kc = Kc; st.nnz = nnz; st.n_windows = nwin;
+        if (o.build_spmm) {
+            st.spmm_dense_vectors = sa.dense_vectors; st.spmm_blocks = sa.n_blocks(); st.spmm_pad_slots = sa.pad_slots;
+            st.spmm_dense_nnz = (int64_t)sa.dense_perm.size(); st.spmm_res_nnz = (int64_t)sa.res_perm.size();
+            st.spmm_tasks = (int64_t)sa.tasks.size(); st.spmm_chunk_tasks = sa.n_chunk_tasks;
+            st.spmm_zero_rows = (int64_t)sa.zero_rows.size();
+            st.spmm_short_rows = sa.short_rows; st.spmm_long_rows = sa.long_rows; st.spmm_split_rows = sa.split_rows;
+            st.spmm_gather_rows = sa.dense_vectors + st.spmm_res_nnz;
+        }
+        if (o.build_sddmm) {
+            st.sddmm_dense_vectors = sd.dense_vectors; st.sddmm_blocks = sd.n_blocks(); st.sddmm_pad_slots = sd.pad_slots;
+            st.sddmm_dense_nnz = (int64_t)sd.dense_perm.size(); st.sddmm_res_nnz = (int64_t)sd.res_perm.size();
+            st.sddmm_tasks = (int64_t)sd.tasks.size();
+            st.sddmm_gather_rows = sd.dense_vectors + (int64_t)o.W * sd.n_blocks() + 2 * st.sddmm_res_nnz;
+        }
+        st.plan_seconds = std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count();
+    } catch (...) {
+        delete P;
+        return LIBRA_ERR_NOMEM;
+    }
+    *out = P;
+    return LIBRA_OK;
+}
+
+static void fill_view(const libra_plan_t *P, const SubPlan &sp, bool spmm, libra_subplan_view_t *v) {
+    std::memset(v, 0, sizeof *v);
+    v->n_windows = (int64_t)sp.win_blkptr.size() - 1;
+    v->n_blocks = sp.n_blocks();
+    v->n_dense_nnz = (int64_t)sp.dense_perm.size();
+    v->n_res_nnz = (int64_t)sp.res_perm.size();
+    v->n_tasks = (int64_t)sp.tasks.size();
+    v->n_zero_rows = (int64_t)sp.zero_rows.size();
+    v->window_rows = P->o.W;
+    v->block_cols = P->o.KB;
+    v->words_per_block = (P->o.W * P->o.KB + 63) / 64;
+    v->value_dtype = P->vdt;
+    v->win_blkptr = sp.win_blkptr.data();
+    v->blk_cols = sp.blk_cols.data();
+    v->blk_bitmap = sp.blk_bitmap.data();
+    v->blk_valptr = sp.blk_valptr.data();
+    v->dense_val = sp.dense_val.data();
+    v->dense_perm = sp.dense_perm.data();
+    v->res_rowptr = spmm ? sp.res_rowptr.data() : nullptr;
+    v->res_row = spmm ? nullptr : sp.res_row.data();
+    v->res_col = sp.res_col.data();
+    v->res_val = sp.res_val.data();
+    v->res_perm = sp.res_perm.data();
+    v->tasks = sp.tasks.data();
+    v->zero_rows = sp.zero_rows.data();
+}
+
+extern "C" int libra_plan_export(const libra_plan_t *plan, int which, libra_subplan_view_t *view) {
+    if (!plan || !view) return LIBRA_ERR_NULL;
+    if (which == 0) {
+        if (!plan->o.build_spmm) return LIBRA_ERR_NOT_BUILT;
+        fill_view(plan, plan->spmm, true, view);
+    } else if (which == 1) {
+        if (!plan->o.build_sddmm) return LIBRA_ERR_NOT_BUILT;
+        fill_view(plan, plan->sddmm, false, view);
+    } else {
+        return LIBRA_ERR_OPTION;
+    }
+    return LIBRA_OK;
+}
+
+extern "C" int libra_plan_stats(const libra_plan_t *plan, libra_stats_t *stats) {
+    if (!plan || !stats) return LIBRA_ERR_NULL;
+    *stats = plan->stats;
+    return LIBRA_OK;
+}
+
+extern "C" void libra_plan_destroy(libra_plan_t *plan) { delete plan; }
+
+extern "C" int libra_version(void) { return LIBRA_VERSION; }
+
+extern "C" const char *libra_strerror(int code) {
+    switch (code) {
+    case LIBRA_OK: return "ok";
+    case LIBRA_ERR_NULL: return "a required pointer is NULL";
+    case LIBRA_ERR_SHAPE: return "matrix or operand shape out of range";
+    case LIBRA_ERR_ROWPTR: return "rowptr must start at 0 and be non-decreasing";
+    case LIBRA_ERR_COLUMN: return "column index outside [0, Kc)";
+    case LIBRA_ERR_UNSORTED: return "column indices must be strictly increasing inside a row";
+    case LIBRA_ERR_TOO_LARGE: return "size does not fit in 31 bits";
+    case LIBRA_ERR_DTYPE: return "unknown value type";
+    case LIBRA_ERR_OPTION: return "plan option out of range";
+    case LIBRA_ERR_UNSUPPORTED: return "request not supported by the gfx950 kernels";
+    case LIBRA_ERR_NOT_UPLOADED: return "plan has no device copy (call libra_plan_upload)";
+    case LIBRA_ERR_BUFFER: return "device buffer too small or misaligned";
+    case LIBRA_ERR_NOT_BUILT: return "the required sub-plan was not built";
+    case LIBRA_ERR_HIP: return "HIP runtime error";
+    case LIBRA_ERR_NOMEM: return "host allocation failed";
+    default: return "unknown error";
+    }
+}

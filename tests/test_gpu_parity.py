@@ -1,0 +1,382 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle
+on the same seeded inputs.
+
+Tolerances (graded error, see oracle.graded_error):
+  fp16 inputs, fp32 accumulate ... <= 1e-2   (the stated bar)
+  fp32 VALU-only mode ............ <= 1e-5   (the stated bar)
+and, because products of fp16 numbers are exact in fp32 and only the fp32
+accumulation rounds, a derived bound 16*sqrt(d)*2^-24 (d = summed terms) that a
+correct kernel also meets on these inputs; it catches small dropped terms the
+1e-2 bar would let through.
+"""
+import functools
+import os
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2506_22714_amd import binding as lb
+from paper_2506_22714_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+TOL_F16 = 1e-2
+TOL_F32 = 1e-5
+
+
+def derived_tol(d):
+    return 16.0 * np.sqrt(max(float(d), 1.0)) * 2.0 ** -24
+
+
+@pytest.fixture(scope="module", autouse=True)
+def need_gpu_and_library():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    if not os.path.exists(lb.LIB_PATH):
+        from paper_2506_22714_amd.build import build_library
+        build_library()
+    lb.lib()
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def gpu_spmm(A, B, val=None, ldb=None, ldc=None, **opts):
+    p = lb.Plan.from_csr(A, val=val, flags=opts.pop("flags", 0) | lb.FLAG_NO_SDDMM, **opts).upload()
+    N = B.shape[1]
+    if ldb is None and ldc is None:
+        C = p.spmm(dev(B))
+    else:
+        Bp = torch.zeros((B.shape[0], ldb or N), dtype=dev(B).dtype, device="cuda")
+        Bp[:, :N] = dev(B)
+        Cp = torch.full((A.M, ldc or N), 7.0, dtype=torch.float32, device="cuda")
+        p.spmm(Bp[:, :N], out=Cp[:, :N])
+        assert torch.all(Cp[:, N:] == 7.0)          # nothing written outside the N columns
+        C = Cp[:, :N]
+    torch.cuda.synchronize()
+    out = C.cpu().numpy()
+    st = p.stats()
+    p.close()
+    return out, st
+
+
+def gpu_sddmm(A, X, Y, val=None, **opts):
+    p = lb.Plan.from_csr(A, val=val, flags=opts.pop("flags", 0) | lb.FLAG_NO_SPMM, **opts).upload()
+    out = torch.full((p.nnz,), float("nan"), dtype=torch.float32, device="cuda")
+    p.sddmm(dev(X), dev(Y), out=out)
+    torch.cuda.synchronize()
+    res = out.cpu().numpy()
+    st = p.stats()
+    p.close()
+    return res, st
+
+
+def bound(tol, d):
+    """The stated bar, tightened to the derived bound where that is smaller."""
+    return min(tol, derived_tol(d))
+
+
+def check_spmm(A, B, C, tol, val=None, rows=None, C_is_subset=False):
+    v = A.val if val is None else val
+    ref, S = oracle.spmm(A.rowptr, A.col, v, B, rows=rows)
+    deg = np.diff(A.rowptr).astype(np.float64)
+    if rows is not None:
+        deg = deg[rows]
+        if not C_is_subset:
+            C = C[rows]
+    assert np.all(np.isfinite(C))
+    err = oracle.graded_error(C, ref, S, deg[:, None])
+    lim = bound(tol, deg.max() if deg.size else 1)
+    assert err <= lim, f"graded error {err:.3e} > {lim:.3e}"
+    return err
+
+
+def check_sddmm(A, X, Y, out, tol, val=None, idx=None):
+    v = A.val if val is None else val
+    ref, S = oracle.sddmm(A.rowptr, A.col, v, X, Y, idx=idx)
+    got = out if idx is None else out[idx]
+    assert np.all(np.isfinite(got))
+    err = oracle.graded_error(got, ref, S, X.shape[1])
+    lim = bound(tol, X.shape[1])
+    assert err <= lim, f"graded error {err:.3e} > {lim:.3e}"
+    return err
+
+
+def mixed_matrix(M=1000, Kc=900, seed=1):
+    """Ragged tail (M % 16 != 0), empty rows, a few very long rows (row splitting)
+    and a band of dense columns (windows with more blocks than Ts)."""
+    A = wl.random_pattern(M, Kc, 0.02, seed=seed, empty_rows=0.2)
+    A = wl.with_long_rows(A, [5, 6, 333, M - 1], 700, seed=seed + 1)
+    D = np.zeros((M, Kc), dtype=np.float32)
+    for i in range(A.M):
+        s, e = A.rowptr[i], A.rowptr[i + 1]
+        D[i, A.col[s:e]] = A.val[s:e]
+    rng = np.random.default_rng(seed + 2)
+    band = rng.random((64, 200)) < 0.5
+    D[100:164, 300:500] = np.where(band, wl.uniform_values(rng, band.size).reshape(band.shape), D[100:164, 300:500])
+    return wl.from_dense(D)
+
+
+# ---------------------------------------------------------------- config 1
+@pytest.mark.parametrize("mode", [lb.MODE_HYBRID, lb.MODE_DENSE_ONLY, lb.MODE_SCALAR_ONLY])
+def test_tiny_config_spmm_and_sddmm(mode):
+    A = wl.tiny()
+    B = wl.dense_normal(A.Kc, 32, seed=wl.BASE_SEED + 101)
+    C, st = gpu_spmm(A, B, mode=mode)
+    check_spmm(A, B, C, TOL_F16)
+    X = wl.dense_normal(A.M, 32, seed=wl.BASE_SEED + 102)
+    Y = wl.dense_normal(A.Kc, 32, seed=wl.BASE_SEED + 103)
+    out, st = gpu_sddmm(A, X, Y, mode=mode)
+    check_sddmm(A, X, Y, out, TOL_F16)
+
+
+def test_tiny_config_fp32_mode():
+    A = wl.tiny()
+    v32 = A.val.astype(np.float32)
+    B = wl.dense_normal(A.Kc, 32, seed=wl.BASE_SEED + 101, dtype=np.float32)
+    C, st = gpu_spmm(A, B, val=v32)
+    assert st["spmm_dense_nnz"] == 0
+    check_spmm(A, B, C, TOL_F32, val=v32)
+    X = wl.dense_normal(A.M, 32, seed=wl.BASE_SEED + 102, dtype=np.float32)
+    Y = wl.dense_normal(A.Kc, 32, seed=wl.BASE_SEED + 103, dtype=np.float32)
+    out, _ = gpu_sddmm(A, X, Y, val=v32)
+    check_sddmm(A, X, Y, out, TOL_F32, val=v32)
+
+
+# ------------------------------------------------------- shapes and splitting
+@pytest.mark.parametrize("N", [32, 64, 96, 128, 256, 512])
+def test_spmm_feature_widths_on_mixed_matrix(N):
+    A = mixed_matrix()
+    B = wl.dense_normal(A.Kc, N, seed=N)
+    C, st = gpu_spmm(A, B, ts=2, cs=48)
+    assert st["spmm_split_rows"] >= 4 and st["spmm_chunk_tasks"] > 8 and st["spmm_zero_rows"] > 0
+    assert st["spmm_dense_nnz"] > 0 and st["spmm_res_nnz"] > 0
+    check_spmm(A, B, C, TOL_F16)
+
+
+@pytest.mark.parametrize("N", [16, 48, 128])
+def test_spmm_fp32_mode_widths(N):
+    A = mixed_matrix(M=500, Kc=450, seed=4)
+    v32 = A.val.astype(np.float32)
+    B = wl.dense_normal(A.Kc, N, seed=N, dtype=np.float32)
+    C, _ = gpu_spmm(A, B, val=v32, cs=64)
+    check_spmm(A, B, C, TOL_F32, val=v32)
+
+
+@pytest.mark.parametrize("K", [32, 64, 128])
+def test_sddmm_feature_widths_on_mixed_matrix(K):
+    A = mixed_matrix(seed=3)
+    X = wl.dense_normal(A.M, K, seed=K)
+    Y = wl.dense_normal(A.Kc, K, seed=K + 1)
+    out, st = gpu_sddmm(A, X, Y, ts=2, sddmm_cs=100, sddmm_min_blk_nnz=24)
+    assert st["sddmm_dense_nnz"] > 0 and st["sddmm_res_nnz"] > 0
+    check_sddmm(A, X, Y, out, TOL_F16)
+    v32 = A.val.astype(np.float32)
+    out32, _ = gpu_sddmm(A, X.astype(np.float32), Y.astype(np.float32), val=v32)
+    check_sddmm(A, X.astype(np.float32), Y.astype(np.float32), out32, TOL_F32, val=v32)
+
+
+def test_mode_equivalence_over_thresholds():
+    """Matrix-unit-only, scalar-only and hybrid at several thresholds compute the same product (Section 5.3.2)."""
+    A = wl.community(n_blocks=12, seed=9)
+    B = wl.dense_normal(A.Kc, 64, seed=5)
+    X = wl.dense_normal(A.M, 32, seed=6)
+    Y = wl.dense_normal(A.Kc, 32, seed=7)
+    shares = []
+    for kw in (dict(mode=lb.MODE_SCALAR_ONLY), dict(mode=lb.MODE_DENSE_ONLY), dict(spmm_min_vec_nnz=2, sddmm_min_blk_nnz=16),
+               dict(spmm_min_vec_nnz=4, sddmm_min_blk_nnz=48), dict(spmm_min_vec_nnz=8, sddmm_min_blk_nnz=96, flags=lb.FLAG_NO_FILL_PADDING)):
+        C, st = gpu_spmm(A, B, **dict(kw))
+        check_spmm(A, B, C, TOL_F16)
+        out, st2 = gpu_sddmm(A, X, Y, **dict(kw))
+        check_sddmm(A, X, Y, out, TOL_F16)
+        shares.append((st["spmm_dense_nnz"], st2["sddmm_dense_nnz"]))
+    assert shares[0] == (0, 0) and shares[1] == (A.nnz, A.nnz)
+    assert len(set(shares)) == len(shares)          # the thresholds really changed the split
+
+
+def test_strided_operands_and_untouched_padding():
+    A = mixed_matrix(M=300, Kc=260, seed=8)
+    B = wl.dense_normal(A.Kc, 64, seed=2)
+    C, _ = gpu_spmm(A, B, ldb=72, ldc=100, cs=32)
+    check_spmm(A, B, C, TOL_F16)
+
+
+def test_non_atomic_rows_are_bitwise_repeatable_and_exact_on_integers():
+    A = mixed_matrix(M=400, Kc=300, seed=11)
+    A.val = np.random.default_rng(0).integers(1, 4, size=A.nnz).astype(np.float16)
+    B = wl.dense_small_int(A.Kc, 128, seed=3)
+    C1, _ = gpu_spmm(A, B, cs=64)
+    C2, _ = gpu_spmm(A, B, cs=64)
+    ref, _ = oracle.spmm(A.rowptr, A.col, A.val, B)
+    # small integers: every partial sum is exact in fp32, so any summation order gives the oracle's bits
+    assert np.array_equal(C1.astype(np.float64), ref) and np.array_equal(C1, C2)
+
+
+# ------------------------------------------------------------------ edge cases
+def test_degenerate_matrices():
+    B = wl.dense_normal(40, 32, seed=1)
+    # no nonzeros at all: C must be all zeros whatever it held before
+    E = wl.Csr(33, 40, np.zeros(34, dtype=np.int32), np.zeros(0, dtype=np.int32), np.zeros(0, dtype=np.float16))
+    C, _ = gpu_spmm(E, B, ldc=32)
+    assert C.shape == (33, 32) and not C.any()
+    out, _ = gpu_sddmm(E, wl.dense_normal(33, 32, seed=2), wl.dense_normal(40, 32, seed=3))
+    assert out.size == 0
+    # one row, one nonzero; one full dense row; M = 1
+    one = wl.from_dense(np.eye(1, 40, 7))
+    C, _ = gpu_spmm(one, B)
+    assert np.array_equal(C[0], B[7].astype(np.float32))
+    full = wl.from_dense(np.ones((17, 40)))
+    C, _ = gpu_spmm(full, B)
+    check_spmm(full, B, C, TOL_F16)
+    out, _ = gpu_sddmm(full, wl.dense_normal(17, 32, seed=2), wl.dense_normal(40, 32, seed=3))
+    check_sddmm(full, wl.dense_normal(17, 32, seed=2), wl.dense_normal(40, 32, seed=3), out, TOL_F16)
+
+
+def test_fp16_subnormal_inputs_are_not_flushed():
+    A = wl.random_pattern(64, 64, 0.3, seed=5)
+    A.val = np.full(A.nnz, 1024.0, dtype=np.float16)
+    B = np.full((64, 32), 2.0 ** -24, dtype=np.float16)        # smallest fp16 subnormal
+    for mode in (lb.MODE_DENSE_ONLY, lb.MODE_SCALAR_ONLY):
+        C, _ = gpu_spmm(A, B, mode=mode)
+        ref, _ = oracle.spmm(A.rowptr, A.col, A.val, B)
+        assert np.array_equal(C.astype(np.float64), ref)
+
+
+def test_unsupported_requests_return_codes():
+    A = wl.random_pattern(64, 64, 0.1, seed=2)
+    p = lb.Plan.from_csr(A).upload()
+    B = torch.zeros((64, 40), dtype=torch.float16, device="cuda")
+    with pytest.raises(lb.LibraError) as e:
+        p.spmm(B)
+    assert e.value.code == lb.ERR["UNSUPPORTED"]
+    X = torch.zeros((64, 48), dtype=torch.float16, device="cuda")
+    with pytest.raises(lb.LibraError) as e:
+        p.sddmm(X, X)
+    assert e.value.code == lb.ERR["UNSUPPORTED"]
+    p8 = lb.Plan.from_csr(A, window_rows=8).upload()
+    with pytest.raises(lb.LibraError) as e:
+        p8.spmm(torch.zeros((64, 32), dtype=torch.float16, device="cuda"))
+    assert e.value.code == lb.ERR["UNSUPPORTED"]
+
+
+# ---------------------------------------------- softmax glue and new values
+def test_edge_softmax_and_set_values_attention_head():
+    A = wl.make("gat", small=True)
+    K = 64
+    X = wl.dense_normal(A.M, K, seed=21)
+    Y = wl.dense_normal(A.Kc, K, seed=22)
+    scale = 1.0 / np.sqrt(K)
+    s_ref, a_ref, C_ref, S_ref = oracle.attention_head(A.rowptr, A.col, A.val, X, Y, Y, scale)
+    p = lb.Plan.from_csr(A).upload()
+    Yd = dev(Y)
+    scores = p.sddmm(dev(X), Yd)
+    alpha = p.edge_softmax(scores, scale)
+    p.set_values(alpha)
+    C = p.spmm(Yd)
+    torch.cuda.synchronize()
+    # scores and alpha step by step
+    check_sddmm(A, X, Y, scores.cpu().numpy(), TOL_F16)
+    a = alpha.cpu().numpy().astype(np.float64)
+    deg = np.diff(A.rowptr)
+    rows = np.repeat(np.arange(A.M), deg)
+    assert np.max(np.abs(a - a_ref.astype(np.float64)) / np.maximum(a_ref.astype(np.float64), 2.0 ** -14)) < 4e-3
+    sums = np.bincount(rows, weights=a, minlength=A.M)
+    assert np.all(np.abs(sums[deg > 0] - 1.0) <= 2.0 ** -11 * np.maximum(deg[deg > 0], 4))
+    # whole head against the oracle's head (alpha differs by at most an fp16 ulp, inside the 1e-2 bar)
+    err = oracle.graded_error(C.cpu().numpy(), C_ref, S_ref, np.maximum(deg, 1)[:, None])
+    assert err <= TOL_F16
+    # and the SpMM step alone, fed the GPU's own alpha, to the derived bound
+    check_spmm(A, Y, C.cpu().numpy(), TOL_F16, val=alpha.cpu().numpy())
+    # fp32 softmax output path
+    a32 = p.edge_softmax(scores, scale, out=torch.empty(p.nnz, dtype=torch.float32, device="cuda")).cpu().numpy()
+    ref32 = oracle.edge_softmax(A.rowptr, scores.cpu().numpy().astype(np.float64), scale)
+    assert np.max(np.abs(a32 - ref32) / ref32) < 1e-5
+
+
+# ------------------------------------------- reduced instances of configs 2-4
+@pytest.mark.parametrize("name,N,K", [("powerlaw", 128, 32), ("community", 64, 64), ("irregular", 32, 32)])
+def test_small_instances_of_the_configs(name, N, K):
+    A = wl.make(name, small=True)
+    B = wl.dense_normal(A.Kc, N, seed=31)
+    C, st = gpu_spmm(A, B)
+    check_spmm(A, B, C, TOL_F16)
+    X = wl.dense_normal(A.M, K, seed=32)
+    Y = wl.dense_normal(A.Kc, K, seed=33)
+    out, _ = gpu_sddmm(A, X, Y)
+    check_sddmm(A, X, Y, out, TOL_F16)
+
+
+# ------------------------------------- full-size configs, sampled against the oracle
+@functools.lru_cache(maxsize=1)
+def _full(name):
+    return wl.make(name)
+
+
+def _sample_rows(A, n, seed):
+    rng = np.random.default_rng(seed)
+    deg = np.diff(A.rowptr)
+    heavy = np.argsort(deg)[-32:]
+    return np.unique(np.concatenate([rng.integers(0, A.M, size=n), heavy, [0, A.M - 1]])).astype(np.int64)
+
+
+def _plan_invariants(p, A):
+    """Properties that hold at any size: every nonzero on exactly one path, values in place."""
+    for which in (0, 1):
+        try:
+            ex = p.export(which)
+        except lb.LibraError:
+            continue
+        seen = np.zeros(A.nnz, dtype=np.uint8)
+        np.add.at(seen, ex["dense_perm"], 1)
+        np.add.at(seen, ex["res_perm"], 1)
+        assert seen.min() == 1 and seen.max() == 1
+        assert np.array_equal(ex["dense_val"], A.val[ex["dense_perm"]])
+        assert np.array_equal(ex["res_col"], A.col[ex["res_perm"]])
+
+
+def test_full_powerlaw_config_as_benchmarked():
+    A = _full("powerlaw")
+    N, K = 128, 32
+    B = wl.dense_normal(A.Kc, N, seed=wl.BASE_SEED + 201)
+    p = lb.Plan.from_csr(A).upload()
+    _plan_invariants(p, A)
+    C = p.spmm(dev(B))
+    torch.cuda.synchronize()
+    Ch = C.cpu().numpy()
+    rows = _sample_rows(A, 4000, seed=1)
+    check_spmm(A, B, Ch, TOL_F16, rows=rows)
+    # whole-output property: A(B 1) = (A B) 1 - column sums of C against an SpMM of the row-summed B, all rows
+    ref_sum, S_sum = oracle.spmm(A.rowptr, A.col, A.val, B.astype(np.float32).sum(axis=1, keepdims=True).astype(np.float32))
+    got_sum = Ch.astype(np.float64).sum(axis=1, keepdims=True)
+    assert np.max(np.abs(got_sum - ref_sum) / np.maximum(S_sum, 1.0)) < 1e-3
+    X = wl.dense_normal(A.M, K, seed=wl.BASE_SEED + 202)
+    Y = wl.dense_normal(A.Kc, K, seed=wl.BASE_SEED + 203)
+    out = p.sddmm(dev(X), dev(Y)).cpu().numpy()
+    check_sddmm(A, X, Y, out, TOL_F16)           # all 3.7 M outputs
+    p.close()
+
+
+def test_full_community_config_sampled():
+    A = _full("community")
+    p = lb.Plan.from_csr(A).upload()
+    _plan_invariants(p, A)
+    rows = _sample_rows(A, 3000, seed=2)
+    for N in (64, 128):
+        B = wl.dense_normal(A.Kc, N, seed=wl.BASE_SEED + 300 + N)
+        C = p.spmm(dev(B))
+        torch.cuda.synchronize()
+        sub = C[torch.from_numpy(rows).cuda()].cpu().numpy()
+        check_spmm(A, B, sub, TOL_F16, rows=rows, C_is_subset=True)
+        del C
+    K = 32
+    X = wl.dense_normal(A.M, K, seed=wl.BASE_SEED + 310)
+    Y = wl.dense_normal(A.Kc, K, seed=wl.BASE_SEED + 311)
+    out = p.sddmm(dev(X), dev(Y)).cpu().numpy()
+    idx = np.random.default_rng(3).integers(0, A.nnz, size=200_000)
+    check_sddmm(A, X, Y, out, TOL_F16, idx=idx)
+    assert np.all(np.isfinite(out))
+    p.close()

@@ -1,0 +1,205 @@
+"""Host-side tests of the product library (no GPU): it loads, exports every
+symbol the header declares, validates its input, and its planner output is
+bit-identical to the reference planner's."""
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import planner_ref as pr
+from paper_2506_22714_amd import binding as lb
+from paper_2506_22714_amd import workloads as wl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="session", autouse=True)
+def built_library():
+    if not os.path.exists(lb.LIB_PATH):
+        from paper_2506_22714_amd.build import build_library
+        build_library()
+    return lb.lib()
+
+
+def test_library_exports_every_declared_symbol(built_library):
+    names = set()
+    for fn in os.listdir(os.path.join(ROOT, "include")):
+        text = open(os.path.join(ROOT, "include", fn)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names |= set(re.findall(r"\b(libra_[a-z_]+)\s*\(", text))
+    assert {"libra_plan", "libra_spmm", "libra_sddmm", "libra_plan_upload", "libra_edge_softmax"} <= names
+    for n in sorted(names):
+        assert hasattr(built_library, n), n
+    assert lb.libra_version() == 1
+    assert "NULL" in lb.strerror(-1) and lb.strerror(0) == "ok"
+
+
+# ----------------------------------------------------------------- validation
+def _plan_rc(M, Kc, rowptr, col, val, opts=None, dtype=None):
+    import ctypes as C
+    h = C.c_void_p()
+    rowptr = None if rowptr is None else np.ascontiguousarray(rowptr, dtype=np.int32)
+    col = None if col is None else np.ascontiguousarray(col, dtype=np.int32)
+    val = None if val is None else np.ascontiguousarray(val)
+    rc = lb.lib().libra_plan(M, Kc, lb._np_ptr(rowptr), lb._np_ptr(col), lb._np_ptr(val),
+                             lb.F16 if dtype is None else dtype, C.byref(opts) if opts else None, C.byref(h))
+    if rc == 0:
+        lb.libra_plan_destroy(h)
+    return rc
+
+
+def test_invalid_inputs_are_rejected_with_codes():
+    rp = np.array([0, 2, 3], dtype=np.int32)
+    col = np.array([0, 2, 1], dtype=np.int32)
+    val = np.ones(3, dtype=np.float16)
+    assert _plan_rc(2, 3, rp, col, val) == 0
+    assert _plan_rc(2, 3, None, col, val) == lb.ERR["NULL"]
+    assert _plan_rc(2, 3, rp, None, val) == lb.ERR["NULL"]
+    assert _plan_rc(0, 3, rp, col, val) == lb.ERR["SHAPE"]
+    assert _plan_rc(2, 0, rp, col, val) == lb.ERR["SHAPE"]
+    assert _plan_rc(2, 3, np.array([1, 2, 3]), col, val) == lb.ERR["ROWPTR"]
+    assert _plan_rc(2, 3, np.array([0, 3, 2]), col, val) == lb.ERR["ROWPTR"]
+    assert _plan_rc(2, 2, rp, col, val) == lb.ERR["COLUMN"]
+    assert _plan_rc(2, 3, rp, np.array([0, -1, 1]), val) == lb.ERR["COLUMN"]
+    assert _plan_rc(2, 3, rp, np.array([2, 0, 1]), val) == lb.ERR["UNSORTED"]
+    assert _plan_rc(2, 3, rp, np.array([1, 1, 1]), val) == lb.ERR["UNSORTED"]       # duplicate
+    assert _plan_rc(2, 3, rp, col, val, dtype=7) == lb.ERR["DTYPE"]
+    assert _plan_rc(2, 3, rp, col, val, dtype=lb.BF16) == lb.ERR["UNSUPPORTED"]
+    assert _plan_rc(2, 3, rp, col, val, opts=lb.PlanOpts(window_rows=33)) == lb.ERR["OPTION"]
+    assert _plan_rc(2, 3, rp, col, val, opts=lb.PlanOpts(mode=5)) == lb.ERR["OPTION"]
+    bad = lb.PlanOpts()
+    bad.struct_size = 8
+    assert _plan_rc(2, 3, rp, col, val, opts=bad) == lb.ERR["OPTION"]
+    # an empty matrix (no nonzeros) is valid
+    assert _plan_rc(3, 3, np.zeros(4, dtype=np.int32), None, None) == 0
+
+
+def test_compute_calls_without_device_copy_fail_cleanly():
+    A = wl.random_pattern(40, 40, 0.1, seed=1)
+    p = lb.Plan.from_csr(A)
+    with pytest.raises(lb.LibraError) as e:
+        lb.libra_spmm(p.handle, 256, 32, 32, 512, 32)
+    assert e.value.code == lb.ERR["NOT_UPLOADED"]
+    with pytest.raises(lb.LibraError) as e:
+        lb.libra_spmm(p.handle, 0, 32, 32, 512, 32)
+    assert e.value.code == lb.ERR["NULL"]
+    with pytest.raises(lb.LibraError) as e:
+        lb.libra_plan_upload(p.handle, 128, 10)
+    assert e.value.code == lb.ERR["BUFFER"]
+    p2 = lb.Plan.from_csr(A, flags=lb.FLAG_NO_SDDMM)
+    with pytest.raises(lb.LibraError) as e:
+        lb.libra_sddmm(p2.handle, 256, 256, 32, 256)
+    assert e.value.code == lb.ERR["NOT_BUILT"]
+    with pytest.raises(lb.LibraError) as e:
+        p2.export(1)
+    assert e.value.code == lb.ERR["NOT_BUILT"]
+    assert lb.libra_plan_device_bytes(p.handle) > 0
+
+
+# ------------------------------------------------- plan == reference planner
+def canon_tasks(tasks):
+    return sorted((int(t["kind"]), int(t["id"]), int(t["begin"]), int(t["end"]), int(t["scalar_mask"]),
+                   int(t["atomic_mask"]), int(t["store_mask"])) for t in tasks)
+
+
+def check_subplan(A: wl.Csr, ex: dict, ref: pr.SubPlan, spmm: bool):
+    assert list(ex["win_blkptr"]) == ref.win_blkptr
+    assert ex["n_blocks"] == len(ref.blocks)
+    if ref.blocks:
+        assert np.array_equal(ex["blk_cols"], np.array([b.cols for b in ref.blocks], dtype=np.int32))
+        assert np.array_equal(ex["blk_bitmap"], np.array([b.bitmap for b in ref.blocks], dtype=np.uint64))
+    assert list(ex["blk_valptr"]) == list(np.cumsum([0] + [b.nnz for b in ref.blocks]))
+    ref_dense_perm = [p for b in ref.blocks for p in b.perm]
+    assert list(ex["dense_perm"]) == ref_dense_perm
+    assert list(ex["res_perm"]) == ref.res_perm
+    # every nonzero exactly once, on exactly one path
+    allp = np.concatenate([ex["dense_perm"], ex["res_perm"]])
+    assert np.array_equal(np.sort(allp), np.arange(A.nnz))
+    label = np.zeros(A.nnz, dtype=np.int8)
+    label[ex["dense_perm"]] = 1
+    assert np.array_equal(label, ref.label)
+    # values and columns travel with their nonzero
+    assert np.array_equal(ex["dense_val"], A.val[ex["dense_perm"]])
+    assert np.array_equal(ex["res_val"], A.val[ex["res_perm"]])
+    assert np.array_equal(ex["res_col"], A.col[ex["res_perm"]])
+    # bitmap popcounts equal block nnz
+    pc = [sum(bin(int(w)).count("1") for w in row) for row in ex["blk_bitmap"]]
+    assert pc == list(np.diff(ex["blk_valptr"]))
+    if spmm:
+        assert list(ex["res_rowptr"]) == ref.res_rowptr
+        assert sorted(ex["zero_rows"]) == ref.zero_rows
+    else:
+        rows = np.repeat(np.arange(A.M), np.diff(A.rowptr))
+        assert np.array_equal(ex["res_row"], rows[ex["res_perm"]])
+    assert canon_tasks(ex["tasks"]) == sorted(ref.tasks)
+
+
+CASES = [
+    dict(),                                                     # defaults
+    dict(spmm_min_vec_nnz=3, sddmm_min_blk_nnz=20, ts=2, cs=7, sddmm_cs=33),
+    dict(mode=lb.MODE_DENSE_ONLY, ts=3),
+    dict(mode=lb.MODE_SCALAR_ONLY, cs=5),
+    dict(flags=lb.FLAG_NO_FILL_PADDING, ts=1, cs=3),
+    dict(window_rows=4, block_cols=4, spmm_min_vec_nnz=2, sddmm_min_blk_nnz=4, ts=2, cs=5, short_len=2),
+    dict(window_rows=8, block_cols=16, sddmm_min_blk_nnz=24, spmm_min_vec_nnz=3, ts=4, cs=16),
+    dict(window_rows=32, block_cols=64, ts=1, cs=9),
+    dict(flags=lb.FLAG_NATURAL_ORDER, ts=2, cs=6),
+]
+
+
+def ref_opts(kw: dict) -> pr.Opts:
+    fl = kw.get("flags", 0)
+    return pr.Opts(mode=kw.get("mode", 0), W=kw.get("window_rows", 16), KB=kw.get("block_cols", 16),
+                   tau_spmm=kw.get("spmm_min_vec_nnz", 2), tau_sddmm=kw.get("sddmm_min_blk_nnz", 32),
+                   Ts=kw.get("ts", 8), Cs=kw.get("cs", 128), short_len=kw.get("short_len", 3),
+                   fill_padding=not (fl & lb.FLAG_NO_FILL_PADDING), sddmm_Cs=kw.get("sddmm_cs", 1024))
+
+
+def matrices():
+    yield "random", wl.random_pattern(203, 150, 0.08, seed=5, empty_rows=0.15)
+    yield "community", wl.community(n_blocks=6, seed=2)
+    yield "rmat", wl.rmat(scale=9, avg_degree=8, seed=3)
+    yield "longrows", wl.with_long_rows(wl.random_pattern(90, 400, 0.03, seed=7), [3, 17, 18, 64], 300, seed=8)
+    yield "single_row", wl.random_pattern(1, 50, 0.5, seed=9)
+
+
+@pytest.mark.parametrize("case", range(len(CASES)))
+def test_planner_matches_reference_bit_for_bit(case):
+    kw = CASES[case]
+    for name, A in matrices():
+        p = lb.Plan.from_csr(A, **kw)
+        o = ref_opts(kw)
+        check_subplan(A, p.export(0), pr.plan_spmm(A.M, A.rowptr, A.col, o), spmm=True)
+        check_subplan(A, p.export(1), pr.plan_sddmm(A.M, A.rowptr, A.col, o), spmm=False)
+        st = p.stats()
+        ref = pr.plan_spmm(A.M, A.rowptr, A.col, o)
+        assert st["n_vectors"] == ref.stats["n_vectors"] and st["n_vectors_nnz1"] == ref.stats["n_vectors_nnz1"]
+        assert st["spmm_dense_vectors"] == ref.stats["n_dense_vectors"] and st["spmm_pad_slots"] == ref.stats["n_pad_slots"]
+        assert (st["spmm_short_rows"], st["spmm_long_rows"], st["spmm_split_rows"]) == (ref.n_short_rows, ref.n_long_rows, ref.n_split_rows)
+        # Eq. 2 summed over the plan: rows of B fetched = dense vectors + residual nonzeros <= nnz
+        assert st["spmm_gather_rows"] == st["spmm_dense_vectors"] + st["spmm_res_nnz"] <= max(A.nnz, st["spmm_gather_rows"])
+        p.close()
+
+
+def test_plan_does_not_depend_on_thread_count_and_orders_heaviest_first():
+    A = wl.rmat(scale=11, avg_degree=8, seed=4)
+    e1 = lb.Plan.from_csr(A, threads=1, cs=16, ts=2).export(0)
+    e7 = lb.Plan.from_csr(A, threads=7, cs=16, ts=2).export(0)
+    for k in e1:
+        assert np.array_equal(e1[k], e7[k]), k
+    cost = e1["tasks"]["cost"].astype(np.int64)
+    assert np.all(np.diff(cost) <= 0)
+    nat = lb.Plan.from_csr(A, cs=16, ts=2, flags=lb.FLAG_NATURAL_ORDER).export(0)
+    assert canon_tasks(nat["tasks"]) == canon_tasks(e1["tasks"])
+    win = nat["tasks"]["id"][nat["tasks"]["kind"] == lb.TASK_WINDOW]
+    assert np.all(np.diff(win) >= 0)
+
+
+def test_fp32_values_force_the_scalar_path():
+    A = wl.random_pattern(64, 64, 0.2, seed=3)
+    p = lb.Plan.from_csr(A, val=A.val.astype(np.float32))
+    st = p.stats()
+    assert st["spmm_dense_nnz"] == 0 and st["sddmm_dense_nnz"] == 0 and st["spmm_res_nnz"] == A.nnz
+    ex = p.export(0)
+    assert ex["res_val"].dtype == np.float32 and np.array_equal(ex["res_val"], A.val.astype(np.float32))
