@@ -87,7 +87,7 @@ void plan_range(const Ctx &c, int64_t w0, int64_t w1, Part &out) {
     sa.blk_valptr.push_back(0);
     sd.win_blkptr.push_back(0);
     sd.blk_valptr.push_back(0);
-    const int64_t row_base = w0 * W;
+    const int64_t row_base = std::min<int64_t>(c.M, w0 * W);
     const int64_t row_end_all = std::min<int64_t>(c.M, w1 * W);
     if (o.build_spmm) sa.res_rowptr.assign((size_t)(row_end_all - row_base) + 1, 0);
 

@@ -162,13 +162,15 @@ def matrices():
     yield "rmat", wl.rmat(scale=9, avg_degree=8, seed=3)
     yield "longrows", wl.with_long_rows(wl.random_pattern(90, 400, 0.03, seed=7), [3, 17, 18, 64], 300, seed=8)
     yield "single_row", wl.random_pattern(1, 50, 0.5, seed=9)
+    # more window ranges than windows can fill near the tail: M not a multiple of the window height
+    yield "ragged_tail", wl.random_pattern(1000, 300, 0.03, seed=10, empty_rows=0.3)
 
 
 @pytest.mark.parametrize("case", range(len(CASES)))
 def test_planner_matches_reference_bit_for_bit(case):
     kw = CASES[case]
     for name, A in matrices():
-        p = lb.Plan.from_csr(A, **kw)
+        p = lb.Plan.from_csr(A, threads=8, **kw)
         o = ref_opts(kw)
         check_subplan(A, p.export(0), pr.plan_spmm(A.M, A.rowptr, A.col, o), spmm=True)
         check_subplan(A, p.export(1), pr.plan_sddmm(A.M, A.rowptr, A.col, o), spmm=False)
