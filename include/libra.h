@@ -186,7 +186,7 @@ int libra_spmm(const libra_plan_t *plan, const void *B, int32_t N, int64_t ldb,
  * libra_sddmm - out[p] = val[p] * <X[i,:], Y[col[p],:]> for every nonzero p of row i (Section 2.2; Eq. 4).
  *   X    device, M x K row-major, contiguous, plan's value type
  *   Y    device, Kc x K row-major, contiguous, plan's value type
- *   out  device, fp32[nnz] in A's CSR order; fully overwritten
+ *   out  device, fp32[nnz] in A's CSR order; fully overwritten (may be NULL when nnz = 0)
  *   K    32, 64 or 128
  * Errors: NULL, UNSUPPORTED, NOT_UPLOADED, NOT_BUILT, HIP.
  */

@@ -482,7 +482,8 @@ extern "C" int libra_spmm(const libra_plan_t *P, const void *B, int32_t N, int64
 }
 
 extern "C" int libra_sddmm(const libra_plan_t *P, const void *X, const void *Y, int32_t K, float *out, void *stream) {
-    if (!P || !X || !Y || !out) return LIBRA_ERR_NULL;
+    if (!P || !X || !Y) return LIBRA_ERR_NULL;
+    if (!out && P->nnz > 0) return LIBRA_ERR_NULL;           // a matrix without nonzeros has no output
     if (!P->o.build_sddmm) return LIBRA_ERR_NOT_BUILT;
     if (!P->dev_base) return LIBRA_ERR_NOT_UPLOADED;
     if (P->o.W != W || P->o.KB != KB) return LIBRA_ERR_UNSUPPORTED;
@@ -525,7 +526,8 @@ extern "C" int libra_sddmm(const libra_plan_t *P, const void *X, const void *Y, 
 }
 
 extern "C" int libra_edge_softmax(const libra_plan_t *P, const float *scores, float scale, void *vals_out, int out_dtype, void *stream) {
-    if (!P || !scores || !vals_out) return LIBRA_ERR_NULL;
+    if (!P) return LIBRA_ERR_NULL;
+    if ((!scores || !vals_out) && P->nnz > 0) return LIBRA_ERR_NULL;
     if (out_dtype != LIBRA_F16 && out_dtype != LIBRA_F32) return LIBRA_ERR_DTYPE;
     if (!P->dev_base) return LIBRA_ERR_NOT_UPLOADED;
     hipStream_t s = (hipStream_t)stream;
@@ -538,7 +540,8 @@ extern "C" int libra_edge_softmax(const libra_plan_t *P, const float *scores, fl
 }
 
 extern "C" int libra_plan_set_values(libra_plan_t *P, const void *vals, int dtype, void *stream) {
-    if (!P || !vals) return LIBRA_ERR_NULL;
+    if (!P) return LIBRA_ERR_NULL;
+    if (!vals && P->nnz > 0) return LIBRA_ERR_NULL;
     if (dtype != P->vdt) return LIBRA_ERR_DTYPE;
     if (!P->dev_base) return LIBRA_ERR_NOT_UPLOADED;
     hipStream_t s = (hipStream_t)stream;

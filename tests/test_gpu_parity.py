@@ -116,8 +116,9 @@ def mixed_matrix(M=1000, Kc=900, seed=1):
         s, e = A.rowptr[i], A.rowptr[i + 1]
         D[i, A.col[s:e]] = A.val[s:e]
     rng = np.random.default_rng(seed + 2)
-    band = rng.random((64, 200)) < 0.5
-    D[100:164, 300:500] = np.where(band, wl.uniform_values(rng, band.size).reshape(band.shape), D[100:164, 300:500])
+    c0, c1 = Kc // 3, min(Kc, Kc // 3 + 200)
+    band = rng.random((64, c1 - c0)) < 0.5
+    D[100:164, c0:c1] = np.where(band, wl.uniform_values(rng, band.size).reshape(band.shape), D[100:164, c0:c1])
     return wl.from_dense(D)
 
 
