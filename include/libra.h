@@ -91,14 +91,15 @@ typedef struct {
 } libra_plan_opts_t;
 
 /* ---- task table entry (Section 4.3: WindowOffset/RowOffset, CurWindow/CurRow, Atomic) ---- */
-#define LIBRA_TASK_WINDOW 0   /* dense blocks [begin,end) of window `id` plus the residual rows in scalar_mask */
-#define LIBRA_TASK_CHUNK  1   /* SpMM: residual nonzeros [begin,end) of the decomposed row `id`
-                                 SDDMM: residual nonzeros [begin,end) of the flat residual list (id = 0) */
+#define LIBRA_TASK_WINDOW 0   /* dense blocks [blk_begin,blk_end) of window `id` plus residual nonzeros [res_begin,res_end) */
+#define LIBRA_TASK_CHUNK  1   /* SpMM: residual nonzeros [res_begin,res_end) of the decomposed row `id`
+                                 SDDMM: residual nonzeros [res_begin,res_end) of the residual list (id = 0) */
 typedef struct {
     int32_t  kind;
     int32_t  id;
-    int32_t  begin, end;
-    uint32_t scalar_mask;   /* SpMM window task: bit r set = this task adds the residual nonzeros of row id*m + r  */
+    int32_t  blk_begin, blk_end;
+    int32_t  res_begin, res_end;
+    uint32_t scalar_mask;   /* SpMM window task: bit r set = [res_begin,res_end) holds the residual nonzeros of row id*m + r */
     uint32_t atomic_mask;   /* SpMM window task: rows this task adds to C with atomics (they are zero-initialised first) */
     uint32_t store_mask;    /* SpMM window task: rows this task alone owns and writes with plain stores (zeros included) */
     uint32_t cost;          /* modelled rows of the dense operand this task fetches (ordering key) */
@@ -114,11 +115,12 @@ typedef struct {
     const int32_t  *blk_valptr;   /* [n_blocks+1] first packed value of each block                               */
     const void     *dense_val;    /* [n_dense_nnz] packed values in bit order, value_dtype                       */
     const int32_t  *dense_perm;   /* [n_dense_nnz] CSR position of each packed value                             */
-    const int32_t  *res_rowptr;   /* SpMM: [M+1] residual CSR row pointer; SDDMM: NULL                           */
-    const int32_t  *res_row;      /* SDDMM: [n_res_nnz] row of each residual nonzero; SpMM: NULL                 */
+    const int32_t  *win_resptr;   /* SpMM: [n_windows+1] first residual nonzero of each window; SDDMM: NULL      */
+    const int32_t  *res_row;      /* [n_res_nnz] row of each residual nonzero                                    */
     const int32_t  *res_col;      /* [n_res_nnz]                                                                 */
     const void     *res_val;      /* [n_res_nnz] value_dtype                                                     */
-    const int32_t  *res_perm;     /* [n_res_nnz] CSR position, increasing                                        */
+    const int32_t  *res_perm;     /* [n_res_nnz] CSR position.  SDDMM: increasing.  SpMM: window by window, the
+                                     rows that are not decomposed first (row order), then the decomposed rows     */
     const libra_task_t *tasks;    /* [n_tasks] in launch order                                                   */
     const int32_t  *zero_rows;    /* SpMM: [n_zero_rows] rows cleared before the kernel (rows with >1 writer)    */
 } libra_subplan_view_t;

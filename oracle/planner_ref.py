@@ -65,9 +65,11 @@ class SubPlan:
     label: np.ndarray                 # int8 per CSR nonzero: 1 dense path, 0 scalar path
     blocks: list = field(default_factory=list)
     win_blkptr: list = field(default_factory=list)
-    res_perm: list = field(default_factory=list)      # residual nonzeros, CSR order
-    res_rowptr: list = field(default_factory=list)    # SpMM only: residual CSR row pointer
-    tasks: list = field(default_factory=list)         # canonical tuples, see below
+    res_perm: list = field(default_factory=list)      # residual nonzeros (CSR position of each)
+    res_row: list = field(default_factory=list)       # row of each residual nonzero
+    win_resptr: list = field(default_factory=lambda: [0])   # SpMM only: first residual nonzero of each window
+    # (kind, id, blk_begin, blk_end, res_begin, res_end, scalar_mask, atomic_mask, store_mask)
+    tasks: list = field(default_factory=list)
     zero_rows: list = field(default_factory=list)     # SpMM only
     n_short_rows: int = 0
     n_long_rows: int = 0
@@ -133,19 +135,15 @@ def plan_spmm(M, rowptr, col, o: Opts) -> SubPlan:
             if c not in dense_set:
                 for (r, p) in lst:
                     res_by_row[w * W + r].append(p)
-    sp.res_rowptr = [0]
-    for i in range(M):
-        res_by_row[i].sort()
-        sp.res_perm.extend(res_by_row[i])
-        sp.res_rowptr.append(len(sp.res_perm))
-
-    # ---- hybrid load balancing (Section 4.3) ----
+    # ---- hybrid load balancing (Section 4.3) and the residual array ----
+    # Residual nonzeros are stored window by window: first the rows that are not
+    # decomposed (row order, CSR order inside a row), then the decomposed rows.
     zero = set()
     for w in range(nwin):
         b0, b1 = sp.win_blkptr[w], sp.win_blkptr[w + 1]
         nb = b1 - b0
         rows = range(w * W, min(M, (w + 1) * W))
-        rlen = {i: sp.res_rowptr[i + 1] - sp.res_rowptr[i] for i in rows}
+        rlen = {i: len(res_by_row[i]) for i in rows}
         split_rows = set()
         for i in rows:
             r = rlen[i]
@@ -168,6 +166,12 @@ def plan_spmm(M, rowptr, col, o: Opts) -> SubPlan:
                             m |= 1 << ((wd * 64 + bit) // KB)
             return m
 
+        q0 = len(sp.res_perm)
+        for i in rows:
+            if i not in split_rows:
+                sp.res_perm.extend(sorted(res_by_row[i]))
+                sp.res_row.extend([i] * rlen[i])
+        q1 = len(sp.res_perm)
         valid = sum(1 << (i - w * W) for i in rows)
         split_mask = sum(1 << (i - w * W) for i in split_rows)
         scalar_mask = sum(1 << (i - w * W) for i in rows if rlen[i] > 0 and i not in split_rows)
@@ -175,18 +179,22 @@ def plan_spmm(M, rowptr, col, o: Opts) -> SubPlan:
             # decomposed dense part: every segment of the window is atomic
             for g0 in range(b0, b1, o.Ts):
                 g1 = min(b1, g0 + o.Ts)
-                sp.tasks.append((TASK_WINDOW, w, g0, g1, 0, touched(g0, g1), 0))
+                sp.tasks.append((TASK_WINDOW, w, g0, g1, q0, q0, 0, touched(g0, g1), 0))
             if scalar_mask:
-                sp.tasks.append((TASK_WINDOW, w, b1, b1, scalar_mask, scalar_mask, 0))
+                sp.tasks.append((TASK_WINDOW, w, b1, b1, q0, q1, scalar_mask, scalar_mask, 0))
             zero.update(rows)
         else:
             atomic_mask = split_mask & touched(b0, b1)
-            sp.tasks.append((TASK_WINDOW, w, b0, b1, scalar_mask, atomic_mask, valid & ~split_mask))
+            sp.tasks.append((TASK_WINDOW, w, b0, b1, q0, q1, scalar_mask, atomic_mask, valid & ~split_mask))
             zero.update(split_rows)
         for i in sorted(split_rows):
-            s, e = sp.res_rowptr[i], sp.res_rowptr[i + 1]
+            s = len(sp.res_perm)
+            sp.res_perm.extend(sorted(res_by_row[i]))
+            sp.res_row.extend([i] * rlen[i])
+            e = len(sp.res_perm)
             for c0 in range(s, e, o.Cs):
-                sp.tasks.append((TASK_CHUNK, i, c0, min(e, c0 + o.Cs), 0, 0, 0))
+                sp.tasks.append((TASK_CHUNK, i, 0, 0, c0, min(e, c0 + o.Cs), 0, 0, 0))
+        sp.win_resptr.append(len(sp.res_perm))
     sp.zero_rows = sorted(zero)
     dense_nnz = int(sp.label.sum())
     sp.stats = dict(n_windows=nwin, n_vectors=n_vec, n_vectors_nnz1=n_vec1, n_dense_vectors=n_dense_vec,
@@ -225,13 +233,15 @@ def plan_sddmm(M, rowptr, col, o: Opts) -> SubPlan:
             n_pad += KB - len(cols)
         sp.win_blkptr.append(len(sp.blocks))
     sp.res_perm = [int(p) for p in np.flatnonzero(sp.label == 0)]
+    rows_of = np.repeat(np.arange(M), np.diff(np.asarray(rowptr[:M + 1], dtype=np.int64)))
+    sp.res_row = [int(rows_of[p]) for p in sp.res_perm]
     # load balancing: groups of Ts blocks per window; residual list in groups of sddmm_Cs nonzeros
     for w in range(nwin):
         b0, b1 = sp.win_blkptr[w], sp.win_blkptr[w + 1]
         for g0 in range(b0, b1, o.Ts):
-            sp.tasks.append((TASK_WINDOW, w, g0, min(b1, g0 + o.Ts), 0, 0, 0))
+            sp.tasks.append((TASK_WINDOW, w, g0, min(b1, g0 + o.Ts), 0, 0, 0, 0, 0))
     for c0 in range(0, len(sp.res_perm), o.sddmm_Cs):
-        sp.tasks.append((TASK_CHUNK, 0, c0, min(len(sp.res_perm), c0 + o.sddmm_Cs), 0, 0, 0))
+        sp.tasks.append((TASK_CHUNK, 0, 0, 0, c0, min(len(sp.res_perm), c0 + o.sddmm_Cs), 0, 0, 0))
     dense_nnz = int(sp.label.sum())
     sp.stats = dict(n_windows=nwin, n_vectors=n_vec, n_vectors_nnz1=n_vec1, n_dense_vectors=n_dense_vec,
                     n_blocks=len(sp.blocks), n_pad_slots=n_pad, dense_nnz=dense_nnz,

@@ -14,7 +14,8 @@ import os
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "liblibra.so")
+# LIBRA_LIBRARY selects another build of the same library (e.g. an experimental one); default: the in-tree build
+LIB_PATH = os.environ.get("LIBRA_LIBRARY") or os.path.join(_HERE, "liblibra.so")
 
 F16, BF16, F32 = 0, 1, 2
 MODE_HYBRID, MODE_DENSE_ONLY, MODE_SCALAR_ONLY = 0, 1, 2
@@ -43,12 +44,14 @@ class PlanOpts(C.Structure):
 
 
 class Task(C.Structure):
-    _fields_ = [("kind", C.c_int32), ("id", C.c_int32), ("begin", C.c_int32), ("end", C.c_int32),
+    _fields_ = [("kind", C.c_int32), ("id", C.c_int32), ("blk_begin", C.c_int32), ("blk_end", C.c_int32),
+                ("res_begin", C.c_int32), ("res_end", C.c_int32),
                 ("scalar_mask", C.c_uint32), ("atomic_mask", C.c_uint32), ("store_mask", C.c_uint32),
                 ("cost", C.c_uint32)]
 
 
-TASK_DTYPE = np.dtype([("kind", "<i4"), ("id", "<i4"), ("begin", "<i4"), ("end", "<i4"),
+TASK_DTYPE = np.dtype([("kind", "<i4"), ("id", "<i4"), ("blk_begin", "<i4"), ("blk_end", "<i4"),
+                       ("res_begin", "<i4"), ("res_end", "<i4"),
                        ("scalar_mask", "<u4"), ("atomic_mask", "<u4"), ("store_mask", "<u4"), ("cost", "<u4")])
 
 
@@ -59,7 +62,7 @@ class SubplanView(C.Structure):
                 ("value_dtype", C.c_int32),
                 ("win_blkptr", C.c_void_p), ("blk_cols", C.c_void_p), ("blk_bitmap", C.c_void_p),
                 ("blk_valptr", C.c_void_p), ("dense_val", C.c_void_p), ("dense_perm", C.c_void_p),
-                ("res_rowptr", C.c_void_p), ("res_row", C.c_void_p), ("res_col", C.c_void_p),
+                ("win_resptr", C.c_void_p), ("res_row", C.c_void_p), ("res_col", C.c_void_p),
                 ("res_val", C.c_void_p), ("res_perm", C.c_void_p), ("tasks", C.c_void_p),
                 ("zero_rows", C.c_void_p)]
 
@@ -201,16 +204,14 @@ def libra_plan_export(plan, which: int) -> dict:
                blk_valptr=_arr(v.blk_valptr, nb + 1, np.int32),
                dense_val=_arr(v.dense_val, v.n_dense_nnz, vt),
                dense_perm=_arr(v.dense_perm, v.n_dense_nnz, np.int32),
+               res_row=_arr(v.res_row, v.n_res_nnz, np.int32),
                res_col=_arr(v.res_col, v.n_res_nnz, np.int32),
                res_val=_arr(v.res_val, v.n_res_nnz, vt),
                res_perm=_arr(v.res_perm, v.n_res_nnz, np.int32),
                tasks=_arr(v.tasks, v.n_tasks, TASK_DTYPE),
                zero_rows=_arr(v.zero_rows, v.n_zero_rows, np.int32))
-    st = libra_plan_stats(plan)
     if which == 0:
-        out["res_rowptr"] = _arr(v.res_rowptr, st["M"] + 1, np.int32)
-    else:
-        out["res_row"] = _arr(v.res_row, v.n_res_nnz, np.int32)
+        out["win_resptr"] = _arr(v.win_resptr, v.n_windows + 1, np.int32)
     return out
 
 

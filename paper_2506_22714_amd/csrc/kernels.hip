@@ -2,19 +2,25 @@
 //
 // One wavefront (64 lanes) owns one task of the plan's task table.
 //
-//   SpMM window task   dense blocks -> v_mfma_f32_16x16x16_f16 (A tile decoded from the
-//                      block bitmap in registers, gathered B rows transposed through LDS),
-//                      accumulators parked in an LDS C tile; then every row of the window
-//                      is finished on the VALU: tile row + residual nonzeros, one coalesced
-//                      store (or fp32 atomics for rows that have other writers).
-//   SpMM chunk task    a segment of a decomposed long row, VALU, atomics.
-//   SDDMM window task  X window x gathered Y rows on v_mfma_f32_16x16x32_f16 (both operands
-//                      are contiguous along K, so they load straight into MFMA layout),
-//                      sampled through the bitmap, write offsets by popcount.
-//   SDDMM chunk task   per-nonzero dot products on the VALU with a cross-lane reduction.
+//   SpMM task    dense blocks -> v_mfma_f32_16x16x16_f16: the A tile is decoded from the block
+//                bitmap in registers (Section 4.4 of the paper), the gathered B rows are staged
+//                in LDS and read back in MFMA operand layout with ds_read_b64_tr_b16.  The
+//                accumulators are parked in an fp32 LDS tile of the window.  The residual
+//                nonzeros of the task are then cut into equal contiguous runs, one per lane
+//                group; a group keeps a row's partial sum in registers and adds it into the LDS
+//                tile when the row changes.  Finally the tile is written once: plain coalesced
+//                stores for rows this task owns, fp32 atomics for rows with other writers.
+//                A segment of a decomposed long row is the same task with no blocks and one
+//                atomic output row.
+//   SDDMM window task  X window x gathered Y rows on v_mfma_f32_16x16x32_f16 (both operands are
+//                contiguous along K, so they load straight into MFMA layout), sampled through
+//                the bitmap, write offsets by popcount.
+//   SDDMM segment task per-nonzero dot products on the VALU with a cross-lane reduction.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <cstring>
+#include <type_traits>
 #include <vector>
 
 #include "plan_internal.h"
@@ -25,6 +31,7 @@ typedef _Float16 half_t;
 typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
 typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
 typedef float float4_t __attribute__((ext_vector_type(4)));
+typedef short short4_t __attribute__((ext_vector_type(4)));
 
 namespace {
 
@@ -33,187 +40,382 @@ constexpr int W = 16;    // window height the kernels are written for
 constexpr int KB = 16;   // block width the kernels are written for
 
 struct SpmmArgs {
-    const libra_task_t *tasks;
+    const DevTask *tasks;
     const int32_t *blk_cols;
     const uint64_t *blk_bitmap;
     const int32_t *blk_valptr;
     const void *dense_val;
-    const int32_t *res_rowptr;
-    const int32_t *res_col;
-    const void *res_val;
+    const void *res_ent;
     const void *B;
     float *C;
     int64_t ldb, ldc;
-    int64_t M;
 };
 
-// 8 consecutive elements of a dense-operand row, widened to fp32.
-template <class T> struct Row8;
-template <> struct Row8<half_t> {
-    static constexpr int PER_LANE = 8;
-    __device__ static void load(const void *base, int64_t elem_off, float (&f)[8]) {
-        half8_t h = *reinterpret_cast<const half8_t *>(reinterpret_cast<const half_t *>(base) + elem_off);
-#pragma unroll
-        for (int e = 0; e < 8; ++e) f[e] = (float)h[e];
+// Per storage type: how a lane reads its piece of a dense-operand row and a residual entry.
+template <class T> struct Elem;
+template <> struct Elem<half_t> {
+    static constexpr int PER_LANE = 8;                   // 16 bytes
+    typedef uint4 raw_t;
+    typedef ResEnt16 ent_t;
+    __device__ static raw_t load(const void *base, int64_t elem_off) {
+        return *reinterpret_cast<const uint4 *>(reinterpret_cast<const half_t *>(base) + elem_off);
     }
-    __device__ static float val(const void *base, int64_t i) { return (float)reinterpret_cast<const half_t *>(base)[i]; }
-};
-template <> struct Row8<float> {
-    static constexpr int PER_LANE = 4;
-    __device__ static void load(const void *base, int64_t elem_off, float (&f)[8]) {
-        float4_t v = *reinterpret_cast<const float4_t *>(reinterpret_cast<const float *>(base) + elem_off);
+    __device__ static void fma(float v, const raw_t &r, float (&acc)[8]) {
+        half8_t h;
+        __builtin_memcpy(&h, &r, 16);
 #pragma unroll
-        for (int e = 0; e < 4; ++e) f[e] = v[e];
+        for (int e = 0; e < 8; ++e) acc[e] = fmaf(v, (float)h[e], acc[e]);
     }
-    __device__ static float val(const void *base, int64_t i) { return reinterpret_cast<const float *>(base)[i]; }
+    __device__ static float dot(const raw_t &x, const raw_t &y, float s) {
+        half8_t a, b;
+        __builtin_memcpy(&a, &x, 16);
+        __builtin_memcpy(&b, &y, 16);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) s = fmaf((float)a[e], (float)b[e], s);
+        return s;
+    }
+    __device__ static ent_t load_ent(const void *base, int64_t i) {
+        const uint2 u = reinterpret_cast<const uint2 *>(base)[i];
+        ent_t e;
+        e.col = (int32_t)u.x;
+        e.val = (uint16_t)(u.y & 0xffffu);
+        e.row = (uint16_t)(u.y >> 16);
+        return e;
+    }
+    __device__ static float ent_val(const ent_t &e) {
+        half_t h;
+        __builtin_memcpy(&h, &e.val, 2);
+        return (float)h;
+    }
+    // one 8-byte LDS read per entry
+    __device__ static ent_t lds_ent(const ent_t *lds, int i) {
+        const uint2 u = reinterpret_cast<const uint2 *>(lds)[i];
+        ent_t e;
+        e.col = (int32_t)u.x;
+        e.val = (uint16_t)(u.y & 0xffffu);
+        e.row = (uint16_t)(u.y >> 16);
+        return e;
+    }
+    // the lane's 16 bytes of row `col`: one 32x32->64 multiply-add for the address
+    __device__ static raw_t load_row(const void *base, int32_t col, uint32_t ld_bytes, int sub) {
+        const char *p = reinterpret_cast<const char *>(base) + ((uint64_t)(uint32_t)col * ld_bytes + (uint32_t)sub * 16u);
+        return *reinterpret_cast<const uint4 *>(p);
+    }
+    __device__ static float word_val(uint32_t bits) {
+        const uint16_t lo = (uint16_t)bits;
+        half_t h;
+        __builtin_memcpy(&h, &lo, 2);
+        return (float)h;
+    }
 };
+template <> struct Elem<float> {
+    static constexpr int PER_LANE = 4;                   // 16 bytes
+    typedef float4_t raw_t;
+    typedef ResEnt32 ent_t;
+    __device__ static raw_t load(const void *base, int64_t elem_off) {
+        return *reinterpret_cast<const float4_t *>(reinterpret_cast<const float *>(base) + elem_off);
+    }
+    __device__ static void fma(float v, const raw_t &r, float (&acc)[8]) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) acc[e] = fmaf(v, r[e], acc[e]);
+    }
+    __device__ static float dot(const raw_t &x, const raw_t &y, float s) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) s = fmaf(x[e], y[e], s);
+        return s;
+    }
+    __device__ static ent_t load_ent(const void *base, int64_t i) {
+        const float4_t u = reinterpret_cast<const float4_t *>(base)[i];
+        ent_t e;
+        e.col = __float_as_int(u[0]);
+        e.val = u[1];
+        e.row = __float_as_int(u[2]);
+        e.pad = 0;
+        return e;
+    }
+    __device__ static float ent_val(const ent_t &e) { return e.val; }
+    __device__ static ent_t lds_ent(const ent_t *lds, int i) {
+        const float4_t u = reinterpret_cast<const float4_t *>(lds)[i];
+        ent_t e;
+        e.col = __float_as_int(u[0]);
+        e.val = u[1];
+        e.row = __float_as_int(u[2]);
+        e.pad = 0;
+        return e;
+    }
+    __device__ static raw_t load_row(const void *base, int32_t col, uint32_t ld_bytes, int sub) {
+        const char *p = reinterpret_cast<const char *>(base) + ((uint64_t)(uint32_t)col * ld_bytes + (uint32_t)sub * 16u);
+        return *reinterpret_cast<const float4_t *>(p);
+    }
+    __device__ static float word_val(uint32_t bits) { return __uint_as_float(bits); }
+};
+
+__device__ inline void lds_add(float *p, float v) {
+    __hip_atomic_fetch_add(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+}
+__device__ inline void global_add(float *p, float v) {
+    __hip_atomic_fetch_add(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
 
 // ---------------------------------------------------------------------------------------
 // SpMM.  N = feature columns handled by this launch, T = storage type of values and B.
+//
+// A task is latency-bound unless few dependent memory round trips carry many row fetches, so
+// the kernel is organised around round trips: (1) the task record; (2) all the metadata of the
+// task at once - residual entries, block column ids, block bitmaps - staged in LDS; (3..) the
+// B-row fetches in large batches whose addresses come from LDS, never from another global load.
 // ---------------------------------------------------------------------------------------
-template <class T, int N, bool DENSE>
+
+// Orders the LDS accesses of one wavefront (the hardware runs a wave's LDS instructions in order;
+// this only stops the compiler from moving them across the point).
+__device__ inline void wave_sync() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+template <class T, int N>
 __global__ __launch_bounds__(WAVE) void spmm_task_kernel(SpmmArgs a) {
-    using R = Row8<T>;
-    constexpr int PL = R::PER_LANE;          // elements of a row per lane
+    using E = Elem<T>;
+    typedef typename E::ent_t ent_t;
+    constexpr bool DENSE = std::is_same<T, half_t>::value;
+    constexpr int PL = E::PER_LANE;          // elements of a row per lane
     constexpr int LPR = N / PL;              // lanes per row
-    constexpr int RPW = WAVE / LPR;          // rows per wave pass
+    constexpr int RPW = WAVE / LPR;          // lane groups per wave
     static_assert(LPR >= 1 && LPR <= WAVE && WAVE % LPR == 0, "unsupported N");
-    constexpr int LDC = N + 4;               // fp32 C tile row stride (floats)
-    constexpr int LDB = N + 4;               // fp16 B stage row stride (halves): rows 4 apart land 8 banks apart
-    __shared__ __attribute__((aligned(16))) float lds_c[(DENSE ? W : (RPW < 1 ? 1 : RPW)) * LDC];
-    __shared__ __attribute__((aligned(16))) half_t lds_b[DENSE ? KB * LDB : 8];
+    constexpr int LDC = N + 4;               // fp32 tile row stride (floats)
+    constexpr int BPI = N <= 128 ? 2 : 1;    // dense blocks fetched per round trip
+    constexpr int LDBS = N + 16;             // fp16 stage row stride (halves): 4 consecutive rows cover all 32 banks
+    constexpr int TILE_BYTES = W * LDC * 4;
+    constexpr int STAGE_BYTES = DENSE ? BPI * KB * LDBS * 2 : 0;
+    constexpr int SMEM = TILE_BYTES > STAGE_BYTES ? TILE_BYTES : STAGE_BYTES;
+    constexpr int ECAP = 128;                // residual entries staged per round
+    constexpr int BCAP = 8;                  // dense blocks whose metadata is staged per round
+    constexpr int U = N <= 128 ? 16 : 8;     // B-row fetches in flight per lane group
+    // the B stage (dense phase) and the C tile (afterwards) share the same LDS bytes
+    __shared__ __attribute__((aligned(16))) unsigned char smem[SMEM];
+    __shared__ __attribute__((aligned(16))) ent_t ent_lds[ECAP];
+    __shared__ __attribute__((aligned(16))) float slots[RPW * N];      // one partial row per lane group
+    __shared__ int slot_row[RPW];
+    __shared__ __attribute__((aligned(16))) int32_t cols_lds[DENSE ? BCAP * KB : 4];
+    __shared__ __attribute__((aligned(16))) uint64_t bm_lds[DENSE ? BCAP * 4 : 2];
+    float *tile = reinterpret_cast<float *>(smem);
 
-    const libra_task_t t = a.tasks[blockIdx.x];
+    const DevTask t = a.tasks[blockIdx.x];
     const int lane = threadIdx.x;
-    const int sub = lane % LPR;              // which PL-wide piece of the row
-    const int grp = lane / LPR;              // which row of the pass
+    const int sub = lane % LPR;              // which PL-wide piece of a row
+    const int grp = lane / LPR;              // which lane group
+    const uint32_t atomic_mask = t.masks & 0xffffu, store_mask = t.masks >> 16;
+    const uint32_t out_mask = atomic_mask | store_mask;
+    const int nblk = t.blk_end - t.blk_begin;
+    const int L = t.res_end - t.res_begin;
+    const uint32_t ldb_bytes = (uint32_t)a.ldb * (uint32_t)sizeof(T);
 
-    if (t.kind == LIBRA_TASK_CHUNK) {
-        // ---- a segment of a decomposed long row: groups stride over it, reduce in LDS, atomics ----
-        float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-        for (int p = t.begin + grp; p < t.end; p += RPW) {
-            const int64_t c = a.res_col[p];
-            const float v = R::val(a.res_val, p);
-            float b[8];
-            R::load(a.B, c * a.ldb + sub * PL, b);
+    // ---- round trip 2: all metadata of the task (first round of each kind) ----
+    auto fetch_entries = [&](int e0, int nE) {
+        const ent_t *src = reinterpret_cast<const ent_t *>(a.res_ent) + t.res_begin + e0;
 #pragma unroll
-            for (int e = 0; e < PL; ++e) acc[e] = fmaf(v, b[e], acc[e]);
+        for (int k = 0; k < ECAP; k += WAVE)
+            if (k + lane < nE) ent_lds[k + lane] = src[k + lane];
+    };
+    auto fetch_blocks = [&](int b0, int nb) {
+        if constexpr (DENSE) {
+            const int32_t *csrc = a.blk_cols + (int64_t)(t.blk_begin + b0) * KB;
+#pragma unroll
+            for (int k = 0; k < BCAP * KB; k += WAVE)
+                if (k + lane < nb * KB) cols_lds[k + lane] = csrc[k + lane];
+            if (lane < nb * 4) bm_lds[lane] = a.blk_bitmap[(int64_t)(t.blk_begin + b0) * 4 + lane];
         }
-#pragma unroll
-        for (int e = 0; e < PL; ++e) lds_c[grp * LDC + sub * PL + e] = acc[e];
-        __syncthreads();
-        float *crow = a.C + (int64_t)t.id * a.ldc;
-        for (int f = lane; f < N; f += WAVE) {
-            float s = 0.f;
-#pragma unroll
-            for (int q = 0; q < RPW; ++q) s += lds_c[q * LDC + f];
-            atomicAdd(crow + f, s);
-        }
-        return;
-    }
+    };
+    fetch_entries(0, min(L, ECAP));
+    fetch_blocks(0, min(nblk, BCAP));
+    wave_sync();
 
-    const int w = t.id;
-    bool have_tile = false;
+    bool tile_ready = false;
     if constexpr (DENSE) {
-        if (t.end > t.begin) {
-            have_tile = true;
+        if (nblk > 0) {
+            tile_ready = true;
             constexpr int NT = N / 16;
+            constexpr int PASSES = BPI * KB / RPW;               // wave loads per fetched round
+            static_assert(BPI * KB % RPW == 0 && PASSES >= 1, "stage shape");
+            half_t *stage = reinterpret_cast<half_t *>(smem);
             const int g = lane >> 4, j = lane & 15;
             float4_t acc[NT];
 #pragma unroll
             for (int n = 0; n < NT; ++n) acc[n] = float4_t{0.f, 0.f, 0.f, 0.f};
-            for (int b = t.begin; b < t.end; ++b) {
-                // gather the block's B rows into LDS (padding slots become zero rows)
+            int vbase = t.val_begin;                             // first packed value of the current block
+            for (int b0 = 0; b0 < nblk; b0 += BCAP) {
+                const int nbr = min(BCAP, nblk - b0);
+                if (b0 > 0) {
+                    wave_sync();
+                    fetch_blocks(b0, nbr);
+                    wave_sync();
+                }
+                for (int bb = 0; bb < nbr; bb += BPI) {
+                    const int nb = min(BPI, nbr - bb);
+                    // B rows of up to BPI blocks (padding slots become zero rows)
+                    uint4 raw[PASSES];
 #pragma unroll
-                for (int k0 = 0; k0 < KB; k0 += RPW) {
-                    const int k = k0 + grp;
-                    if (RPW <= KB || k < KB) {
-                        const int c = a.blk_cols[(int64_t)b * KB + k];
-                        uint4 raw = make_uint4(0u, 0u, 0u, 0u);
-                        if (c >= 0)
-                            raw = *reinterpret_cast<const uint4 *>(reinterpret_cast<const half_t *>(a.B) + (int64_t)c * a.ldb + sub * 8);
-                        uint2 *dst = reinterpret_cast<uint2 *>(&lds_b[k * LDB + sub * 8]);
-                        dst[0] = make_uint2(raw.x, raw.y);
-                        dst[1] = make_uint2(raw.z, raw.w);
+                    for (int ps = 0; ps < PASSES; ++ps) {
+                        const int k = ps * RPW + grp;
+                        raw[ps] = make_uint4(0u, 0u, 0u, 0u);
+                        if (k < nb * KB) {
+                            const int c = cols_lds[bb * KB + k];
+                            if (c >= 0) raw[ps] = Elem<half_t>::load_row(a.B, c, ldb_bytes, sub);
+                        }
+                    }
+                    // this lane's 4 A elements (row j, slots 4g..4g+3) of each block, decoded from its bitmap
+                    half4_t af[BPI];
+#pragma unroll
+                    for (int x = 0; x < BPI; ++x) {
+                        af[x] = half4_t{(half_t)0, (half_t)0, (half_t)0, (half_t)0};
+                        if (x < nb) {
+                            const uint64_t *bm = &bm_lds[(bb + x) * 4];
+                            const uint64_t w0 = bm[0], w1 = bm[1], w2 = bm[2], w3 = bm[3];
+                            const int q = j >> 2;
+                            const uint64_t word = q == 0 ? w0 : q == 1 ? w1 : q == 2 ? w2 : w3;
+                            const int c0 = __popcll(w0), c1 = __popcll(w1), c2 = __popcll(w2), c3 = __popcll(w3);
+                            int prefix = (q > 0 ? c0 : 0) + (q > 1 ? c1 : 0) + (q > 2 ? c2 : 0);
+                            const int bitpos = (j & 3) * 16 + 4 * g;
+                            prefix += __popcll(word & ((1ull << bitpos) - 1ull));
+                            const unsigned nib = (unsigned)(word >> bitpos) & 0xFu;
+                            const half_t *vals = reinterpret_cast<const half_t *>(a.dense_val) + vbase + prefix;
+#pragma unroll
+                            for (int e = 0; e < 4; ++e)
+                                if (nib >> e & 1u) af[x][e] = vals[__popc(nib & ((1u << e) - 1u))];
+                            vbase += c0 + c1 + c2 + c3;
+                        }
+                    }
+                    wave_sync();                 // the previous round's operand reads are done
+#pragma unroll
+                    for (int ps = 0; ps < PASSES; ++ps) {
+                        const int k = ps * RPW + grp;
+                        *reinterpret_cast<uint4 *>(&stage[k * LDBS + sub * 8]) = raw[ps];
+                    }
+                    wave_sync();
+#pragma unroll
+                    for (int x = 0; x < BPI; ++x) {
+                        if (x < nb) {
+                            // lane i of a 16-lane block points at row i/4, halves 4(i%4)..+3 of the 32-byte row piece;
+                            // the transposing read hands lane j the four rows' element j: B[4g+e][16n+j], e = 0..3
+                            const half_t *src = &stage[(x * KB + 4 * g + (j >> 2)) * LDBS + 4 * (j & 3)];
+#pragma unroll
+                            for (int n = 0; n < NT; ++n) {
+                                const short4_t r = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                                    (short4_t __attribute__((address_space(3))) *)(src + 16 * n));
+                                half4_t bf;
+                                __builtin_memcpy(&bf, &r, 8);
+                                acc[n] = __builtin_amdgcn_mfma_f32_16x16x16f16(af[x], bf, acc[n], 0, 0, 0);
+                            }
+                        }
                     }
                 }
-                // decode this lane's 4 A elements (row j, slots 4g..4g+3) from the bitmap
-                const uint64_t *bm = a.blk_bitmap + (int64_t)b * 4;
-                const int q = j >> 2;
-                const uint64_t word = bm[q];
-                int prefix = 0;
-                if (q > 0) prefix += __popcll(bm[0]);
-                if (q > 1) prefix += __popcll(bm[1]);
-                if (q > 2) prefix += __popcll(bm[2]);
-                const int bitpos = (j & 3) * 16 + 4 * g;
-                prefix += __popcll(word & ((1ull << bitpos) - 1ull));
-                const unsigned nib = (unsigned)(word >> bitpos) & 0xFu;
-                const half_t *vals = reinterpret_cast<const half_t *>(a.dense_val) + a.blk_valptr[b] + prefix;
-                half4_t af;
-#pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    af[e] = (nib >> e & 1u) ? vals[__popc(nib & ((1u << e) - 1u))] : (half_t)0;
-                __syncthreads();
-#pragma unroll
-                for (int n = 0; n < NT; ++n) {
-                    half4_t bf;
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) bf[e] = lds_b[(4 * g + e) * LDB + 16 * n + j];
-                    acc[n] = __builtin_amdgcn_mfma_f32_16x16x16f16(af, bf, acc[n], 0, 0, 0);
-                }
-                __syncthreads();
             }
+            wave_sync();
             // park the accumulators: lane (g, j) holds rows 4g..4g+3, feature 16n + j
 #pragma unroll
             for (int n = 0; n < NT; ++n)
 #pragma unroll
-                for (int e = 0; e < 4; ++e) lds_c[(4 * g + e) * LDC + 16 * n + j] = acc[n][e];
-            __syncthreads();
+                for (int e = 0; e < 4; ++e) tile[(4 * g + e) * LDC + 16 * n + j] = acc[n][e];
         }
     }
+    constexpr int LPF = N / 4;                                   // lanes per tile row at 4 floats each
+    constexpr int RPP = WAVE / LPF >= 1 ? WAVE / LPF : 1;        // tile rows per wave pass
+    static_assert(LPF <= WAVE, "N too wide for one wave pass");
+    const int rr = lane / LPF, cl = lane % LPF;
+    if (!tile_ready) {
+        // clear the output rows of the tile
+#pragma unroll
+        for (int r0 = 0; r0 < W; r0 += RPP) {
+            const int r = r0 + rr;
+            if (out_mask >> r & 1u) *reinterpret_cast<float4_t *>(&tile[r * LDC + cl * 4]) = float4_t{0.f, 0.f, 0.f, 0.f};
+        }
+    }
+    wave_sync();
 
-    // ---- finish every row of the window on the VALU ----
-    const uint32_t active = t.store_mask | t.atomic_mask;
-    for (int r0 = 0; r0 < W; r0 += RPW) {
-        const int r = r0 + grp;
-        if (r >= W || !(active >> r & 1u)) continue;
-        const int64_t row = (int64_t)w * W + r;
+    // ---- residual nonzeros, ECAP per round: equal contiguous runs per lane group, row sums flushed into the tile ----
+    for (int e0 = 0; e0 < L; e0 += ECAP) {
+        const int nE = min(ECAP, L - e0);
+        if (e0 > 0) {
+            wave_sync();
+            fetch_entries(e0, nE);
+            wave_sync();
+        }
+        const int per = (nE + RPW - 1) / RPW;
+        const int q0 = grp * per;
+        const int q1 = min(nE, q0 + per);
+        // A row is added into the tile by the group that holds its first entry (plain read-add-write:
+        // one owner per row).  A group whose run starts inside a row hands that row's partial sum to
+        // its slot instead; the slots are added afterwards in group order, so the order of additions is fixed.
+        bool first_is_shared = q0 > 0 && q0 < q1 && E::lds_ent(ent_lds, q0 - 1).row == E::lds_ent(ent_lds, q0).row;
+        if (sub == 0) slot_row[grp] = -1;
+        int cur = -1;
         float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-        if (have_tile) {
+        auto flush = [&]() {
+            if (first_is_shared) {
+                first_is_shared = false;
+                if (sub == 0) slot_row[grp] = cur;
 #pragma unroll
-            for (int e = 0; e < PL; ++e) acc[e] = lds_c[r * LDC + sub * PL + e];
-        }
-        if (t.scalar_mask >> r & 1u) {
-            int p = a.res_rowptr[row];
-            const int pe = a.res_rowptr[row + 1];
-            for (; p + 4 <= pe; p += 4) {
-                int64_t c[4];
-                float v[4], b[4][8];
+                for (int e = 0; e < PL; e += 4)
+                    *reinterpret_cast<float4_t *>(&slots[grp * N + sub * PL + e]) = float4_t{acc[e], acc[e + 1], acc[e + 2], acc[e + 3]};
+            } else {
 #pragma unroll
-                for (int u = 0; u < 4; ++u) { c[u] = a.res_col[p + u]; v[u] = R::val(a.res_val, p + u); }
-#pragma unroll
-                for (int u = 0; u < 4; ++u) R::load(a.B, c[u] * a.ldb + sub * PL, b[u]);
-#pragma unroll
-                for (int u = 0; u < 4; ++u)
-#pragma unroll
-                    for (int e = 0; e < PL; ++e) acc[e] = fmaf(v[u], b[u][e], acc[e]);
+                for (int e = 0; e < PL; e += 4) {
+                    float4_t *p = reinterpret_cast<float4_t *>(&tile[cur * LDC + sub * PL + e]);
+                    float4_t v = *p;
+                    v[0] += acc[e]; v[1] += acc[e + 1]; v[2] += acc[e + 2]; v[3] += acc[e + 3];
+                    *p = v;
+                }
             }
-            for (; p < pe; ++p) {
-                const int64_t c = a.res_col[p];
-                const float v = R::val(a.res_val, p);
-                float b[8];
-                R::load(a.B, c * a.ldb + sub * PL, b);
+        };
+        for (int q = q0; q < q1; q += U) {
+            // all entry reads, then all row fetches, back to back; slots past the run repeat its last entry
+            // (their fetch is harmless and their product is never formed)
+            ent_t en[U];
+            typename E::raw_t raw[U];
 #pragma unroll
-                for (int e = 0; e < PL; ++e) acc[e] = fmaf(v, b[e], acc[e]);
+            for (int u = 0; u < U; ++u) en[u] = E::lds_ent(ent_lds, min(q + u, q1 - 1));
+#pragma unroll
+            for (int u = 0; u < U; ++u) raw[u] = E::load_row(a.B, en[u].col, ldb_bytes, sub);
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                if (q + u < q1) {
+                    const int r = (int)en[u].row;
+                    if (r != cur) {
+                        if (cur >= 0) flush();
+#pragma unroll
+                        for (int e = 0; e < PL; ++e) acc[e] = 0.f;
+                        cur = r;
+                    }
+                    E::fma(E::ent_val(en[u]), raw[u], acc);
+                }
             }
         }
-        float *dst = a.C + row * a.ldc + sub * PL;
-        if (t.store_mask >> r & 1u) {
-            *reinterpret_cast<float4_t *>(dst) = float4_t{acc[0], acc[1], acc[2], acc[3]};
-            if (PL == 8) *reinterpret_cast<float4_t *>(dst + 4) = float4_t{acc[4], acc[5], acc[6], acc[7]};
-        } else {
+        if (cur >= 0) flush();
+        wave_sync();
+        for (int gq = 1; gq < RPW; ++gq) {
+            const int r = slot_row[gq];
+            if (r >= 0)
+                for (int f = lane; f < N; f += WAVE) tile[r * LDC + f] += slots[gq * N + f];
+        }
+    }
+    wave_sync();
+
+    // ---- write the tile once: a wave pass covers RPP rows, LPF lanes per row ----
+    {
+        float *cbase = a.C + (int64_t)t.id * W * a.ldc;
 #pragma unroll
-            for (int e = 0; e < PL; ++e) atomicAdd(dst + e, acc[e]);
+        for (int r0 = 0; r0 < W; r0 += RPP) {
+            const int r = r0 + rr;
+            if (!(out_mask >> r & 1u)) continue;
+            float *dst = cbase + (int64_t)r * a.ldc;
+            if (store_mask >> r & 1u) {
+                *reinterpret_cast<float4_t *>(dst + cl * 4) = *reinterpret_cast<const float4_t *>(&tile[r * LDC + cl * 4]);
+            } else {
+                // each atomic instruction covers LPF consecutive floats of the row
+#pragma unroll
+                for (int e = 0; e < 4; ++e) global_add(dst + e * LPF + cl, tile[r * LDC + e * LPF + cl]);
+            }
         }
     }
 }
@@ -232,16 +434,13 @@ __global__ __launch_bounds__(256) void zero_rows_kernel(const int32_t *rows, int
 // SDDMM
 // ---------------------------------------------------------------------------------------
 struct SddmmArgs {
-    const libra_task_t *tasks;
+    const DevTask *tasks;
     const int32_t *blk_cols;
     const uint64_t *blk_bitmap;
     const int32_t *blk_valptr;
     const void *dense_val;
     const int32_t *dense_perm;
-    const int32_t *res_row;
-    const int32_t *res_col;
-    const void *res_val;
-    const int32_t *res_perm;
+    const SdEnt *res_ent;
     const void *X;
     const void *Y;
     float *out;
@@ -251,7 +450,7 @@ struct SddmmArgs {
 template <int K>
 __global__ __launch_bounds__(WAVE) void sddmm_window_kernel(SddmmArgs a) {
     constexpr int KS = K / 32;               // MFMA k-steps
-    const libra_task_t t = a.tasks[blockIdx.x];
+    const DevTask t = a.tasks[blockIdx.x];
     const int lane = threadIdx.x;
     const int g = lane >> 4, j = lane & 15;
     const half_t *X = reinterpret_cast<const half_t *>(a.X);
@@ -262,7 +461,7 @@ __global__ __launch_bounds__(WAVE) void sddmm_window_kernel(SddmmArgs a) {
     half8_t xa[KS];
 #pragma unroll
     for (int s = 0; s < KS; ++s) xa[s] = *reinterpret_cast<const half8_t *>(X + xr * K + 32 * s + 8 * g);
-    for (int b = t.begin; b < t.end; ++b) {
+    for (int b = t.blk_begin; b < t.blk_end; ++b) {
         int c = a.blk_cols[(int64_t)b * KB + j];
         if (c < 0) c = 0;                    // padding slot: no bit is set in its column
         float4_t d = {0.f, 0.f, 0.f, 0.f};
@@ -290,28 +489,44 @@ __global__ __launch_bounds__(WAVE) void sddmm_window_kernel(SddmmArgs a) {
 }
 
 template <class T, int K>
-__global__ __launch_bounds__(WAVE) void sddmm_chunk_kernel(SddmmArgs a) {
-    using R = Row8<T>;
-    constexpr int PL = R::PER_LANE;
+__global__ __launch_bounds__(WAVE) void sddmm_segment_kernel(SddmmArgs a) {
+    using E = Elem<T>;
+    constexpr int PL = E::PER_LANE;
     constexpr int LPN = K / PL;              // lanes per nonzero
     constexpr int NPW = WAVE / LPN;          // nonzeros per wave pass
+    constexpr int U = 4;                     // passes in flight
     static_assert(LPN >= 1 && LPN <= WAVE, "unsupported K");
-    const libra_task_t t = a.tasks[blockIdx.x];
+    const DevTask t = a.tasks[blockIdx.x];
     const int lane = threadIdx.x;
     const int sub = lane % LPN, grp = lane / LPN;
-    for (int q0 = t.begin; q0 < t.end; q0 += NPW) {
-        const int q = q0 + grp;
-        float s = 0.f;
-        if (q < t.end) {
-            float x[8], y[8];
-            R::load(a.X, (int64_t)a.res_row[q] * K + sub * PL, x);
-            R::load(a.Y, (int64_t)a.res_col[q] * K + sub * PL, y);
+    for (int q0 = t.res_begin; q0 < t.res_end; q0 += NPW * U) {
+        SdEnt ent[U];
+        typename E::raw_t x[U], y[U];
 #pragma unroll
-            for (int e = 0; e < PL; ++e) s = fmaf(x[e], y[e], s);
+        for (int u = 0; u < U; ++u) {
+            const int q = q0 + u * NPW + grp;
+            if (q < t.res_end) {
+                const uint4 w = reinterpret_cast<const uint4 *>(a.res_ent)[q];
+                ent[u].row = (int32_t)w.x; ent[u].col = (int32_t)w.y; ent[u].perm = (int32_t)w.z; ent[u].val = w.w;
+            }
         }
 #pragma unroll
-        for (int m = 1; m < LPN; m <<= 1) s += __shfl_xor(s, m, WAVE);
-        if (q < t.end && sub == 0) a.out[a.res_perm[q]] = R::val(a.res_val, q) * s;
+        for (int u = 0; u < U; ++u) {
+            const int q = q0 + u * NPW + grp;
+            if (q < t.res_end) {
+                x[u] = E::load(a.X, (int64_t)ent[u].row * K + sub * PL);
+                y[u] = E::load(a.Y, (int64_t)ent[u].col * K + sub * PL);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int q = q0 + u * NPW + grp;
+            float s = 0.f;
+            if (q < t.res_end) s = E::dot(x[u], y[u], 0.f);
+#pragma unroll
+            for (int m = 1; m < LPN; m <<= 1) s += __shfl_xor(s, m, WAVE);
+            if (q < t.res_end && sub == 0) a.out[ent[u].perm] = E::word_val(ent[u].val) * s;
+        }
     }
 }
 
@@ -348,25 +563,26 @@ __global__ __launch_bounds__(256) void edge_softmax_kernel(const int32_t *rowptr
     }
 }
 
+// dst[i * stride + offset] (as T) = src[perm[i]]: new values into a packed array or into entry records
 template <class T>
-__global__ __launch_bounds__(256) void gather_values_kernel(const T *src, const int32_t *perm, int64_t n, T *dst) {
+__global__ __launch_bounds__(256) void scatter_values_kernel(const T *src, const int32_t *perm, int64_t n, void *dst, int stride, int offset) {
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x)
-        dst[i] = src[perm[i]];
+        *reinterpret_cast<T *>(reinterpret_cast<char *>(dst) + i * stride + offset) = src[perm[i]];
 }
 
 inline int hip_rc(hipError_t e) { return e == hipSuccess ? LIBRA_OK : LIBRA_ERR_HIP; }
 
-template <class T, int N, bool DENSE>
+template <class T, int N>
 int launch_spmm(const SpmmArgs &a, int64_t ntasks, hipStream_t s) {
     if (ntasks == 0) return LIBRA_OK;
-    hipLaunchKernelGGL((spmm_task_kernel<T, N, DENSE>), dim3((unsigned)ntasks), dim3(WAVE), 0, s, a);
+    hipLaunchKernelGGL((spmm_task_kernel<T, N>), dim3((unsigned)ntasks), dim3(WAVE), 0, s, a);
     return hip_rc(hipGetLastError());
 }
 
 int spmm_piece(const libra_plan_t *P, const void *B, int n, int64_t ldb, float *C, int64_t ldc, hipStream_t s) {
     const SubPlan &sp = P->spmm;
     SpmmArgs a{sp.dev.tasks, sp.dev.blk_cols, sp.dev.blk_bitmap, sp.dev.blk_valptr, sp.dev.dense_val,
-               sp.dev.res_rowptr, sp.dev.res_col, sp.dev.res_val, B, C, ldb, ldc, P->M};
+               sp.dev.res_ent, B, C, ldb, ldc};
     if (!sp.zero_rows.empty()) {
         const int64_t total = (int64_t)sp.zero_rows.size() * (n / 4);
         const unsigned blocks = (unsigned)std::min<int64_t>((total + 255) / 256, 65536);
@@ -376,18 +592,18 @@ int spmm_piece(const libra_plan_t *P, const void *B, int n, int64_t ldb, float *
     const int64_t nt = (int64_t)sp.tasks.size();
     if (P->vdt == LIBRA_F16) {
         switch (n) {
-        case 32: return launch_spmm<half_t, 32, true>(a, nt, s);
-        case 64: return launch_spmm<half_t, 64, true>(a, nt, s);
-        case 128: return launch_spmm<half_t, 128, true>(a, nt, s);
-        case 256: return launch_spmm<half_t, 256, true>(a, nt, s);
+        case 32: return launch_spmm<half_t, 32>(a, nt, s);
+        case 64: return launch_spmm<half_t, 64>(a, nt, s);
+        case 128: return launch_spmm<half_t, 128>(a, nt, s);
+        case 256: return launch_spmm<half_t, 256>(a, nt, s);
         }
     } else {
         switch (n) {
-        case 16: return launch_spmm<float, 16, false>(a, nt, s);
-        case 32: return launch_spmm<float, 32, false>(a, nt, s);
-        case 64: return launch_spmm<float, 64, false>(a, nt, s);
-        case 128: return launch_spmm<float, 128, false>(a, nt, s);
-        case 256: return launch_spmm<float, 256, false>(a, nt, s);
+        case 16: return launch_spmm<float, 16>(a, nt, s);
+        case 32: return launch_spmm<float, 32>(a, nt, s);
+        case 64: return launch_spmm<float, 64>(a, nt, s);
+        case 128: return launch_spmm<float, 128>(a, nt, s);
+        case 256: return launch_spmm<float, 256>(a, nt, s);
         }
     }
     return LIBRA_ERR_UNSUPPORTED;
@@ -399,40 +615,107 @@ int spmm_piece(const libra_plan_t *P, const void *B, int n, int64_t ldb, float *
 // C ABI: upload and compute
 // =========================================================================================
 namespace {
-struct Slot { const void *src; size_t bytes; const void **dst; };
-
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
-template <class V> Slot slot(const V &v, const void **dst) { return {v.data(), v.size() * sizeof(v[0]), dst}; }
-
-void collect(libra_plan_t *P, std::vector<Slot> &s) {
-    s.push_back(slot(P->rowptr, (const void **)&P->d_rowptr));
-    for (SubPlan *sp : {&P->spmm, &P->sddmm}) {
-        SubPlanDev &d = sp->dev;
-        s.push_back(slot(sp->tasks, (const void **)&d.tasks));
-        s.push_back(slot(sp->win_blkptr, (const void **)&d.win_blkptr));
-        s.push_back(slot(sp->blk_cols, (const void **)&d.blk_cols));
-        s.push_back(slot(sp->blk_bitmap, (const void **)&d.blk_bitmap));
-        s.push_back(slot(sp->blk_valptr, (const void **)&d.blk_valptr));
-        s.push_back(slot(sp->dense_val, (const void **)&d.dense_val));
-        s.push_back(slot(sp->dense_perm, (const void **)&d.dense_perm));
-        s.push_back(slot(sp->res_rowptr, (const void **)&d.res_rowptr));
-        s.push_back(slot(sp->res_row, (const void **)&d.res_row));
-        s.push_back(slot(sp->res_col, (const void **)&d.res_col));
-        s.push_back(slot(sp->res_val, (const void **)&d.res_val));
-        s.push_back(slot(sp->res_perm, (const void **)&d.res_perm));
-        s.push_back(slot(sp->zero_rows, (const void **)&d.zero_rows));
+// Lays arrays out back to back (256-byte aligned, 16 spare bytes each) and copies them.
+struct Uploader {
+    char *base = nullptr;     // nullptr: size pass only
+    size_t off = 0;
+    hipStream_t s = nullptr;
+    bool ok = true;
+    template <class P>
+    void put(const void *src, size_t bytes, P *&dst) {
+        if (base) {
+            dst = reinterpret_cast<P *>(base + off);
+            if (bytes && hipMemcpyAsync(base + off, src, bytes, hipMemcpyHostToDevice, s) != hipSuccess) ok = false;
+        }
+        off += align256(bytes + 16);
     }
+    template <class V, class P>
+    void putv(const V &v, P *&dst) { put(v.data(), v.size() * sizeof(v[0]), dst); }
+};
+
+std::vector<DevTask> pack_tasks(const libra_plan_t *P, const SubPlan &sp, bool spmm) {
+    std::vector<DevTask> out(sp.tasks.size());
+    for (size_t i = 0; i < sp.tasks.size(); ++i) {
+        const libra_task_t &t = sp.tasks[i];
+        DevTask d{t.id, t.blk_begin, t.blk_end, t.res_begin, t.res_end, (t.atomic_mask & 0xffffu) | (t.store_mask << 16),
+                  (uint32_t)t.kind, t.kind == LIBRA_TASK_WINDOW ? sp.blk_valptr[t.blk_begin] : 0};
+        if (spmm && t.kind == LIBRA_TASK_CHUNK) {
+            // a segment of a decomposed row = a task of the row's window with one atomic output row
+            d.id = t.id / P->o.W;
+            d.blk_begin = d.blk_end = 0;
+            d.masks = 1u << (t.id % P->o.W);
+        }
+        out[i] = d;
+    }
+    return out;
+}
+
+// Host staging of everything the kernels read in packed form; alive until the copies have finished.
+struct Staging {
+    std::vector<DevTask> tasks_a, tasks_d;
+    std::vector<ResEnt16> ent16;
+    std::vector<ResEnt32> ent32;
+    std::vector<SdEnt> sdent;
+};
+
+void layout(libra_plan_t *P, Uploader &u, Staging *st) {
+    u.putv(P->rowptr, P->d_rowptr);
+    SubPlan &sa = P->spmm, &sd = P->sddmm;
+    const bool f16 = P->vdt == LIBRA_F16;
+    // ---- SpMM ----
+    if (st) st->tasks_a = pack_tasks(P, sa, true);
+    u.put(st ? (const void *)st->tasks_a.data() : nullptr, sa.tasks.size() * sizeof(DevTask), sa.dev.tasks);
+    u.putv(sa.blk_cols, sa.dev.blk_cols);
+    u.putv(sa.blk_bitmap, sa.dev.blk_bitmap);
+    u.putv(sa.blk_valptr, sa.dev.blk_valptr);
+    u.putv(sa.dense_val, sa.dev.dense_val);
+    u.putv(sa.dense_perm, sa.dev.dense_perm);
+    const size_t nres = sa.res_perm.size();
+    if (st) {
+        const int Wp = P->o.W;
+        if (f16) {
+            st->ent16.resize(nres);
+            const uint16_t *v = reinterpret_cast<const uint16_t *>(sa.res_val.data());
+            for (size_t i = 0; i < nres; ++i) st->ent16[i] = {sa.res_col[i], v[i], (uint16_t)(sa.res_row[i] % Wp)};
+        } else {
+            st->ent32.resize(nres);
+            const float *v = reinterpret_cast<const float *>(sa.res_val.data());
+            for (size_t i = 0; i < nres; ++i) st->ent32[i] = {sa.res_col[i], v[i], sa.res_row[i] % Wp, 0};
+        }
+    }
+    if (f16) u.put(st ? (const void *)st->ent16.data() : nullptr, nres * sizeof(ResEnt16), sa.dev.res_ent);
+    else u.put(st ? (const void *)st->ent32.data() : nullptr, nres * sizeof(ResEnt32), sa.dev.res_ent);
+    u.putv(sa.res_perm, sa.dev.res_perm);
+    u.putv(sa.zero_rows, sa.dev.zero_rows);
+    // ---- SDDMM ----
+    if (st) st->tasks_d = pack_tasks(P, sd, false);
+    u.put(st ? (const void *)st->tasks_d.data() : nullptr, sd.tasks.size() * sizeof(DevTask), sd.dev.tasks);
+    u.putv(sd.blk_cols, sd.dev.blk_cols);
+    u.putv(sd.blk_bitmap, sd.dev.blk_bitmap);
+    u.putv(sd.blk_valptr, sd.dev.blk_valptr);
+    u.putv(sd.dense_val, sd.dev.dense_val);
+    u.putv(sd.dense_perm, sd.dev.dense_perm);
+    const size_t nrd = sd.res_perm.size();
+    if (st) {
+        st->sdent.resize(nrd);
+        for (size_t i = 0; i < nrd; ++i) {
+            uint32_t bits = 0;
+            std::memcpy(&bits, sd.res_val.data() + i * P->vsize, P->vsize);
+            st->sdent[i] = {sd.res_row[i], sd.res_col[i], sd.res_perm[i], bits};
+        }
+    }
+    u.put(st ? (const void *)st->sdent.data() : nullptr, nrd * sizeof(SdEnt), sd.dev.res_ent);
+    u.putv(sd.res_perm, sd.dev.res_perm);
 }
 }  // namespace
 
 extern "C" int libra_plan_device_bytes(const libra_plan_t *plan, size_t *bytes) {
     if (!plan || !bytes) return LIBRA_ERR_NULL;
-    std::vector<Slot> s;
-    collect(const_cast<libra_plan_t *>(plan), s);
-    size_t total = 256;
-    for (auto &x : s) total += align256(x.bytes + 16);     // 16 spare bytes: vector loads may read past a tail
-    *bytes = total;
+    Uploader u;
+    layout(const_cast<libra_plan_t *>(plan), u, nullptr);
+    *bytes = u.off + 256;
     return LIBRA_OK;
 }
 
@@ -441,17 +724,16 @@ extern "C" int libra_plan_upload(libra_plan_t *plan, void *dev_buf, size_t bytes
     size_t need = 0;
     libra_plan_device_bytes(plan, &need);
     if (bytes < need || ((uintptr_t)dev_buf & 255)) return LIBRA_ERR_BUFFER;
-    hipStream_t s = (hipStream_t)stream;
-    std::vector<Slot> slots;
-    collect(plan, slots);
-    size_t off = 0;
-    for (auto &x : slots) {
-        char *dst = (char *)dev_buf + off;
-        *x.dst = dst;
-        if (x.bytes && hipMemcpyAsync(dst, x.src, x.bytes, hipMemcpyHostToDevice, s) != hipSuccess) return LIBRA_ERR_HIP;
-        off += align256(x.bytes + 16);
+    try {
+        Staging st;
+        Uploader u;
+        u.base = (char *)dev_buf;
+        u.s = (hipStream_t)stream;
+        layout(plan, u, &st);
+        if (hipStreamSynchronize(u.s) != hipSuccess || !u.ok) return LIBRA_ERR_HIP;
+    } catch (...) {
+        return LIBRA_ERR_NOMEM;
     }
-    if (hipStreamSynchronize(s) != hipSuccess) return LIBRA_ERR_HIP;
     plan->dev_base = dev_buf;
     plan->dev_bytes = bytes;
     return LIBRA_OK;
@@ -465,7 +747,7 @@ extern "C" int libra_spmm(const libra_plan_t *P, const void *B, int32_t N, int64
     const int unit = P->vdt == LIBRA_F16 ? 32 : 16;
     if (N < unit || N > 512) return LIBRA_ERR_SHAPE;
     if (N % unit) return LIBRA_ERR_UNSUPPORTED;
-    if (ldb < N || ldc < N) return LIBRA_ERR_SHAPE;
+    if (ldb < N || ldc < N || ldb > (1ll << 30)) return LIBRA_ERR_SHAPE;
     if (ldb % (P->vdt == LIBRA_F16 ? 8 : 4) || ldc % 4) return LIBRA_ERR_UNSUPPORTED;
     if (((uintptr_t)B & 15) || ((uintptr_t)C & 15)) return LIBRA_ERR_BUFFER;
     hipStream_t s = (hipStream_t)stream;
@@ -493,7 +775,7 @@ extern "C" int libra_sddmm(const libra_plan_t *P, const void *X, const void *Y, 
     hipStream_t s = (hipStream_t)stream;
     const SubPlan &sp = P->sddmm;
     SddmmArgs a{sp.dev.tasks, sp.dev.blk_cols, sp.dev.blk_bitmap, sp.dev.blk_valptr, sp.dev.dense_val, sp.dev.dense_perm,
-                sp.dev.res_row, sp.dev.res_col, sp.dev.res_val, sp.dev.res_perm, X, Y, out, P->M};
+                reinterpret_cast<const SdEnt *>(sp.dev.res_ent), X, Y, out, P->M};
     // window tasks come first in the table, residual segments after them
     const int64_t nw = sp.n_window_tasks, nc = sp.n_chunk_tasks;
     if (nw > 0) {
@@ -509,15 +791,15 @@ extern "C" int libra_sddmm(const libra_plan_t *P, const void *X, const void *Y, 
         a.tasks = sp.dev.tasks + nw;
         if (P->vdt == LIBRA_F16) {
             switch (K) {
-            case 32: hipLaunchKernelGGL((sddmm_chunk_kernel<half_t, 32>), dim3((unsigned)nc), dim3(WAVE), 0, s, a); break;
-            case 64: hipLaunchKernelGGL((sddmm_chunk_kernel<half_t, 64>), dim3((unsigned)nc), dim3(WAVE), 0, s, a); break;
-            case 128: hipLaunchKernelGGL((sddmm_chunk_kernel<half_t, 128>), dim3((unsigned)nc), dim3(WAVE), 0, s, a); break;
+            case 32: hipLaunchKernelGGL((sddmm_segment_kernel<half_t, 32>), dim3((unsigned)nc), dim3(WAVE), 0, s, a); break;
+            case 64: hipLaunchKernelGGL((sddmm_segment_kernel<half_t, 64>), dim3((unsigned)nc), dim3(WAVE), 0, s, a); break;
+            case 128: hipLaunchKernelGGL((sddmm_segment_kernel<half_t, 128>), dim3((unsigned)nc), dim3(WAVE), 0, s, a); break;
             }
         } else {
             switch (K) {
-            case 32: hipLaunchKernelGGL((sddmm_chunk_kernel<float, 32>), dim3((unsigned)nc), dim3(WAVE), 0, s, a); break;
-            case 64: hipLaunchKernelGGL((sddmm_chunk_kernel<float, 64>), dim3((unsigned)nc), dim3(WAVE), 0, s, a); break;
-            case 128: hipLaunchKernelGGL((sddmm_chunk_kernel<float, 128>), dim3((unsigned)nc), dim3(WAVE), 0, s, a); break;
+            case 32: hipLaunchKernelGGL((sddmm_segment_kernel<float, 32>), dim3((unsigned)nc), dim3(WAVE), 0, s, a); break;
+            case 64: hipLaunchKernelGGL((sddmm_segment_kernel<float, 64>), dim3((unsigned)nc), dim3(WAVE), 0, s, a); break;
+            case 128: hipLaunchKernelGGL((sddmm_segment_kernel<float, 128>), dim3((unsigned)nc), dim3(WAVE), 0, s, a); break;
             }
         }
         if (hipGetLastError() != hipSuccess) return LIBRA_ERR_HIP;
@@ -545,19 +827,23 @@ extern "C" int libra_plan_set_values(libra_plan_t *P, const void *vals, int dtyp
     if (dtype != P->vdt) return LIBRA_ERR_DTYPE;
     if (!P->dev_base) return LIBRA_ERR_NOT_UPLOADED;
     hipStream_t s = (hipStream_t)stream;
-    for (SubPlan *sp : {&P->spmm, &P->sddmm}) {
-        struct { const int32_t *perm; void *dst; int64_t n; } seg[2] = {
-            {sp->dev.dense_perm, sp->dev.dense_val, (int64_t)sp->dense_perm.size()},
-            {sp->dev.res_perm, sp->dev.res_val, (int64_t)sp->res_perm.size()}};
-        for (auto &g : seg) {
-            if (g.n == 0) continue;
-            const unsigned blocks = (unsigned)std::min<int64_t>((g.n + 255) / 256, 1 << 16);
-            if (dtype == LIBRA_F16)
-                hipLaunchKernelGGL((gather_values_kernel<half_t>), dim3(blocks), dim3(256), 0, s, (const half_t *)vals, g.perm, g.n, (half_t *)g.dst);
-            else
-                hipLaunchKernelGGL((gather_values_kernel<float>), dim3(blocks), dim3(256), 0, s, (const float *)vals, g.perm, g.n, (float *)g.dst);
-            if (hipGetLastError() != hipSuccess) return LIBRA_ERR_HIP;
-        }
+    const bool f16 = dtype == LIBRA_F16;
+    const int vs = P->vsize;
+    struct Seg { const int32_t *perm; void *dst; int64_t n; int stride, offset; };
+    const SubPlan &sa = P->spmm, &sd = P->sddmm;
+    const Seg segs[4] = {
+        {sa.dev.dense_perm, sa.dev.dense_val, (int64_t)sa.dense_perm.size(), vs, 0},
+        {sa.dev.res_perm, sa.dev.res_ent, (int64_t)sa.res_perm.size(), f16 ? (int)sizeof(ResEnt16) : (int)sizeof(ResEnt32), 4},
+        {sd.dev.dense_perm, sd.dev.dense_val, (int64_t)sd.dense_perm.size(), vs, 0},
+        {sd.dev.res_perm, sd.dev.res_ent, (int64_t)sd.res_perm.size(), (int)sizeof(SdEnt), 12}};
+    for (const Seg &g : segs) {
+        if (g.n == 0) continue;
+        const unsigned blocks = (unsigned)std::min<int64_t>((g.n + 255) / 256, 1 << 16);
+        if (f16)
+            hipLaunchKernelGGL((scatter_values_kernel<half_t>), dim3(blocks), dim3(256), 0, s, (const half_t *)vals, g.perm, g.n, g.dst, g.stride, g.offset);
+        else
+            hipLaunchKernelGGL((scatter_values_kernel<float>), dim3(blocks), dim3(256), 0, s, (const float *)vals, g.perm, g.n, g.dst, g.stride, g.offset);
+        if (hipGetLastError() != hipSuccess) return LIBRA_ERR_HIP;
     }
     return LIBRA_OK;
 }

@@ -87,9 +87,7 @@ void plan_range(const Ctx &c, int64_t w0, int64_t w1, Part &out) {
     sa.blk_valptr.push_back(0);
     sd.win_blkptr.push_back(0);
     sd.blk_valptr.push_back(0);
-    const int64_t row_base = std::min<int64_t>(c.M, w0 * W);
-    const int64_t row_end_all = std::min<int64_t>(c.M, w1 * W);
-    if (o.build_spmm) sa.res_rowptr.assign((size_t)(row_end_all - row_base) + 1, 0);
+    sa.win_resptr.push_back(0);
 
     for (int64_t w = w0; w < w1; ++w) {
         const int64_t r0 = w * W, r1 = std::min<int64_t>(c.M, r0 + W);
@@ -136,7 +134,7 @@ void plan_range(const Ctx &c, int64_t w0, int64_t w1, Part &out) {
                                                  (int)std::min<size_t>(KB, ids.size() - s), tmp));
             const int32_t b1 = (int32_t)sa.n_blocks();
             sa.win_blkptr.push_back(b1);
-            // residual nonzeros in CSR order
+            // residual nonzeros of the window in CSR order, and how many each row keeps
             resp.clear();
             for (int v = 0; v < (int)vecs.size(); ++v)
                 if (!is_dense[v])
@@ -149,13 +147,8 @@ void plan_range(const Ctx &c, int64_t w0, int64_t w1, Part &out) {
                 for (int32_t p : resp) {
                     while (p >= c.rowptr[i + 1]) ++i;
                     ++rlen[i - r0];
-                    sa.res_perm.push_back(p);
-                    sa.res_col.push_back(c.col[p]);
-                    push_val(sa.res_val, c, p);
                 }
             }
-            for (int64_t i = r0; i < r1; ++i)
-                sa.res_rowptr[(size_t)(i - row_base) + 1] = sa.res_rowptr[(size_t)(i - row_base)] + rlen[i - r0];
 
             // ---- hybrid load balancing (Section 4.3) ----
             uint32_t valid = 0, split_mask = 0, scalar_mask = 0;
@@ -171,6 +164,21 @@ void plan_range(const Ctx &c, int64_t w0, int64_t w1, Part &out) {
                 if (!(split_mask >> r & 1)) scalar_mask |= 1u << r;
             }
             sa.split_rows += __builtin_popcount(split_mask);
+            // residual array: rows that are not decomposed first (row order), then the decomposed rows
+            auto emit_rows = [&](bool want_split) {
+                int64_t i = r0;
+                for (int32_t p : resp) {
+                    while (p >= c.rowptr[i + 1]) ++i;
+                    if ((bool)(split_mask >> (i - r0) & 1) != want_split) continue;
+                    sa.res_perm.push_back(p);
+                    sa.res_row.push_back((int32_t)i);
+                    sa.res_col.push_back(c.col[p]);
+                    push_val(sa.res_val, c, p);
+                }
+            };
+            const int32_t q0 = (int32_t)sa.res_perm.size();
+            emit_rows(false);
+            const int32_t q1 = (int32_t)sa.res_perm.size();
             auto touched = [&](int32_t g0, int32_t g1) {
                 uint32_t m = 0;
                 for (int32_t b = g0; b < g1; ++b) m |= blk_rowmask[b - b0];
@@ -182,31 +190,34 @@ void plan_range(const Ctx &c, int64_t w0, int64_t w1, Part &out) {
                     for (int s = 0; s < KB; ++s) n += sa.blk_cols[(size_t)b * KB + s] >= 0;
                 return n;
             };
-            uint32_t res_unsplit = 0;
-            for (int r = 0; r < (int)(r1 - r0); ++r)
-                if (scalar_mask >> r & 1) res_unsplit += rlen[r];
             if (b1 - b0 > o.Ts) {
                 for (int32_t g0 = b0; g0 < b1; g0 += o.Ts) {
                     int32_t g1 = std::min(b1, g0 + o.Ts);
-                    sa.tasks.push_back({LIBRA_TASK_WINDOW, (int32_t)w, g0, g1, 0u, touched(g0, g1), 0u, cols_in(g0, g1)});
+                    sa.tasks.push_back({LIBRA_TASK_WINDOW, (int32_t)w, g0, g1, q0, q0, 0u, touched(g0, g1), 0u, cols_in(g0, g1)});
                 }
                 if (scalar_mask)
-                    sa.tasks.push_back({LIBRA_TASK_WINDOW, (int32_t)w, b1, b1, scalar_mask, scalar_mask, 0u, res_unsplit});
+                    sa.tasks.push_back({LIBRA_TASK_WINDOW, (int32_t)w, b1, b1, q0, q1, scalar_mask, scalar_mask, 0u, (uint32_t)(q1 - q0)});
                 for (int64_t i = r0; i < r1; ++i) sa.zero_rows.push_back((int32_t)i);
             } else {
-                sa.tasks.push_back({LIBRA_TASK_WINDOW, (int32_t)w, b0, b1, scalar_mask, split_mask & touched(b0, b1),
-                                    valid & ~split_mask, cols_in(b0, b1) + res_unsplit});
+                sa.tasks.push_back({LIBRA_TASK_WINDOW, (int32_t)w, b0, b1, q0, q1, scalar_mask, split_mask & touched(b0, b1),
+                                    valid & ~split_mask, cols_in(b0, b1) + (uint32_t)(q1 - q0)});
                 for (int r = 0; r < (int)(r1 - r0); ++r)
                     if (split_mask >> r & 1) sa.zero_rows.push_back((int32_t)(r0 + r));
             }
-            for (int r = 0; r < (int)(r1 - r0); ++r) {
-                if (!(split_mask >> r & 1)) continue;
-                int32_t s = sa.res_rowptr[(size_t)(r0 + r - row_base)], e = sa.res_rowptr[(size_t)(r0 + r - row_base) + 1];
-                for (int32_t q = s; q < e; q += o.Cs) {
-                    int32_t q1 = std::min(e, q + o.Cs);
-                    sa.tasks.push_back({LIBRA_TASK_CHUNK, (int32_t)(r0 + r), q, q1, 0u, 0u, 0u, (uint32_t)(q1 - q)});
+            emit_rows(true);
+            {
+                int32_t q = q1;
+                for (int r = 0; r < (int)(r1 - r0); ++r) {
+                    if (!(split_mask >> r & 1)) continue;
+                    const int32_t e = q + rlen[r];
+                    for (; q < e; q += o.Cs) {
+                        int32_t qe = std::min(e, q + o.Cs);
+                        sa.tasks.push_back({LIBRA_TASK_CHUNK, (int32_t)(r0 + r), 0, 0, q, qe, 0u, 0u, 0u, (uint32_t)(qe - q)});
+                    }
+                    q = e;
                 }
             }
+            sa.win_resptr.push_back((int32_t)sa.res_perm.size());
         }
 
         // =================== SDDMM sub-plan ===================
@@ -233,7 +244,7 @@ void plan_range(const Ctx &c, int64_t w0, int64_t w1, Part &out) {
                 uint32_t ncols = 0;
                 for (int32_t b = g0; b < g1; ++b)
                     for (int s = 0; s < KB; ++s) ncols += sd.blk_cols[(size_t)b * KB + s] >= 0;
-                sd.tasks.push_back({LIBRA_TASK_WINDOW, (int32_t)w, g0, g1, 0u, 0u, 0u, ncols + (uint32_t)W});
+                sd.tasks.push_back({LIBRA_TASK_WINDOW, (int32_t)w, g0, g1, 0, 0, 0u, 0u, 0u, ncols + (uint32_t)W});
             }
             resp.clear();
             for (size_t q = used; q < ids.size(); ++q) {
@@ -273,10 +284,10 @@ void concat(SubPlan &dst, SubPlan &src, bool spmm) {
     append(dst.res_val, src.res_val);
     append(dst.zero_rows, src.zero_rows);
     if (spmm)
-        for (size_t i = 1; i < src.res_rowptr.size(); ++i) dst.res_rowptr.push_back(src.res_rowptr[i] + res_base);
+        for (size_t i = 1; i < src.win_resptr.size(); ++i) dst.win_resptr.push_back(src.win_resptr[i] + res_base);
     for (libra_task_t t : src.tasks) {
-        if (t.kind == LIBRA_TASK_WINDOW) { t.begin += blk_base; t.end += blk_base; }
-        else if (spmm) { t.begin += res_base; t.end += res_base; }
+        if (t.kind == LIBRA_TASK_WINDOW) { t.blk_begin += blk_base; t.blk_end += blk_base; }
+        if (spmm) { t.res_begin += res_base; t.res_end += res_base; }
         dst.tasks.push_back(t);
     }
     dst.dense_vectors += src.dense_vectors;
@@ -377,7 +388,7 @@ extern "C" int libra_plan(int64_t M, int64_t Kc, const int32_t *rowptr, const in
         for (int f : failed) if (f) throw std::bad_alloc();
 
         SubPlan &sa = P->spmm, &sd = P->sddmm;
-        sa.win_blkptr.push_back(0); sa.blk_valptr.push_back(0); sa.res_rowptr.push_back(0);
+        sa.win_blkptr.push_back(0); sa.blk_valptr.push_back(0); sa.win_resptr.push_back(0);
         sd.win_blkptr.push_back(0); sd.blk_valptr.push_back(0);
         libra_stats_t &st = P->stats;
         for (auto &pt : parts) {
@@ -394,7 +405,7 @@ extern "C" int libra_plan(int64_t M, int64_t Kc, const int32_t *rowptr, const in
             const int32_t nres = (int32_t)sd.res_perm.size();
             for (int32_t q = 0; q < nres; q += o.sddmm_Cs) {
                 int32_t q1 = std::min(nres, q + o.sddmm_Cs);
-                sd.tasks.push_back({LIBRA_TASK_CHUNK, 0, q, q1, 0u, 0u, 0u, (uint32_t)(2 * (q1 - q))});
+                sd.tasks.push_back({LIBRA_TASK_CHUNK, 0, 0, 0, q, q1, 0u, 0u, 0u, (uint32_t)(2 * (q1 - q))});
             }
         }
         // ---- ordering: heaviest first, so that the tail of the launch is made of light tasks ----
@@ -451,8 +462,8 @@ static void fill_view(const libra_plan_t *P, const SubPlan &sp, bool spmm, libra
     v->blk_valptr = sp.blk_valptr.data();
     v->dense_val = sp.dense_val.data();
     v->dense_perm = sp.dense_perm.data();
-    v->res_rowptr = spmm ? sp.res_rowptr.data() : nullptr;
-    v->res_row = spmm ? nullptr : sp.res_row.data();
+    v->win_resptr = spmm ? sp.win_resptr.data() : nullptr;
+    v->res_row = sp.res_row.data();
     v->res_col = sp.res_col.data();
     v->res_val = sp.res_val.data();
     v->res_perm = sp.res_perm.data();

@@ -9,19 +9,45 @@
 
 namespace libra {
 
+// Task record as the kernels read it (32 bytes).  SpMM: a decomposed-row segment is stored
+// as a window task without blocks whose only output row is the atomic one.
+struct DevTask {
+    int32_t id;                 // window index
+    int32_t blk_begin, blk_end; // dense blocks
+    int32_t res_begin, res_end; // residual entries
+    uint32_t masks;             // SpMM: atomic_mask | store_mask << 16
+    uint32_t kind;
+    int32_t val_begin;          // first packed value of block blk_begin
+};
+
+// Residual entry of the SpMM sub-plan, fp16 values: 8 bytes.
+struct ResEnt16 {
+    int32_t col;
+    uint16_t val;               // IEEE binary16 bits
+    uint16_t row;               // row inside the window
+};
+// Same, fp32 values: 16 bytes.
+struct ResEnt32 {
+    int32_t col;
+    float val;
+    int32_t row;
+    int32_t pad;
+};
+// Residual entry of the SDDMM sub-plan: 16 bytes.
+struct SdEnt {
+    int32_t row, col, perm;
+    uint32_t val;               // fp16 bits in the low half, or fp32 bits
+};
+
 // Device-side pointers of one sub-plan (all inside the caller's buffer).
 struct SubPlanDev {
-    const libra_task_t *tasks = nullptr;
-    const int32_t *win_blkptr = nullptr;
+    const DevTask *tasks = nullptr;
     const int32_t *blk_cols = nullptr;
     const uint64_t *blk_bitmap = nullptr;
     const int32_t *blk_valptr = nullptr;
     void *dense_val = nullptr;
     const int32_t *dense_perm = nullptr;
-    const int32_t *res_rowptr = nullptr;
-    const int32_t *res_row = nullptr;
-    const int32_t *res_col = nullptr;
-    void *res_val = nullptr;
+    void *res_ent = nullptr;            // ResEnt16 / ResEnt32 (SpMM) or SdEnt (SDDMM)
     const int32_t *res_perm = nullptr;
     const int32_t *zero_rows = nullptr;
 };
@@ -30,7 +56,7 @@ struct SubPlan {
     std::vector<int32_t> win_blkptr, blk_cols, blk_valptr, dense_perm;
     std::vector<uint64_t> blk_bitmap;
     std::vector<uint8_t> dense_val, res_val;        // raw bytes, value dtype
-    std::vector<int32_t> res_rowptr, res_row, res_col, res_perm, zero_rows;
+    std::vector<int32_t> win_resptr, res_row, res_col, res_perm, zero_rows;
     std::vector<libra_task_t> tasks;
     int64_t n_window_tasks = 0, n_chunk_tasks = 0;
     int64_t dense_vectors = 0, pad_slots = 0;

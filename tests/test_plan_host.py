@@ -99,8 +99,8 @@ def test_compute_calls_without_device_copy_fail_cleanly():
 
 # ------------------------------------------------- plan == reference planner
 def canon_tasks(tasks):
-    return sorted((int(t["kind"]), int(t["id"]), int(t["begin"]), int(t["end"]), int(t["scalar_mask"]),
-                   int(t["atomic_mask"]), int(t["store_mask"])) for t in tasks)
+    return sorted((int(t["kind"]), int(t["id"]), int(t["blk_begin"]), int(t["blk_end"]), int(t["res_begin"]),
+                   int(t["res_end"]), int(t["scalar_mask"]), int(t["atomic_mask"]), int(t["store_mask"])) for t in tasks)
 
 
 def check_subplan(A: wl.Csr, ex: dict, ref: pr.SubPlan, spmm: bool):
@@ -126,12 +126,13 @@ def check_subplan(A: wl.Csr, ex: dict, ref: pr.SubPlan, spmm: bool):
     # bitmap popcounts equal block nnz
     pc = [sum(bin(int(w)).count("1") for w in row) for row in ex["blk_bitmap"]]
     assert pc == list(np.diff(ex["blk_valptr"]))
+    rows = np.repeat(np.arange(A.M), np.diff(A.rowptr))
+    assert np.array_equal(ex["res_row"], rows[ex["res_perm"]]) and list(ex["res_row"]) == ref.res_row
     if spmm:
-        assert list(ex["res_rowptr"]) == ref.res_rowptr
+        assert list(ex["win_resptr"]) == ref.win_resptr
         assert sorted(ex["zero_rows"]) == ref.zero_rows
     else:
-        rows = np.repeat(np.arange(A.M), np.diff(A.rowptr))
-        assert np.array_equal(ex["res_row"], rows[ex["res_perm"]])
+        assert np.all(np.diff(ex["res_perm"]) > 0)
     assert canon_tasks(ex["tasks"]) == sorted(ref.tasks)
 
 

@@ -129,21 +129,28 @@ def test_spmm_plan_invariants(seed, W, KB, tau, fill):
             assert not below
         else:
             assert len(below) < KB and all(c in blks[-1].cols for c in below)
-    # residual CSR is the scalar-labelled nonzeros in CSR order
-    assert sp.res_perm == list(np.flatnonzero(sp.label == 0))
-    assert sp.res_rowptr[-1] == len(sp.res_perm)
-    # load balancing: sizes respect Ts / Cs and add up
-    for (kind, ident, a, b_, smask, amask, stmask) in sp.tasks:
+    # the residual array is the scalar-labelled nonzeros, each with its row, grouped by window
+    assert sorted(sp.res_perm) == list(np.flatnonzero(sp.label == 0))
+    assert [int(rows[p]) for p in sp.res_perm] == sp.res_row
+    assert sp.win_resptr[-1] == len(sp.res_perm)
+    for w in range(sp.stats["n_windows"]):
+        assert all(r // W == w for r in sp.res_row[sp.win_resptr[w]:sp.win_resptr[w + 1]])
+    # load balancing: sizes respect Ts / Cs, residual ranges tile the residual array exactly once
+    covered = np.zeros(len(sp.res_perm), dtype=int)
+    for (kind, ident, a, b_, q0, q1, smask, amask, stmask) in sp.tasks:
+        covered[q0:q1] += 1
         if kind == pr.TASK_WINDOW:
             assert 0 <= b_ - a <= o.Ts
             assert sp.win_blkptr[ident] <= a and b_ <= sp.win_blkptr[ident + 1]
+            assert {r - ident * W for r in sp.res_row[q0:q1]} == {r for r in range(W) if smask >> r & 1}
+            assert all(q1 - q0 == 0 or sp.res_row[q0:q1].count(ident * W + r) <= o.Cs for r in range(W))
         else:
-            assert 0 < b_ - a <= o.Cs
-            assert sp.res_rowptr[ident] <= a and b_ <= sp.res_rowptr[ident + 1]
+            assert 0 < q1 - q0 <= o.Cs and set(sp.res_row[q0:q1]) == {ident}
+    assert np.all(covered == 1)
     # writers per row: >1 writer => every writer atomic and the row is zero-initialised
     writers = np.zeros(A.M, dtype=int)
     plain = np.zeros(A.M, dtype=int)
-    for (kind, ident, a, b_, smask, amask, stmask) in sp.tasks:
+    for (kind, ident, a, b_, q0, q1, smask, amask, stmask) in sp.tasks:
         if kind == pr.TASK_WINDOW:
             assert amask & stmask == 0
             for r in range(W):
@@ -178,7 +185,7 @@ def test_sddmm_plan_invariants(seed, W, KB, tau):
         for b in blks:
             if -1 not in b.cols:
                 assert b.nnz >= KB                              # a full block holds >= n nonzeros (Section 4.2.1)
-    sizes = [b_ - a for (k, _i, a, b_, *_r) in sp.tasks if k == pr.TASK_CHUNK]
+    sizes = [q1 - q0 for (k, _i, _a, _b, q0, q1, *_r) in sp.tasks if k == pr.TASK_CHUNK]
     assert sum(sizes) == len(sp.res_perm) and all(0 < s <= 50 for s in sizes)
 
 
@@ -211,19 +218,19 @@ def test_three_decomposition_cases():
     # window 0: 2 dense groups (2+1 blocks), 2 chunks of row 1 (5+2); all atomic, nothing plain-stored
     k0 = by_win[0]
     assert sorted(t[3] - t[2] for t in k0 if t[0] == pr.TASK_WINDOW) == [1, 2]
-    assert sorted(t[3] - t[2] for t in k0 if t[0] == pr.TASK_CHUNK) == [2, 5]
-    assert all(t[6] == 0 for t in k0 if t[0] == pr.TASK_WINDOW)
-    assert all(t[5] == 0b0011 for t in k0 if t[0] == pr.TASK_WINDOW)
+    assert sorted(t[5] - t[4] for t in k0 if t[0] == pr.TASK_CHUNK) == [2, 5]
+    assert all(t[8] == 0 for t in k0 if t[0] == pr.TASK_WINDOW)
+    assert all(t[7] == 0b0011 for t in k0 if t[0] == pr.TASK_WINDOW)
     assert {0, 1, 2, 3} <= set(sp.zero_rows)
     # window 1: one window task; row 5 (bit 1) is atomic because its chunks write it too, row 4 is plain
     k1 = by_win[1]
     wt = [t for t in k1 if t[0] == pr.TASK_WINDOW]
-    assert len(wt) == 1 and wt[0][5] == 0b0010 and wt[0][6] == 0b1101
-    assert sorted(t[3] - t[2] for t in k1 if t[0] == pr.TASK_CHUNK) == [1, 5]
+    assert len(wt) == 1 and wt[0][7] == 0b0010 and wt[0][8] == 0b1101
+    assert sorted(t[5] - t[4] for t in k1 if t[0] == pr.TASK_CHUNK) == [1, 5]
     assert 5 in sp.zero_rows and 4 not in sp.zero_rows
     # windows 2 and 3: single task each, no atomics, all rows plain
     for w in (2, 3):
-        assert len(by_win[w]) == 1 and by_win[w][0][5] == 0 and by_win[w][0][6] == 0b1111
+        assert len(by_win[w]) == 1 and by_win[w][0][7] == 0 and by_win[w][0][8] == 0b1111
     assert not ({8, 9, 10, 11, 12, 13, 14, 15} & set(sp.zero_rows))
     assert sp.n_split_rows == 2 and sp.n_short_rows == 2 and sp.n_long_rows == 2
 
