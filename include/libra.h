@@ -85,7 +85,7 @@ typedef struct {
     int32_t  ts;                 /* Ts of Section 4.3: a window's dense part is decomposed iff it has more than ts blocks. default 8 */
     int32_t  cs;                 /* Cs of Section 4.3: a residual row is decomposed iff it has more than cs nonzeros. default 128 */
     int32_t  short_len;          /* Short_len of Section 4.3: a residual row with fewer nonzeros is "short". default 3 */
-    int32_t  sddmm_cs;           /* SDDMM residual nonzeros per scalar segment. default 1024 */
+    int32_t  sddmm_cs;           /* SDDMM residual nonzeros per scalar segment. default 128 */
     uint32_t flags;              /* LIBRA_FLAG_* */
     int32_t  threads;            /* host threads for planning; 0 = hardware concurrency */
 } libra_plan_opts_t;

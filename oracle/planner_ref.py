@@ -48,7 +48,7 @@ class Opts:
     Cs: int = 128
     short_len: int = 3
     fill_padding: bool = True
-    sddmm_Cs: int = 1024
+    sddmm_Cs: int = 128
 
 
 @dataclass

@@ -212,23 +212,49 @@ __global__ __launch_bounds__(WAVE) void spmm_task_kernel(SpmmArgs a) {
     const uint32_t ldb_bytes = (uint32_t)a.ldb * (uint32_t)sizeof(T);
 
     // ---- round trip 2: all metadata of the task (first round of each kind) ----
+    // Loads are issued unconditionally from clamped (always valid) addresses and unused results are
+    // masked afterwards: a load inside a branch makes the compiler wait for all earlier loads first.
+    // First round of each kind of metadata, all loads in flight together, then the LDS writes.
+    {
+        const int nE = min(L, ECAP), nb = min(nblk, BCAP);
+        const ent_t *src = reinterpret_cast<const ent_t *>(a.res_ent) + t.res_begin;
+        ent_t tmp[ECAP / WAVE];
+#pragma unroll
+        for (int k = 0; k < ECAP / WAVE; ++k) tmp[k] = E::load_ent(src, max(min(k * WAVE + lane, nE - 1), 0));
+        if constexpr (DENSE) {
+            const int32_t *csrc = a.blk_cols + (int64_t)t.blk_begin * KB;
+            int32_t c[BCAP * KB / WAVE];
+#pragma unroll
+            for (int k = 0; k < BCAP * KB / WAVE; ++k) c[k] = csrc[max(min(k * WAVE + lane, nb * KB - 1), 0)];
+            const uint64_t w = a.blk_bitmap[(int64_t)t.blk_begin * 4 + max(min(lane, nb * 4 - 1), 0)];
+#pragma unroll
+            for (int k = 0; k < BCAP * KB / WAVE; ++k) cols_lds[k * WAVE + lane] = c[k];
+            if (lane < BCAP * 4) bm_lds[lane] = w;
+        }
+#pragma unroll
+        for (int k = 0; k < ECAP / WAVE; ++k) ent_lds[k * WAVE + lane] = tmp[k];
+    }
+    // later rounds of a task with more than ECAP entries / BCAP blocks are fetched in place
     auto fetch_entries = [&](int e0, int nE) {
         const ent_t *src = reinterpret_cast<const ent_t *>(a.res_ent) + t.res_begin + e0;
+        ent_t tmp[ECAP / WAVE];
 #pragma unroll
-        for (int k = 0; k < ECAP; k += WAVE)
-            if (k + lane < nE) ent_lds[k + lane] = src[k + lane];
+        for (int k = 0; k < ECAP / WAVE; ++k) tmp[k] = E::load_ent(src, min(k * WAVE + lane, nE - 1));
+#pragma unroll
+        for (int k = 0; k < ECAP / WAVE; ++k) ent_lds[k * WAVE + lane] = tmp[k];
     };
     auto fetch_blocks = [&](int b0, int nb) {
         if constexpr (DENSE) {
             const int32_t *csrc = a.blk_cols + (int64_t)(t.blk_begin + b0) * KB;
+            int32_t c[BCAP * KB / WAVE];
 #pragma unroll
-            for (int k = 0; k < BCAP * KB; k += WAVE)
-                if (k + lane < nb * KB) cols_lds[k + lane] = csrc[k + lane];
-            if (lane < nb * 4) bm_lds[lane] = a.blk_bitmap[(int64_t)(t.blk_begin + b0) * 4 + lane];
+            for (int k = 0; k < BCAP * KB / WAVE; ++k) c[k] = csrc[min(k * WAVE + lane, nb * KB - 1)];
+            const uint64_t w = a.blk_bitmap[(int64_t)(t.blk_begin + b0) * 4 + min(lane, nb * 4 - 1)];
+#pragma unroll
+            for (int k = 0; k < BCAP * KB / WAVE; ++k) cols_lds[k * WAVE + lane] = c[k];
+            if (lane < BCAP * 4) bm_lds[lane] = w;
         }
     };
-    fetch_entries(0, min(L, ECAP));
-    fetch_blocks(0, min(nblk, BCAP));
     wave_sync();
 
     bool tile_ready = false;
@@ -258,11 +284,13 @@ __global__ __launch_bounds__(WAVE) void spmm_task_kernel(SpmmArgs a) {
 #pragma unroll
                     for (int ps = 0; ps < PASSES; ++ps) {
                         const int k = ps * RPW + grp;
-                        raw[ps] = make_uint4(0u, 0u, 0u, 0u);
-                        if (k < nb * KB) {
-                            const int c = cols_lds[bb * KB + k];
-                            if (c >= 0) raw[ps] = Elem<half_t>::load_row(a.B, c, ldb_bytes, sub);
-                        }
+                        const int c = cols_lds[bb * KB + min(k, nb * KB - 1)];
+                        // a padding slot fetches row 0 and is cleared by a mask the compiler cannot see through
+                        // (so that it keeps the fetch outside any branch)
+                        uint32_t keep = (k < nb * KB && c >= 0) ? 0xffffffffu : 0u;
+                        asm volatile("" : "+v"(keep));
+                        raw[ps] = Elem<half_t>::load_row(a.B, keep ? c : 0, ldb_bytes, sub);
+                        raw[ps].x &= keep; raw[ps].y &= keep; raw[ps].z &= keep; raw[ps].w &= keep;
                     }
                     // this lane's 4 A elements (row j, slots 4g..4g+3) of each block, decoded from its bitmap
                     half4_t af[BPI];
@@ -280,9 +308,13 @@ __global__ __launch_bounds__(WAVE) void spmm_task_kernel(SpmmArgs a) {
                             prefix += __popcll(word & ((1ull << bitpos) - 1ull));
                             const unsigned nib = (unsigned)(word >> bitpos) & 0xFu;
                             const half_t *vals = reinterpret_cast<const half_t *>(a.dense_val) + vbase + prefix;
+                            // unconditional loads (an unset slot reads a neighbouring value, at most 3 halves past the
+                            // array's end, inside its 16 spare bytes) and a select afterwards
+                            half_t av[4];
 #pragma unroll
-                            for (int e = 0; e < 4; ++e)
-                                if (nib >> e & 1u) af[x][e] = vals[__popc(nib & ((1u << e) - 1u))];
+                            for (int e = 0; e < 4; ++e) av[e] = vals[__popc(nib & ((1u << e) - 1u))];
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) af[x][e] = (nib >> e & 1u) ? av[e] : (half_t)0;
                             vbase += c0 + c1 + c2 + c3;
                         }
                     }
@@ -494,7 +526,7 @@ __global__ __launch_bounds__(WAVE) void sddmm_segment_kernel(SddmmArgs a) {
     constexpr int PL = E::PER_LANE;
     constexpr int LPN = K / PL;              // lanes per nonzero
     constexpr int NPW = WAVE / LPN;          // nonzeros per wave pass
-    constexpr int U = 4;                     // passes in flight
+    constexpr int U = 8;                     // passes in flight: one default segment is one batch
     static_assert(LPN >= 1 && LPN <= WAVE, "unsupported K");
     const DevTask t = a.tasks[blockIdx.x];
     const int lane = threadIdx.x;

@@ -314,7 +314,7 @@ int resolve(const libra_plan_opts_t *in, int vdt, Resolved &o) {
     o.Ts = z.ts ? z.ts : 8;
     o.Cs = z.cs ? z.cs : 128;
     o.short_len = z.short_len ? z.short_len : 3;
-    o.sddmm_Cs = z.sddmm_cs ? z.sddmm_cs : 1024;
+    o.sddmm_Cs = z.sddmm_cs ? z.sddmm_cs : 128;
     o.threads = z.threads;
     if (o.W < 1 || o.W > 32 || o.KB < 1 || o.KB > 64 || o.tau_spmm < 1 || o.tau_sddmm < 1 || o.Ts < 1 ||
         o.Cs < 1 || o.short_len < 1 || o.sddmm_Cs < 1 || o.threads < 0)
