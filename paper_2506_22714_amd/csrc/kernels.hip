@@ -470,8 +470,8 @@ struct SddmmArgs {
     const int32_t *blk_cols;
     const uint64_t *blk_bitmap;
     const int32_t *blk_valptr;
-    const void *dense_val;
-    const int32_t *dense_perm;
+    const uint2 *dense_pv;      // per packed dense nonzero: CSR position, value bits
+    int32_t n_dense;
     const SdEnt *res_ent;
     const void *X;
     const void *Y;
@@ -479,86 +479,117 @@ struct SddmmArgs {
     int64_t M;
 };
 
+// Sum over the LPN consecutive lanes of a group; every lane of the group gets the total.
+// Steps inside a 16-lane row are DPP moves (no LDS traffic); wider groups finish with wave shuffles.
+template <int LPN>
+__device__ inline float group_sum(float s) {
+    auto dpp = [](float v, auto ctrl) {
+        return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), decltype(ctrl)::value, 0xf, 0xf, true));
+    };
+    if constexpr (LPN >= 2) s += dpp(s, std::integral_constant<int, 0xB1>{});      // quad_perm [1,0,3,2]
+    if constexpr (LPN >= 4) s += dpp(s, std::integral_constant<int, 0x4E>{});      // quad_perm [2,3,0,1]
+    if constexpr (LPN >= 8) s += dpp(s, std::integral_constant<int, 0x141>{});     // row_half_mirror
+    if constexpr (LPN >= 16) s += dpp(s, std::integral_constant<int, 0x140>{});    // row_mirror
+#pragma unroll
+    for (int m = 16; m < LPN; m <<= 1) s += __shfl_xor(s, m, WAVE);
+    return s;
+}
+
+// Dense blocks of one window: D = Xwin * Y[cols]^T on the MFMA, sampled through the bitmap.
+// Blocks are handled BB at a time so that each dependent step (column ids and bitmaps; Y rows;
+// value/position records) is one batch of loads for the whole group.  All loads are unconditional
+// from clamped addresses; only the final stores are predicated.
 template <int K>
 __global__ __launch_bounds__(WAVE) void sddmm_window_kernel(SddmmArgs a) {
     constexpr int KS = K / 32;               // MFMA k-steps
+    constexpr int BB = K <= 64 ? 4 : 2;      // blocks per batch
     const DevTask t = a.tasks[blockIdx.x];
     const int lane = threadIdx.x;
     const int g = lane >> 4, j = lane & 15;
     const half_t *X = reinterpret_cast<const half_t *>(a.X);
     const half_t *Y = reinterpret_cast<const half_t *>(a.Y);
     // A operand: row j of the window, k = 32*s + 8g .. +7 (rows past M repeat the last row; never sampled)
-    int64_t xr = (int64_t)t.id * W + j;
-    if (xr >= a.M) xr = a.M - 1;
+    const int64_t xr = min((int64_t)t.id * W + j, a.M - 1);
     half8_t xa[KS];
 #pragma unroll
     for (int s = 0; s < KS; ++s) xa[s] = *reinterpret_cast<const half8_t *>(X + xr * K + 32 * s + 8 * g);
-    for (int b = t.blk_begin; b < t.blk_end; ++b) {
-        int c = a.blk_cols[(int64_t)b * KB + j];
-        if (c < 0) c = 0;                    // padding slot: no bit is set in its column
-        float4_t d = {0.f, 0.f, 0.f, 0.f};
+    for (int b0 = t.blk_begin; b0 < t.blk_end; b0 += BB) {
+        int col[BB], vptr[BB];
+        uint64_t word[BB];
 #pragma unroll
-        for (int s = 0; s < KS; ++s) {
-            half8_t yb = *reinterpret_cast<const half8_t *>(Y + (int64_t)c * K + 32 * s + 8 * g);
-            d = __builtin_amdgcn_mfma_f32_16x16x32_f16(xa[s], yb, d, 0, 0, 0);
+        for (int x = 0; x < BB; ++x) {
+            const int b = min(b0 + x, t.blk_end - 1);
+            col[x] = a.blk_cols[(int64_t)b * KB + j];
+            word[x] = a.blk_bitmap[(int64_t)b * 4 + g];          // rows 4g..4g+3 of the block, bit e*16 + j
+            vptr[x] = a.blk_valptr[b];
         }
-        // lane (g, j) holds D[4g+e][j]; rows 4g..4g+3 are word g of the bitmap, bit e*16 + j
-        const uint64_t *bm = a.blk_bitmap + (int64_t)b * 4;
-        const uint64_t word = bm[g];
-        int prefix = a.blk_valptr[b];
-        if (g > 0) prefix += __popcll(bm[0]);
-        if (g > 1) prefix += __popcll(bm[1]);
-        if (g > 2) prefix += __popcll(bm[2]);
+        half8_t yb[BB][KS];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const int bit = e * 16 + j;
-            if (word >> bit & 1ull) {
-                const int slot = prefix + __popcll(word & ((1ull << bit) - 1ull));
-                a.out[a.dense_perm[slot]] = (float)reinterpret_cast<const half_t *>(a.dense_val)[slot] * d[e];
-            }
+        for (int x = 0; x < BB; ++x) {
+            const int c = max(col[x], 0);                        // padding slot: no bit is set in its column
+#pragma unroll
+            for (int s = 0; s < KS; ++s) yb[x][s] = *reinterpret_cast<const half8_t *>(Y + (int64_t)c * K + 32 * s + 8 * g);
         }
+        // where each of this lane's (up to 4 per block) outputs sits among the block's packed values
+        int slot[BB][4];
+#pragma unroll
+        for (int x = 0; x < BB; ++x) {
+            const int cnt = __popcll(word[x]);
+            const int c0 = __builtin_amdgcn_readlane(cnt, 0), c1 = __builtin_amdgcn_readlane(cnt, 16), c2 = __builtin_amdgcn_readlane(cnt, 32);
+            const int prefix = vptr[x] + (g > 0 ? c0 : 0) + (g > 1 ? c1 : 0) + (g > 2 ? c2 : 0);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) slot[x][e] = prefix + __popcll(word[x] & ((1ull << (e * 16 + j)) - 1ull));
+        }
+        // value/position records of the outputs (an unset bit reads a neighbouring record and drops it)
+        uint2 pv[BB][4];
+#pragma unroll
+        for (int x = 0; x < BB; ++x)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) pv[x][e] = a.dense_pv[min(slot[x][e], a.n_dense - 1)];
+        float4_t d[BB];
+#pragma unroll
+        for (int x = 0; x < BB; ++x) {
+            d[x] = float4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int s = 0; s < KS; ++s) d[x] = __builtin_amdgcn_mfma_f32_16x16x32_f16(xa[s], yb[x][s], d[x], 0, 0, 0);
+        }
+#pragma unroll
+        for (int x = 0; x < BB; ++x)
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (b0 + x < t.blk_end && (word[x] >> (e * 16 + j) & 1ull))
+                    a.out[(int32_t)pv[x][e].x] = Elem<half_t>::word_val(pv[x][e].y) * d[x][e];
     }
 }
 
+// Residual nonzeros: LPN lanes per nonzero, NPW nonzeros per wave pass, U passes in one batch of loads.
 template <class T, int K>
 __global__ __launch_bounds__(WAVE) void sddmm_segment_kernel(SddmmArgs a) {
     using E = Elem<T>;
     constexpr int PL = E::PER_LANE;
     constexpr int LPN = K / PL;              // lanes per nonzero
     constexpr int NPW = WAVE / LPN;          // nonzeros per wave pass
-    constexpr int U = 8;                     // passes in flight: one default segment is one batch
+    constexpr int U = LPN <= 8 ? 8 : 4;      // passes in flight
     static_assert(LPN >= 1 && LPN <= WAVE, "unsupported K");
     const DevTask t = a.tasks[blockIdx.x];
     const int lane = threadIdx.x;
     const int sub = lane % LPN, grp = lane / LPN;
     for (int q0 = t.res_begin; q0 < t.res_end; q0 += NPW * U) {
-        SdEnt ent[U];
+        uint4 ent[U];                        // row, col, position, value bits
         typename E::raw_t x[U], y[U];
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int q = q0 + u * NPW + grp;
-            if (q < t.res_end) {
-                const uint4 w = reinterpret_cast<const uint4 *>(a.res_ent)[q];
-                ent[u].row = (int32_t)w.x; ent[u].col = (int32_t)w.y; ent[u].perm = (int32_t)w.z; ent[u].val = w.w;
-            }
-        }
+        for (int u = 0; u < U; ++u) ent[u] = reinterpret_cast<const uint4 *>(a.res_ent)[min(q0 + u * NPW + grp, t.res_end - 1)];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int q = q0 + u * NPW + grp;
-            if (q < t.res_end) {
-                x[u] = E::load(a.X, (int64_t)ent[u].row * K + sub * PL);
-                y[u] = E::load(a.Y, (int64_t)ent[u].col * K + sub * PL);
-            }
+            x[u] = E::load(a.X, (int64_t)(int32_t)ent[u].x * K + sub * PL);
+            y[u] = E::load(a.Y, (int64_t)(int32_t)ent[u].y * K + sub * PL);
         }
+        float s[U];
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int q = q0 + u * NPW + grp;
-            float s = 0.f;
-            if (q < t.res_end) s = E::dot(x[u], y[u], 0.f);
+        for (int u = 0; u < U; ++u) s[u] = group_sum<LPN>(E::dot(x[u], y[u], 0.f));
 #pragma unroll
-            for (int m = 1; m < LPN; m <<= 1) s += __shfl_xor(s, m, WAVE);
-            if (q < t.res_end && sub == 0) a.out[ent[u].perm] = E::word_val(ent[u].val) * s;
-        }
+        for (int u = 0; u < U; ++u)
+            if (sub == 0 && q0 + u * NPW + grp < t.res_end) a.out[(int32_t)ent[u].z] = E::word_val(ent[u].w) * s[u];
     }
 }
 
@@ -690,6 +721,7 @@ struct Staging {
     std::vector<ResEnt16> ent16;
     std::vector<ResEnt32> ent32;
     std::vector<SdEnt> sdent;
+    std::vector<SdPv> sdpv;
 };
 
 void layout(libra_plan_t *P, Uploader &u, Staging *st) {
@@ -727,7 +759,16 @@ void layout(libra_plan_t *P, Uploader &u, Staging *st) {
     u.putv(sd.blk_cols, sd.dev.blk_cols);
     u.putv(sd.blk_bitmap, sd.dev.blk_bitmap);
     u.putv(sd.blk_valptr, sd.dev.blk_valptr);
-    u.putv(sd.dense_val, sd.dev.dense_val);
+    const size_t ndd = sd.dense_perm.size();
+    if (st) {
+        st->sdpv.resize(ndd);
+        for (size_t i = 0; i < ndd; ++i) {
+            uint32_t bits = 0;
+            std::memcpy(&bits, sd.dense_val.data() + i * P->vsize, P->vsize);
+            st->sdpv[i] = {sd.dense_perm[i], bits};
+        }
+    }
+    u.put(st ? (const void *)st->sdpv.data() : nullptr, ndd * sizeof(SdPv), sd.dev.dense_pv);
     u.putv(sd.dense_perm, sd.dev.dense_perm);
     const size_t nrd = sd.res_perm.size();
     if (st) {
@@ -806,7 +847,8 @@ extern "C" int libra_sddmm(const libra_plan_t *P, const void *X, const void *Y, 
     if (((uintptr_t)X & 15) || ((uintptr_t)Y & 15) || ((uintptr_t)out & 3)) return LIBRA_ERR_BUFFER;
     hipStream_t s = (hipStream_t)stream;
     const SubPlan &sp = P->sddmm;
-    SddmmArgs a{sp.dev.tasks, sp.dev.blk_cols, sp.dev.blk_bitmap, sp.dev.blk_valptr, sp.dev.dense_val, sp.dev.dense_perm,
+    SddmmArgs a{sp.dev.tasks, sp.dev.blk_cols, sp.dev.blk_bitmap, sp.dev.blk_valptr,
+                reinterpret_cast<const uint2 *>(sp.dev.dense_pv), (int32_t)sp.dense_perm.size(),
                 reinterpret_cast<const SdEnt *>(sp.dev.res_ent), X, Y, out, P->M};
     // window tasks come first in the table, residual segments after them
     const int64_t nw = sp.n_window_tasks, nc = sp.n_chunk_tasks;
@@ -866,7 +908,7 @@ extern "C" int libra_plan_set_values(libra_plan_t *P, const void *vals, int dtyp
     const Seg segs[4] = {
         {sa.dev.dense_perm, sa.dev.dense_val, (int64_t)sa.dense_perm.size(), vs, 0},
         {sa.dev.res_perm, sa.dev.res_ent, (int64_t)sa.res_perm.size(), f16 ? (int)sizeof(ResEnt16) : (int)sizeof(ResEnt32), 4},
-        {sd.dev.dense_perm, sd.dev.dense_val, (int64_t)sd.dense_perm.size(), vs, 0},
+        {sd.dev.dense_perm, sd.dev.dense_pv, (int64_t)sd.dense_perm.size(), (int)sizeof(SdPv), 4},
         {sd.dev.res_perm, sd.dev.res_ent, (int64_t)sd.res_perm.size(), (int)sizeof(SdEnt), 12}};
     for (const Seg &g : segs) {
         if (g.n == 0) continue;

@@ -39,13 +39,20 @@ struct SdEnt {
     uint32_t val;               // fp16 bits in the low half, or fp32 bits
 };
 
+// Packed dense nonzero of the SDDMM sub-plan: where the result goes and the value that scales it.
+struct SdPv {
+    int32_t perm;
+    uint32_t val;               // fp16 bits in the low half
+};
+
 // Device-side pointers of one sub-plan (all inside the caller's buffer).
 struct SubPlanDev {
     const DevTask *tasks = nullptr;
     const int32_t *blk_cols = nullptr;
     const uint64_t *blk_bitmap = nullptr;
     const int32_t *blk_valptr = nullptr;
-    void *dense_val = nullptr;
+    void *dense_val = nullptr;          // SpMM: packed values in bit order
+    void *dense_pv = nullptr;           // SDDMM: SdPv per packed value
     const int32_t *dense_perm = nullptr;
     void *res_ent = nullptr;            // ResEnt16 / ResEnt32 (SpMM) or SdEnt (SDDMM)
     const int32_t *res_perm = nullptr;
