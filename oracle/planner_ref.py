@@ -42,7 +42,7 @@ class Opts:
     mode: int = HYBRID
     W: int = 16
     KB: int = 16
-    tau_spmm: int = 2
+    tau_spmm: int = 3
     tau_sddmm: int = 32
     Ts: int = 8
     Cs: int = 128

@@ -309,7 +309,7 @@ int resolve(const libra_plan_opts_t *in, int vdt, Resolved &o) {
     if (vdt == LIBRA_F32) o.mode = LIBRA_MODE_SCALAR_ONLY;
     o.W = z.window_rows ? z.window_rows : 16;
     o.KB = z.block_cols ? z.block_cols : 16;
-    o.tau_spmm = z.spmm_min_vec_nnz ? z.spmm_min_vec_nnz : 2;
+    o.tau_spmm = z.spmm_min_vec_nnz ? z.spmm_min_vec_nnz : 3;
     o.tau_sddmm = z.sddmm_min_blk_nnz ? z.sddmm_min_blk_nnz : 32;
     o.Ts = z.ts ? z.ts : 8;
     o.Cs = z.cs ? z.cs : 128;

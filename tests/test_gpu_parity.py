@@ -381,3 +381,74 @@ def test_full_community_config_sampled():
     check_sddmm(A, X, Y, out, TOL_F16, idx=idx)
     assert np.all(np.isfinite(out))
     p.close()
+
+
+def test_full_irregular_config_sampled():
+    """Config 4: 2.4 M rows, shifted-Zipf degrees up to 100 000 (row splitting, atomics), N = K = 32."""
+    A = _full("irregular")
+    p = lb.Plan.from_csr(A).upload()
+    st = p.stats()
+    assert st["spmm_split_rows"] > 1000 and st["spmm_chunk_tasks"] > 100_000
+    _plan_invariants(p, A)
+    rows = _sample_rows(A, 3000, seed=4)
+    B = wl.dense_normal(A.Kc, 32, seed=wl.BASE_SEED + 401)
+    C = p.spmm(dev(B))
+    torch.cuda.synchronize()
+    sub = C[torch.from_numpy(rows).cuda()].cpu().numpy()
+    ref, S = oracle.spmm(A.rowptr, A.col, A.val, B, rows=rows)
+    deg = np.diff(A.rowptr)[rows].astype(np.float64)
+    # rows of up to 1e5 terms accumulated in chunks with atomics: the stated bar, and the derived bound per row
+    err = oracle.graded_error(sub, ref, S, deg[:, None])
+    assert err <= TOL_F16, err
+    per_row = np.abs(sub - ref) / np.maximum(np.abs(ref), S / np.sqrt(np.maximum(deg, 1))[:, None])
+    assert np.all(per_row.max(axis=1) <= 16.0 * np.sqrt(np.maximum(deg, 1)) * 2.0 ** -24)
+    # whole-output property on all rows: unit values, so C @ 1 = A (B 1)
+    ref_sum, S_sum = oracle.spmm(A.rowptr, A.col, A.val, B.astype(np.float32).sum(axis=1, keepdims=True).astype(np.float32))
+    got_sum = C.sum(dim=1, keepdim=True, dtype=torch.float64).cpu().numpy()
+    assert np.max(np.abs(got_sum - ref_sum) / np.maximum(S_sum, 1.0)) < 1e-3
+    del C
+    X = wl.dense_normal(A.M, 32, seed=wl.BASE_SEED + 402)
+    Y = wl.dense_normal(A.Kc, 32, seed=wl.BASE_SEED + 403)
+    out = p.sddmm(dev(X), dev(Y)).cpu().numpy()
+    idx = np.random.default_rng(5).integers(0, A.nnz, size=300_000)
+    check_sddmm(A, X, Y, out, TOL_F16, idx=idx)
+    assert np.all(np.isfinite(out))
+    p.close()
+
+
+def test_full_gat_config_one_head_sampled():
+    """Config 5: one attention head on the 2^20-node R-MAT graph: SDDMM K=64 -> softmax -> SpMM N=64."""
+    A = _full("gat")
+    K = 64
+    scale = 1.0 / np.sqrt(K)
+    X = wl.dense_normal(A.M, K, seed=wl.BASE_SEED + 501)
+    Y = wl.dense_normal(A.Kc, K, seed=wl.BASE_SEED + 502)
+    p = lb.Plan.from_csr(A).upload()
+    _plan_invariants(p, A)
+    Yd = dev(Y)
+    scores = p.sddmm(dev(X), Yd)
+    alpha = p.edge_softmax(scores, scale)
+    p.set_values(alpha)
+    C = p.spmm(Yd)
+    torch.cuda.synchronize()
+    sc = scores.cpu().numpy()
+    al = alpha.cpu().numpy()
+    idx = np.random.default_rng(6).integers(0, A.nnz, size=300_000)
+    check_sddmm(A, X, Y, sc, TOL_F16, idx=idx)
+    # softmax on sampled rows, from the GPU's own scores
+    rows = _sample_rows(A, 2000, seed=7)
+    deg = np.diff(A.rowptr)
+    for i in rows[:500]:
+        lo, hi = A.rowptr[i], A.rowptr[i + 1]
+        if hi > lo:
+            z = scale * sc[lo:hi].astype(np.float64)
+            e = np.exp(z - z.max())
+            want = e / e.sum()
+            assert np.max(np.abs(al[lo:hi].astype(np.float64) - want) / np.maximum(want, 2.0 ** -14)) < 4e-3
+    # SpMM with the GPU's alpha as values, sampled rows against the oracle
+    sub = C[torch.from_numpy(rows).cuda()].cpu().numpy()
+    ref, S = oracle.spmm(A.rowptr, A.col, al, Y, rows=rows)
+    err = oracle.graded_error(sub, ref, S, deg[rows].astype(np.float64)[:, None])
+    assert err <= bound(TOL_F16, deg[rows].max()), err
+    assert torch.isfinite(C).all()
+    p.close()
