@@ -174,6 +174,9 @@ __device__ inline void wave_sync() {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
+#ifndef SPMM_U
+#define SPMM_U 8
+#endif
 template <class T, int N>
 __global__ __launch_bounds__(WAVE) void spmm_task_kernel(SpmmArgs a) {
     using E = Elem<T>;
@@ -184,19 +187,17 @@ __global__ __launch_bounds__(WAVE) void spmm_task_kernel(SpmmArgs a) {
     constexpr int RPW = WAVE / LPR;          // lane groups per wave
     static_assert(LPR >= 1 && LPR <= WAVE && WAVE % LPR == 0, "unsupported N");
     constexpr int LDC = N + 4;               // fp32 tile row stride (floats)
-    constexpr int BPI = N <= 128 ? 2 : 1;    // dense blocks fetched per round trip
+    constexpr int BPI = 1;                   // dense blocks staged in LDS at a time (the stage then fits inside the tile's bytes)
     constexpr int LDBS = N + 16;             // fp16 stage row stride (halves): 4 consecutive rows cover all 32 banks
     constexpr int TILE_BYTES = W * LDC * 4;
     constexpr int STAGE_BYTES = DENSE ? BPI * KB * LDBS * 2 : 0;
     constexpr int SMEM = TILE_BYTES > STAGE_BYTES ? TILE_BYTES : STAGE_BYTES;
     constexpr int ECAP = 128;                // residual entries staged per round
     constexpr int BCAP = 8;                  // dense blocks whose metadata is staged per round
-    constexpr int U = N <= 128 ? 16 : 8;     // B-row fetches in flight per lane group
+    constexpr int U = SPMM_U;                // B-row fetches in flight per lane group
     // the B stage (dense phase) and the C tile (afterwards) share the same LDS bytes
     __shared__ __attribute__((aligned(16))) unsigned char smem[SMEM];
     __shared__ __attribute__((aligned(16))) ent_t ent_lds[ECAP];
-    __shared__ __attribute__((aligned(16))) float slots[RPW * N];      // one partial row per lane group
-    __shared__ int slot_row[RPW];
     __shared__ __attribute__((aligned(16))) int32_t cols_lds[DENSE ? BCAP * KB : 4];
     __shared__ __attribute__((aligned(16))) uint64_t bm_lds[DENSE ? BCAP * 4 : 2];
     float *tile = reinterpret_cast<float *>(smem);
@@ -262,7 +263,9 @@ __global__ __launch_bounds__(WAVE) void spmm_task_kernel(SpmmArgs a) {
         if (nblk > 0) {
             tile_ready = true;
             constexpr int NT = N / 16;
-            constexpr int PASSES = BPI * KB / RPW;               // wave loads per fetched round
+            constexpr int PASSES = BPI * KB / RPW;               // wave loads per staged group of BPI blocks
+            constexpr int H = 1;                                 // staged groups per round trip (more costs registers, i.e. waves)
+            constexpr int FPI = BPI * H;                         // blocks fetched per round trip
             static_assert(BPI * KB % RPW == 0 && PASSES >= 1, "stage shape");
             half_t *stage = reinterpret_cast<half_t *>(smem);
             const int g = lane >> 4, j = lane & 15;
@@ -277,25 +280,27 @@ __global__ __launch_bounds__(WAVE) void spmm_task_kernel(SpmmArgs a) {
                     fetch_blocks(b0, nbr);
                     wave_sync();
                 }
-                for (int bb = 0; bb < nbr; bb += BPI) {
-                    const int nb = min(BPI, nbr - bb);
-                    // B rows of up to BPI blocks (padding slots become zero rows)
-                    uint4 raw[PASSES];
+                for (int bb = 0; bb < nbr; bb += FPI) {
+                    const int nb = min(FPI, nbr - bb);
+                    // one round trip: the B rows of up to FPI blocks (padding slots become zero rows) ...
+                    uint4 raw[H][PASSES];
 #pragma unroll
-                    for (int ps = 0; ps < PASSES; ++ps) {
-                        const int k = ps * RPW + grp;
-                        const int c = cols_lds[bb * KB + min(k, nb * KB - 1)];
-                        // a padding slot fetches row 0 and is cleared by a mask the compiler cannot see through
-                        // (so that it keeps the fetch outside any branch)
-                        uint32_t keep = (k < nb * KB && c >= 0) ? 0xffffffffu : 0u;
-                        asm volatile("" : "+v"(keep));
-                        raw[ps] = Elem<half_t>::load_row(a.B, keep ? c : 0, ldb_bytes, sub);
-                        raw[ps].x &= keep; raw[ps].y &= keep; raw[ps].z &= keep; raw[ps].w &= keep;
-                    }
-                    // this lane's 4 A elements (row j, slots 4g..4g+3) of each block, decoded from its bitmap
-                    half4_t af[BPI];
+                    for (int h = 0; h < H; ++h)
 #pragma unroll
-                    for (int x = 0; x < BPI; ++x) {
+                        for (int ps = 0; ps < PASSES; ++ps) {
+                            const int k = h * BPI * KB + ps * RPW + grp;
+                            const int c = cols_lds[bb * KB + min(k, nb * KB - 1)];
+                            // a padding slot fetches row 0 and is cleared by a mask the compiler cannot see through
+                            // (so that it keeps the fetch outside any branch)
+                            uint32_t keep = (k < nb * KB && c >= 0) ? 0xffffffffu : 0u;
+                            asm volatile("" : "+v"(keep));
+                            raw[h][ps] = Elem<half_t>::load_row(a.B, keep ? c : 0, ldb_bytes, sub);
+                            raw[h][ps].x &= keep; raw[h][ps].y &= keep; raw[h][ps].z &= keep; raw[h][ps].w &= keep;
+                        }
+                    // ... and this lane's 4 A elements (row j, slots 4g..4g+3) of each block, decoded from its bitmap
+                    half4_t af[FPI];
+#pragma unroll
+                    for (int x = 0; x < FPI; ++x) {
                         af[x] = half4_t{(half_t)0, (half_t)0, (half_t)0, (half_t)0};
                         if (x < nb) {
                             const uint64_t *bm = &bm_lds[(bb + x) * 4];
@@ -318,26 +323,32 @@ __global__ __launch_bounds__(WAVE) void spmm_task_kernel(SpmmArgs a) {
                             vbase += c0 + c1 + c2 + c3;
                         }
                     }
-                    wave_sync();                 // the previous round's operand reads are done
+                    // the fetched rows go through the LDS stage BPI blocks at a time
 #pragma unroll
-                    for (int ps = 0; ps < PASSES; ++ps) {
-                        const int k = ps * RPW + grp;
-                        *reinterpret_cast<uint4 *>(&stage[k * LDBS + sub * 8]) = raw[ps];
-                    }
-                    wave_sync();
+                    for (int h = 0; h < H; ++h) {
+                        if (h * BPI < nb) {
+                            wave_sync();         // the previous operand reads are done
 #pragma unroll
-                    for (int x = 0; x < BPI; ++x) {
-                        if (x < nb) {
-                            // lane i of a 16-lane block points at row i/4, halves 4(i%4)..+3 of the 32-byte row piece;
-                            // the transposing read hands lane j the four rows' element j: B[4g+e][16n+j], e = 0..3
-                            const half_t *src = &stage[(x * KB + 4 * g + (j >> 2)) * LDBS + 4 * (j & 3)];
+                            for (int ps = 0; ps < PASSES; ++ps) {
+                                const int k = ps * RPW + grp;
+                                *reinterpret_cast<uint4 *>(&stage[k * LDBS + sub * 8]) = raw[h][ps];
+                            }
+                            wave_sync();
 #pragma unroll
-                            for (int n = 0; n < NT; ++n) {
-                                const short4_t r = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                                    (short4_t __attribute__((address_space(3))) *)(src + 16 * n));
-                                half4_t bf;
-                                __builtin_memcpy(&bf, &r, 8);
-                                acc[n] = __builtin_amdgcn_mfma_f32_16x16x16f16(af[x], bf, acc[n], 0, 0, 0);
+                            for (int x = 0; x < BPI; ++x) {
+                                if (h * BPI + x < nb) {
+                                    // lane i of a 16-lane block points at row i/4, halves 4(i%4)..+3 of the 32-byte row piece;
+                                    // the transposing read hands lane j the four rows' element j: B[4g+e][16n+j], e = 0..3
+                                    const half_t *src = &stage[(x * KB + 4 * g + (j >> 2)) * LDBS + 4 * (j & 3)];
+#pragma unroll
+                                    for (int n = 0; n < NT; ++n) {
+                                        const short4_t r = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                                            (short4_t __attribute__((address_space(3))) *)(src + 16 * n));
+                                        half4_t bf;
+                                        __builtin_memcpy(&bf, &r, 8);
+                                        acc[n] = __builtin_amdgcn_mfma_f32_16x16x16f16(af[h * BPI + x], bf, acc[n], 0, 0, 0);
+                                    }
+                                }
                             }
                         }
                     }
@@ -377,58 +388,81 @@ __global__ __launch_bounds__(WAVE) void spmm_task_kernel(SpmmArgs a) {
         const int q0 = grp * per;
         const int q1 = min(nE, q0 + per);
         // A row is added into the tile by the group that holds its first entry (plain read-add-write:
-        // one owner per row).  A group whose run starts inside a row hands that row's partial sum to
-        // its slot instead; the slots are added afterwards in group order, so the order of additions is fixed.
+        // one owner per row).  A group whose run starts inside a row keeps that row's partial sum in
+        // registers instead and adds it after the others, in group order, so the order of additions is fixed.
         bool first_is_shared = q0 > 0 && q0 < q1 && E::lds_ent(ent_lds, q0 - 1).row == E::lds_ent(ent_lds, q0).row;
-        if (sub == 0) slot_row[grp] = -1;
+        int kept_row = -1;
+        float kept[8] = {0, 0, 0, 0, 0, 0, 0, 0};
         int cur = -1;
         float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+        auto add_to_tile = [&](int r, const float (&v)[8]) {
+#pragma unroll
+            for (int e = 0; e < PL; e += 4) {
+                float4_t *p = reinterpret_cast<float4_t *>(&tile[r * LDC + sub * PL + e]);
+                float4_t x = *p;
+                x[0] += v[e]; x[1] += v[e + 1]; x[2] += v[e + 2]; x[3] += v[e + 3];
+                *p = x;
+            }
+        };
         auto flush = [&]() {
             if (first_is_shared) {
                 first_is_shared = false;
-                if (sub == 0) slot_row[grp] = cur;
+                kept_row = cur;
 #pragma unroll
-                for (int e = 0; e < PL; e += 4)
-                    *reinterpret_cast<float4_t *>(&slots[grp * N + sub * PL + e]) = float4_t{acc[e], acc[e + 1], acc[e + 2], acc[e + 3]};
+                for (int e = 0; e < PL; ++e) kept[e] = acc[e];
             } else {
-#pragma unroll
-                for (int e = 0; e < PL; e += 4) {
-                    float4_t *p = reinterpret_cast<float4_t *>(&tile[cur * LDC + sub * PL + e]);
-                    float4_t v = *p;
-                    v[0] += acc[e]; v[1] += acc[e + 1]; v[2] += acc[e + 2]; v[3] += acc[e + 3];
-                    *p = v;
-                }
+                add_to_tile(cur, acc);
             }
         };
         for (int q = q0; q < q1; q += U) {
-            // all entry reads, then all row fetches, back to back; slots past the run repeat its last entry
-            // (their fetch is harmless and their product is never formed)
+            // all entry reads, then all row fetches, back to back
             ent_t en[U];
             typename E::raw_t raw[U];
+            const bool full = q + U <= q1;
+            if (full) {
 #pragma unroll
-            for (int u = 0; u < U; ++u) en[u] = E::lds_ent(ent_lds, min(q + u, q1 - 1));
+                for (int u = 0; u < U; ++u) en[u] = E::lds_ent(ent_lds, q + u);
+            } else {
+                // slots past the run repeat its last entry (their fetch is harmless, their product is never formed)
+#pragma unroll
+                for (int u = 0; u < U; ++u) en[u] = E::lds_ent(ent_lds, min(q + u, q1 - 1));
+            }
 #pragma unroll
             for (int u = 0; u < U; ++u) raw[u] = E::load_row(a.B, en[u].col, ldb_bytes, sub);
+            bool one_row = full;
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                if (q + u < q1) {
-                    const int r = (int)en[u].row;
-                    if (r != cur) {
-                        if (cur >= 0) flush();
+            for (int u = 1; u < U; ++u) one_row = one_row && en[u].row == en[0].row;
+            if (one_row) {
+                // common case (long rows, segments of decomposed rows): the whole batch belongs to one row
+                const int r = (int)en[0].row;
+                if (r != cur) {
+                    if (cur >= 0) flush();
 #pragma unroll
-                        for (int e = 0; e < PL; ++e) acc[e] = 0.f;
-                        cur = r;
+                    for (int e = 0; e < PL; ++e) acc[e] = 0.f;
+                    cur = r;
+                }
+#pragma unroll
+                for (int u = 0; u < U; ++u) E::fma(E::ent_val(en[u]), raw[u], acc);
+            } else {
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    if (q + u < q1) {
+                        const int r = (int)en[u].row;
+                        if (r != cur) {
+                            if (cur >= 0) flush();
+#pragma unroll
+                            for (int e = 0; e < PL; ++e) acc[e] = 0.f;
+                            cur = r;
+                        }
+                        E::fma(E::ent_val(en[u]), raw[u], acc);
                     }
-                    E::fma(E::ent_val(en[u]), raw[u], acc);
                 }
             }
         }
         if (cur >= 0) flush();
-        wave_sync();
         for (int gq = 1; gq < RPW; ++gq) {
-            const int r = slot_row[gq];
-            if (r >= 0)
-                for (int f = lane; f < N; f += WAVE) tile[r * LDC + f] += slots[gq * N + f];
+            wave_sync();
+            if (grp == gq && kept_row >= 0) add_to_tile(kept_row, kept);
         }
     }
     wave_sync();
@@ -442,7 +476,8 @@ __global__ __launch_bounds__(WAVE) void spmm_task_kernel(SpmmArgs a) {
             if (!(out_mask >> r & 1u)) continue;
             float *dst = cbase + (int64_t)r * a.ldc;
             if (store_mask >> r & 1u) {
-                *reinterpret_cast<float4_t *>(dst + cl * 4) = *reinterpret_cast<const float4_t *>(&tile[r * LDC + cl * 4]);
+                // streaming store: C is written once and not read again by this call
+                __builtin_nontemporal_store(*reinterpret_cast<const float4_t *>(&tile[r * LDC + cl * 4]), reinterpret_cast<float4_t *>(dst + cl * 4));
             } else {
                 // each atomic instruction covers LPF consecutive floats of the row
 #pragma unroll
