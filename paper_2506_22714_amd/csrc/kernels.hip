@@ -535,10 +535,9 @@ __device__ inline float group_sum(float s) {
 // value/position records) is one batch of loads for the whole group.  All loads are unconditional
 // from clamped addresses; only the final stores are predicated.
 template <int K>
-__global__ __launch_bounds__(WAVE) void sddmm_window_kernel(SddmmArgs a) {
+__device__ inline void sddmm_window_task(const SddmmArgs &a, const DevTask &t) {
     constexpr int KS = K / 32;               // MFMA k-steps
     constexpr int BB = K <= 64 ? 4 : 2;      // blocks per batch
-    const DevTask t = a.tasks[blockIdx.x];
     const int lane = threadIdx.x;
     const int g = lane >> 4, j = lane & 15;
     const half_t *X = reinterpret_cast<const half_t *>(a.X);
@@ -599,14 +598,13 @@ __global__ __launch_bounds__(WAVE) void sddmm_window_kernel(SddmmArgs a) {
 
 // Residual nonzeros: LPN lanes per nonzero, NPW nonzeros per wave pass, U passes in one batch of loads.
 template <class T, int K>
-__global__ __launch_bounds__(WAVE) void sddmm_segment_kernel(SddmmArgs a) {
+__device__ inline void sddmm_segment_task(const SddmmArgs &a, const DevTask &t) {
     using E = Elem<T>;
     constexpr int PL = E::PER_LANE;
     constexpr int LPN = K / PL;              // lanes per nonzero
     constexpr int NPW = WAVE / LPN;          // nonzeros per wave pass
     constexpr int U = LPN <= 8 ? 8 : 4;      // passes in flight
     static_assert(LPN >= 1 && LPN <= WAVE, "unsupported K");
-    const DevTask t = a.tasks[blockIdx.x];
     const int lane = threadIdx.x;
     const int sub = lane % LPN, grp = lane / LPN;
     for (int q0 = t.res_begin; q0 < t.res_end; q0 += NPW * U) {
@@ -628,37 +626,108 @@ __global__ __launch_bounds__(WAVE) void sddmm_segment_kernel(SddmmArgs a) {
     }
 }
 
+// One launch for both kinds of SDDMM task (one wave each): the window tasks, heaviest first, then the
+// residual segments.  fp32 plans have no window tasks.
+template <class T, int K>
+__global__ __launch_bounds__(WAVE) void sddmm_task_kernel(SddmmArgs a) {
+    const DevTask t = a.tasks[blockIdx.x];
+    if constexpr (std::is_same<T, half_t>::value) {
+        if (t.kind == LIBRA_TASK_WINDOW) {
+            sddmm_window_task<K>(a, t);
+            return;
+        }
+    }
+    sddmm_segment_task<T, K>(a, t);
+}
+
 // ---------------------------------------------------------------------------------------
 // Edge softmax (one wave per row, rows dealt round-robin) and value scatter
 // ---------------------------------------------------------------------------------------
-__device__ inline float wave_max(float v) {
-#pragma unroll
-    for (int m = 1; m < WAVE; m <<= 1) v = fmaxf(v, __shfl_xor(v, m, WAVE));
-    return v;
-}
-__device__ inline float wave_sum(float v) {
-#pragma unroll
-    for (int m = 1; m < WAVE; m <<= 1) v += __shfl_xor(v, m, WAVE);
-    return v;
+// Maximum over the 16 lanes of a DPP row; every lane gets the result.
+__device__ inline float row16_max(float s) {
+    auto dpp = [](float v, auto ctrl) {
+        return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), decltype(ctrl)::value, 0xf, 0xf, true));
+    };
+    s = fmaxf(s, dpp(s, std::integral_constant<int, 0xB1>{}));      // quad_perm [1,0,3,2]
+    s = fmaxf(s, dpp(s, std::integral_constant<int, 0x4E>{}));      // quad_perm [2,3,0,1]
+    s = fmaxf(s, dpp(s, std::integral_constant<int, 0x141>{}));     // row_half_mirror
+    s = fmaxf(s, dpp(s, std::integral_constant<int, 0x140>{}));     // row_mirror
+    return s;
 }
 
+
+// Rows of up to 64 nonzeros (the bulk of a graph): 16 lanes per row, read once and kept in registers.
 template <class TO>
-__global__ __launch_bounds__(256) void edge_softmax_kernel(const int32_t *rowptr, int64_t M, const float *score, float scale, TO *out) {
-    const int lane = threadIdx.x & 63;
-    const int64_t wave = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
-    const int64_t nwaves = ((int64_t)gridDim.x * blockDim.x) >> 6;
-    for (int64_t i = wave; i < M; i += nwaves) {
-        const int s = rowptr[i], e = rowptr[i + 1];
-        if (s == e) continue;
-        float mx = -INFINITY;
-        for (int p = s + lane; p < e; p += WAVE) mx = fmaxf(mx, scale * score[p]);
-        mx = wave_max(mx);
-        float den = 0.f;
-        for (int p = s + lane; p < e; p += WAVE) den += __expf(scale * score[p] - mx);
-        den = wave_sum(den);
-        const float inv = 1.f / den;
-        for (int p = s + lane; p < e; p += WAVE) out[p] = (TO)(__expf(scale * score[p] - mx) * inv);
+__global__ __launch_bounds__(256) void edge_softmax_rows_kernel(const int32_t *rowptr, int64_t M, const float *score, float scale, TO *out) {
+    const int l = threadIdx.x & 15;
+    const int64_t group = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 4;
+    const int64_t ngroups = ((int64_t)gridDim.x * blockDim.x) >> 4;
+    for (int64_t i = group; i < M; i += ngroups) {
+        const int s = rowptr[i], n = rowptr[i + 1] - s;
+        if (n == 0 || n > 64) continue;         // longer rows are listed at plan time and run below
+        {
+            float v[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const int q = l + 16 * k;
+                v[k] = scale * score[s + min(q, n - 1)];
+                if (q >= n) v[k] = -INFINITY;
+            }
+            const float mx = row16_max(fmaxf(fmaxf(v[0], v[1]), fmaxf(v[2], v[3])));
+            float ex[4], den = 0.f;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) { ex[k] = __expf(v[k] - mx); den += ex[k]; }      // exp(-inf) = 0 for the padding
+            const float inv = 1.f / group_sum<16>(den);
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+                if (l + 16 * k < n) out[s + l + 16 * k] = (TO)(ex[k] * inv);
+        }
     }
+}
+
+// Rows of 65 .. LIBRA_SOFTMAX_LONG_ROW nonzeros (listed at plan time): one wave per row.
+template <class TO>
+__global__ __launch_bounds__(256) void edge_softmax_medium_kernel(const int32_t *rowptr, const int32_t *rows, int nrows, const float *score, float scale, TO *out) {
+    const int lane = threadIdx.x & 63;
+    const int w = (blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    if (w >= nrows) return;
+    const int64_t i = rows[w];
+    const int s = rowptr[i], n = rowptr[i + 1] - s;
+    float mx = -INFINITY;
+    for (int q = lane; q < n; q += WAVE) mx = fmaxf(mx, scale * score[s + q]);
+#pragma unroll
+    for (int m = 1; m < WAVE; m <<= 1) mx = fmaxf(mx, __shfl_xor(mx, m, WAVE));
+    float den = 0.f;
+    for (int q = lane; q < n; q += WAVE) den += __expf(scale * score[s + q] - mx);
+#pragma unroll
+    for (int m = 1; m < WAVE; m <<= 1) den += __shfl_xor(den, m, WAVE);
+    const float inv = 1.f / den;
+    for (int q = lane; q < n; q += WAVE) out[s + q] = (TO)(__expf(scale * score[s + q] - mx) * inv);
+}
+
+// Long rows (listed at plan time): one 256-thread workgroup per row.
+template <class TO>
+__global__ __launch_bounds__(256) void edge_softmax_long_kernel(const int32_t *rowptr, const int32_t *rows, const float *score, float scale, TO *out) {
+    __shared__ float red[4];
+    const int64_t i = rows[blockIdx.x];
+    const int s = rowptr[i], n = rowptr[i + 1] - s;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    float mx = -INFINITY;
+    for (int q = tid; q < n; q += 256) mx = fmaxf(mx, scale * score[s + q]);
+#pragma unroll
+    for (int m = 1; m < WAVE; m <<= 1) mx = fmaxf(mx, __shfl_xor(mx, m, WAVE));
+    if (lane == 0) red[wave] = mx;
+    __syncthreads();
+    mx = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    __syncthreads();
+    float den = 0.f;
+    for (int q = tid; q < n; q += 256) den += __expf(scale * score[s + q] - mx);
+#pragma unroll
+    for (int m = 1; m < WAVE; m <<= 1) den += __shfl_xor(den, m, WAVE);
+    if (lane == 0) red[wave] = den;
+    __syncthreads();
+    const float inv = 1.f / (red[0] + red[1] + red[2] + red[3]);
+    for (int q = tid; q < n; q += 256) out[s + q] = (TO)(__expf(scale * score[s + q] - mx) * inv);
 }
 
 // dst[i * stride + offset] (as T) = src[perm[i]]: new values into a packed array or into entry records
@@ -761,6 +830,8 @@ struct Staging {
 
 void layout(libra_plan_t *P, Uploader &u, Staging *st) {
     u.putv(P->rowptr, P->d_rowptr);
+    u.putv(P->long_rows, P->d_long_rows);
+    u.putv(P->medium_rows, P->d_medium_rows);
     SubPlan &sa = P->spmm, &sd = P->sddmm;
     const bool f16 = P->vdt == LIBRA_F16;
     // ---- SpMM ----
@@ -885,34 +956,24 @@ extern "C" int libra_sddmm(const libra_plan_t *P, const void *X, const void *Y, 
     SddmmArgs a{sp.dev.tasks, sp.dev.blk_cols, sp.dev.blk_bitmap, sp.dev.blk_valptr,
                 reinterpret_cast<const uint2 *>(sp.dev.dense_pv), (int32_t)sp.dense_perm.size(),
                 reinterpret_cast<const SdEnt *>(sp.dev.res_ent), X, Y, out, P->M};
-    // window tasks come first in the table, residual segments after them
-    const int64_t nw = sp.n_window_tasks, nc = sp.n_chunk_tasks;
-    if (nw > 0) {
-        if (P->vdt != LIBRA_F16) return LIBRA_ERR_UNSUPPORTED;
+    const int64_t nt = (int64_t)sp.tasks.size();
+    if (nt == 0) return LIBRA_OK;
+    if (sp.n_window_tasks > 0 && P->vdt != LIBRA_F16) return LIBRA_ERR_UNSUPPORTED;
+    const dim3 grid((unsigned)nt), block(WAVE);
+    if (P->vdt == LIBRA_F16) {
         switch (K) {
-        case 32: hipLaunchKernelGGL((sddmm_window_kernel<32>), dim3((unsigned)nw), dim3(WAVE), 0, s, a); break;
-        case 64: hipLaunchKernelGGL((sddmm_window_kernel<64>), dim3((unsigned)nw), dim3(WAVE), 0, s, a); break;
-        case 128: hipLaunchKernelGGL((sddmm_window_kernel<128>), dim3((unsigned)nw), dim3(WAVE), 0, s, a); break;
+        case 32: hipLaunchKernelGGL((sddmm_task_kernel<half_t, 32>), grid, block, 0, s, a); break;
+        case 64: hipLaunchKernelGGL((sddmm_task_kernel<half_t, 64>), grid, block, 0, s, a); break;
+        case 128: hipLaunchKernelGGL((sddmm_task_kernel<half_t, 128>), grid, block, 0, s, a); break;
         }
-        if (hipGetLastError() != hipSuccess) return LIBRA_ERR_HIP;
-    }
-    if (nc > 0) {
-        a.tasks = sp.dev.tasks + nw;
-        if (P->vdt == LIBRA_F16) {
-            switch (K) {
-            case 32: hipLaunchKernelGGL((sddmm_segment_kernel<half_t, 32>), dim3((unsigned)nc), dim3(WAVE), 0, s, a); break;
-            case 64: hipLaunchKernelGGL((sddmm_segment_kernel<half_t, 64>), dim3((unsigned)nc), dim3(WAVE), 0, s, a); break;
-            case 128: hipLaunchKernelGGL((sddmm_segment_kernel<half_t, 128>), dim3((unsigned)nc), dim3(WAVE), 0, s, a); break;
-            }
-        } else {
-            switch (K) {
-            case 32: hipLaunchKernelGGL((sddmm_segment_kernel<float, 32>), dim3((unsigned)nc), dim3(WAVE), 0, s, a); break;
-            case 64: hipLaunchKernelGGL((sddmm_segment_kernel<float, 64>), dim3((unsigned)nc), dim3(WAVE), 0, s, a); break;
-            case 128: hipLaunchKernelGGL((sddmm_segment_kernel<float, 128>), dim3((unsigned)nc), dim3(WAVE), 0, s, a); break;
-            }
+    } else {
+        switch (K) {
+        case 32: hipLaunchKernelGGL((sddmm_task_kernel<float, 32>), grid, block, 0, s, a); break;
+        case 64: hipLaunchKernelGGL((sddmm_task_kernel<float, 64>), grid, block, 0, s, a); break;
+        case 128: hipLaunchKernelGGL((sddmm_task_kernel<float, 128>), grid, block, 0, s, a); break;
         }
-        if (hipGetLastError() != hipSuccess) return LIBRA_ERR_HIP;
     }
+    if (hipGetLastError() != hipSuccess) return LIBRA_ERR_HIP;
     return LIBRA_OK;
 }
 
@@ -922,11 +983,18 @@ extern "C" int libra_edge_softmax(const libra_plan_t *P, const float *scores, fl
     if (out_dtype != LIBRA_F16 && out_dtype != LIBRA_F32) return LIBRA_ERR_DTYPE;
     if (!P->dev_base) return LIBRA_ERR_NOT_UPLOADED;
     hipStream_t s = (hipStream_t)stream;
-    const unsigned blocks = (unsigned)std::min<int64_t>((P->M + 3) / 4, 1 << 16);
-    if (out_dtype == LIBRA_F16)
-        hipLaunchKernelGGL((edge_softmax_kernel<half_t>), dim3(blocks), dim3(256), 0, s, P->d_rowptr, P->M, scores, scale, (half_t *)vals_out);
-    else
-        hipLaunchKernelGGL((edge_softmax_kernel<float>), dim3(blocks), dim3(256), 0, s, P->d_rowptr, P->M, scores, scale, (float *)vals_out);
+    if (P->nnz == 0) return LIBRA_OK;
+    const unsigned blocks = (unsigned)std::min<int64_t>((P->M + 15) / 16, 1 << 18);
+    const unsigned nlong = (unsigned)P->long_rows.size(), nmed = (unsigned)P->medium_rows.size();
+    if (out_dtype == LIBRA_F16) {
+        hipLaunchKernelGGL((edge_softmax_rows_kernel<half_t>), dim3(blocks), dim3(256), 0, s, P->d_rowptr, P->M, scores, scale, (half_t *)vals_out);
+        if (nmed) hipLaunchKernelGGL((edge_softmax_medium_kernel<half_t>), dim3((nmed + 3) / 4), dim3(256), 0, s, P->d_rowptr, P->d_medium_rows, (int)nmed, scores, scale, (half_t *)vals_out);
+        if (nlong) hipLaunchKernelGGL((edge_softmax_long_kernel<half_t>), dim3(nlong), dim3(256), 0, s, P->d_rowptr, P->d_long_rows, scores, scale, (half_t *)vals_out);
+    } else {
+        hipLaunchKernelGGL((edge_softmax_rows_kernel<float>), dim3(blocks), dim3(256), 0, s, P->d_rowptr, P->M, scores, scale, (float *)vals_out);
+        if (nmed) hipLaunchKernelGGL((edge_softmax_medium_kernel<float>), dim3((nmed + 3) / 4), dim3(256), 0, s, P->d_rowptr, P->d_medium_rows, (int)nmed, scores, scale, (float *)vals_out);
+        if (nlong) hipLaunchKernelGGL((edge_softmax_long_kernel<float>), dim3(nlong), dim3(256), 0, s, P->d_rowptr, P->d_long_rows, scores, scale, (float *)vals_out);
+    }
     return hip_rc(hipGetLastError());
 }
 

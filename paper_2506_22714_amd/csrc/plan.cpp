@@ -359,6 +359,12 @@ extern "C" int libra_plan(int64_t M, int64_t Kc, const int32_t *rowptr, const in
         P->M = M; P->Kc = Kc; P->nnz = nnz; P->vdt = val_dtype; P->vsize = val_dtype == LIBRA_F32 ? 4 : 2;
         P->o = o;
         P->rowptr.assign(rowptr, rowptr + M + 1);
+        for (int64_t i = 0; i < M; ++i)
+        {
+            const int32_t n = rowptr[i + 1] - rowptr[i];
+            if (n > LIBRA_SOFTMAX_LONG_ROW) P->long_rows.push_back((int32_t)i);
+            else if (n > 64) P->medium_rows.push_back((int32_t)i);
+        }
         Ctx c{M, nnz, rowptr, col, (const uint8_t *)val, P->vsize, o, (o.W * o.KB + 63) / 64};
         const int64_t nwin = (M + o.W - 1) / o.W;
         int nthr = o.threads ? o.threads : (int)std::thread::hardware_concurrency();

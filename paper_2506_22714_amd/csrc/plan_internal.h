@@ -7,6 +7,8 @@
 
 #include "libra.h"
 
+#define LIBRA_SOFTMAX_LONG_ROW 2048
+
 namespace libra {
 
 // Task record as the kernels read it (32 bytes).  SpMM: a decomposed-row segment is stored
@@ -85,10 +87,14 @@ struct libra_plan_s {
     int vsize = 2;
     libra::Resolved o{};
     std::vector<int32_t> rowptr;
+    std::vector<int32_t> long_rows;     // rows with more than LIBRA_SOFTMAX_LONG_ROW nonzeros (edge softmax)
+    std::vector<int32_t> medium_rows;   // rows with 65 .. LIBRA_SOFTMAX_LONG_ROW nonzeros
     libra::SubPlan spmm, sddmm;
     libra_stats_t stats{};
     // device copy
     void *dev_base = nullptr;
     size_t dev_bytes = 0;
     const int32_t *d_rowptr = nullptr;
+    const int32_t *d_long_rows = nullptr;
+    const int32_t *d_medium_rows = nullptr;
 };
