@@ -264,7 +264,7 @@ __global__ __launch_bounds__(WAVE) void spmm_task_kernel(SpmmArgs a) {
             tile_ready = true;
             constexpr int NT = N / 16;
             constexpr int PASSES = BPI * KB / RPW;               // wave loads per staged group of BPI blocks
-            constexpr int H = 1;                                 // staged groups per round trip (more costs registers, i.e. waves)
+            constexpr int H = N <= 128 ? 2 : 1;                  // staged groups per round trip (more costs registers, i.e. waves)
             constexpr int FPI = BPI * H;                         // blocks fetched per round trip
             static_assert(BPI * KB % RPW == 0 && PASSES >= 1, "stage shape");
             half_t *stage = reinterpret_cast<half_t *>(smem);
