@@ -235,15 +235,7 @@ __global__ __launch_bounds__(WAVE) void spmm_task_kernel(SpmmArgs a) {
 #pragma unroll
         for (int k = 0; k < ECAP / WAVE; ++k) ent_lds[k * WAVE + lane] = tmp[k];
     }
-    // later rounds of a task with more than ECAP entries / BCAP blocks are fetched in place
-    auto fetch_entries = [&](int e0, int nE) {
-        const ent_t *src = reinterpret_cast<const ent_t *>(a.res_ent) + t.res_begin + e0;
-        ent_t tmp[ECAP / WAVE];
-#pragma unroll
-        for (int k = 0; k < ECAP / WAVE; ++k) tmp[k] = E::load_ent(src, min(k * WAVE + lane, nE - 1));
-#pragma unroll
-        for (int k = 0; k < ECAP / WAVE; ++k) ent_lds[k * WAVE + lane] = tmp[k];
-    };
+    // later rounds of a task with more than BCAP blocks are fetched in place
     auto fetch_blocks = [&](int b0, int nb) {
         if constexpr (DENSE) {
             const int32_t *csrc = a.blk_cols + (int64_t)(t.blk_begin + b0) * KB;
@@ -379,10 +371,13 @@ __global__ __launch_bounds__(WAVE) void spmm_task_kernel(SpmmArgs a) {
     // ---- residual nonzeros, ECAP per round: equal contiguous runs per lane group, row sums flushed into the tile ----
     for (int e0 = 0; e0 < L; e0 += ECAP) {
         const int nE = min(ECAP, L - e0);
-        if (e0 > 0) {
-            wave_sync();
-            fetch_entries(e0, nE);
-            wave_sync();
+        // the next round's entries go in flight now and wait in registers until this round is done
+        const int nE_next = min(ECAP, L - e0 - ECAP);
+        ent_t next_ent[ECAP / WAVE];
+        if (nE_next > 0) {
+            const ent_t *src = reinterpret_cast<const ent_t *>(a.res_ent) + t.res_begin + e0 + ECAP;
+#pragma unroll
+            for (int k = 0; k < ECAP / WAVE; ++k) next_ent[k] = E::load_ent(src, min(k * WAVE + lane, nE_next - 1));
         }
         const int per = (nE + RPW - 1) / RPW;
         const int q0 = grp * per;
@@ -463,6 +458,12 @@ __global__ __launch_bounds__(WAVE) void spmm_task_kernel(SpmmArgs a) {
         for (int gq = 1; gq < RPW; ++gq) {
             wave_sync();
             if (grp == gq && kept_row >= 0) add_to_tile(kept_row, kept);
+        }
+        if (nE_next > 0) {
+            wave_sync();
+#pragma unroll
+            for (int k = 0; k < ECAP / WAVE; ++k) ent_lds[k * WAVE + lane] = next_ent[k];
+            wave_sync();
         }
     }
     wave_sync();
