@@ -15,3 +15,13 @@ def pytest_configure(config):
 @pytest.fixture(scope="session")
 def golden_dir():
     return os.path.join(ROOT, "tests", "golden")
+
+
+@pytest.fixture(scope="session", autouse=True)
+def built_library():
+    """The tests load the in-tree library; it is compiled here only if nothing has been built yet."""
+    from paper_2506_22714_amd import binding as lb
+    if not os.path.exists(lb.LIB_PATH):
+        from paper_2506_22714_amd.build import build_library
+        build_library()
+    return lb.lib()

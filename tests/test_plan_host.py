@@ -14,14 +14,6 @@ from paper_2506_22714_amd import workloads as wl
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-@pytest.fixture(scope="session", autouse=True)
-def built_library():
-    if not os.path.exists(lb.LIB_PATH):
-        from paper_2506_22714_amd.build import build_library
-        build_library()
-    return lb.lib()
-
-
 def test_library_exports_every_declared_symbol(built_library):
     names = set()
     for fn in os.listdir(os.path.join(ROOT, "include")):
