@@ -58,6 +58,7 @@ def main() -> int:
     ap.add_argument("--ts", type=int, default=0)
     ap.add_argument("--cs", type=int, default=0)
     ap.add_argument("--natural-order", action="store_true")
+    ap.add_argument("--dtype", default="f16", choices=["f16", "bf16"], help="storage type of A's values and the dense operands")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run only a 1 GiB device copy (5 times): the known-size kernel that scales the rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE readings")
@@ -94,8 +95,10 @@ def main() -> int:
     X = wl.dense_normal(A.M, K, seed=wl.BASE_SEED + 202)
     Y = wl.dense_normal(A.Kc, K, seed=wl.BASE_SEED + 203)
 
+    bf16 = args.dtype == "bf16"
+    val = wl.to_bf16_bits(A.val.astype(np.float32)) if bf16 else None
     t0 = time.perf_counter()
-    plan = lb.Plan.from_csr(A, mode=args.mode, spmm_min_vec_nnz=args.tau_spmm, sddmm_min_blk_nnz=args.tau_sddmm,
+    plan = lb.Plan.from_csr(A, val=val, val_dtype=lb.BF16 if bf16 else None, mode=args.mode, spmm_min_vec_nnz=args.tau_spmm, sddmm_min_blk_nnz=args.tau_sddmm,
                             ts=args.ts, cs=args.cs, flags=lb.FLAG_NATURAL_ORDER if args.natural_order else 0)
     plan_s = time.perf_counter() - t0
     t0 = time.perf_counter()
@@ -103,7 +106,11 @@ def main() -> int:
     upload_s = time.perf_counter() - t0
     st = plan.stats()
 
-    Bd, Xd, Yd = (torch.from_numpy(a).cuda() for a in (B, X, Y))
+    if bf16:
+        B, X, Y = (wl.to_bf16_bits(a.astype(np.float32)) for a in (B, X, Y))
+        Bd, Xd, Yd = (torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16) for a in (B, X, Y))
+    else:
+        Bd, Xd, Yd = (torch.from_numpy(a).cuda() for a in (B, X, Y))
     Cd = torch.empty((A.M, N), dtype=torch.float32, device="cuda")
     od = torch.empty(A.nnz, dtype=torch.float32, device="cuda")
 
@@ -129,6 +136,33 @@ def main() -> int:
     spmm_ms = np.array([e[0].elapsed_time(e[1]) for e in ev])
     sddmm_ms = np.array([e[1].elapsed_time(e[2]) for e in ev])
 
+    # Cold calls (a 1 GiB buffer is streamed between calls, which evicts L2 and the 256 MB Infinity Cache) and the
+    # streaming-copy rate of this machine; both after the timed region, so they do not disturb it.
+    scratch = torch.zeros(1 << 28, dtype=torch.float32, device="cuda")
+    n_cold = 15
+    cev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(n_cold)]
+    for i in range(n_cold):
+        scratch.add_(1.0)
+        cev[i][0].record()
+        plan.spmm(Bd, out=Cd)
+        cev[i][1].record()
+        scratch.add_(1.0)
+        cev[i][2].record()
+        plan.sddmm(Xd, Yd, out=od)
+        cev[i][3].record()
+    torch.cuda.synchronize()
+    spmm_cold = np.array([e[0].elapsed_time(e[1]) for e in cev[2:]])
+    sddmm_cold = np.array([e[2].elapsed_time(e[3]) for e in cev[2:]])
+    dst = torch.empty_like(scratch)
+    kev = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(8)]
+    for i in range(8):
+        kev[i][0].record()
+        dst.copy_(scratch)
+        kev[i][1].record()
+    torch.cuda.synchronize()
+    copy_gbs = 2.0 * scratch.numel() * 4 / (float(np.median([e[0].elapsed_time(e[1]) for e in kev[2:]])) * 1e-3) / 1e9
+    del scratch, dst
+
     flops_spmm = 2.0 * A.nnz * N
     flops_sddmm = 2.0 * A.nnz * K
     value = (flops_spmm + flops_sddmm) / (ms_per_step * 1e-3) / 1e9
@@ -139,7 +173,7 @@ def main() -> int:
     bytes_sddmm = sddmm_algorithmic_bytes(A, K, mref, kref)
     spmm_avg_s = float(spmm_ms.mean()) * 1e-3
     achieved = bytes_spmm / spmm_avg_s / 1e9
-    default_cfg = (not args.small and args.mode == 0 and not (args.tau_spmm or args.tau_sddmm or args.ts or args.cs)
+    default_cfg = (not args.small and not bf16 and args.mode == 0 and not (args.tau_spmm or args.tau_sddmm or args.ts or args.cs)
                    and not args.natural_order)
     traffic = MEASURED_TRAFFIC_BYTES.get((args.workload, N)) if default_cfg else None
 
@@ -154,19 +188,23 @@ def main() -> int:
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "f16 (f32 accumulate)",
+        "dtype": f"{args.dtype} (f32 accumulate)",
         "data": "synthetic",
         "config": {"workload": f"{args.workload}{'-small' if args.small else ''}: M={A.M} nnz={A.nnz} SpMM N={N} + SDDMM K={K}",
                    "M": A.M, "nnz": A.nnz, "N": N, "K": K, "mode": args.mode,
                    "tau_spmm": args.tau_spmm or 3, "tau_sddmm": args.tau_sddmm or 32},
-        "roofline": {"bound": "hbm", "kernel": f"spmm_task_kernel<f16,{min(N, 256)}>", "achieved": round(achieved, 1),
+        "roofline": {"bound": "hbm", "kernel": f"spmm_task_kernel<{args.dtype},{min(N, 256)}>", "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
-                     "algorithmic_bytes": bytes_spmm, "avg_us": round(spmm_avg_s * 1e6, 2)},
+                     "algorithmic_bytes": bytes_spmm, "avg_us": round(spmm_avg_s * 1e6, 2),
+                     "frac_of_measured_copy": round(achieved / copy_gbs, 4), "measured_copy_GBs": round(copy_gbs, 1),
+                     "modelled_gather_GBs": round((st["spmm_gather_rows"] * N * 2 + A.nnz * 6 + A.M * N * 4)
+                                                  / spmm_avg_s / 1e9, 1)},
         "spmm": {"gflops": round(flops_spmm / spmm_avg_s / 1e9, 1), "median_us": round(float(np.median(spmm_ms)) * 1e3, 2),
-                 "min_us": round(float(spmm_ms.min()) * 1e3, 2), "bytes": bytes_spmm},
+                 "min_us": round(float(spmm_ms.min()) * 1e3, 2), "cold_median_us": round(float(np.median(spmm_cold)) * 1e3, 2),
+                 "bytes": bytes_spmm},
         "sddmm": {"gflops": round(flops_sddmm / (float(sddmm_ms.mean()) * 1e-3) / 1e9, 1),
                   "median_us": round(float(np.median(sddmm_ms)) * 1e3, 2), "min_us": round(float(sddmm_ms.min()) * 1e3, 2),
-                  "bytes": bytes_sddmm,
+                  "cold_median_us": round(float(np.median(sddmm_cold)) * 1e3, 2), "bytes": bytes_sddmm,
                   "hbm_frac": round(bytes_sddmm / (float(sddmm_ms.mean()) * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)},
         "plan": {"plan_s": round(plan_s, 4), "upload_s": round(upload_s, 4),
                  "spmm_dense_share": round(st["spmm_dense_nnz"] / max(A.nnz, 1), 4),
@@ -180,10 +218,10 @@ def main() -> int:
         import oracle
         nt = oracle.max_threads()
         t0 = time.perf_counter()
-        oracle.spmm(A.rowptr, A.col, A.val, B, want_scale=False)
+        oracle.spmm(A.rowptr, A.col, A.val if val is None else val, B, want_scale=False, bf16=bf16)
         t_sp = time.perf_counter() - t0
         t0 = time.perf_counter()
-        oracle.sddmm(A.rowptr, A.col, A.val, X, Y, want_scale=False)
+        oracle.sddmm(A.rowptr, A.col, A.val if val is None else val, X, Y, want_scale=False, bf16=bf16)
         t_sd = time.perf_counter() - t0
         out["cpu_baseline"] = {"value": round((flops_spmm + flops_sddmm) / (t_sp + t_sd) / 1e9, 2), "unit": "GFLOP/s",
                                "cores": nt, "kind": "oracle",

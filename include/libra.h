@@ -55,7 +55,7 @@ extern "C" {
 
 /* ---- value types (storage type of A's values and of the dense operands) ---- */
 #define LIBRA_F16   0    /* IEEE binary16 in, fp32 accumulate (MFMA + VALU) */
-#define LIBRA_BF16  1    /* reserved; not yet accepted */
+#define LIBRA_BF16  1    /* bfloat16 in, fp32 accumulate (MFMA + VALU); beside the paper's FP16 / TF32 inputs (Section 4.4) */
 #define LIBRA_F32   2    /* binary32 in, fp32 accumulate; scalar (VALU) path only */
 
 /* ---- distribution modes (Section 5.3.2: matrix-unit-only, scalar-only, hybrid) ---- */
@@ -148,7 +148,7 @@ typedef struct {
  *   M, Kc        in   matrix shape, 1 <= M, Kc < 2^31
  *   rowptr       in   host, int32[M+1], rowptr[0] = 0, non-decreasing, rowptr[M] = nnz < 2^31
  *   col          in   host, int32[nnz], strictly increasing inside each row, 0 <= col < Kc
- *   val          in   host, nnz values of type val_dtype (LIBRA_F16 or LIBRA_F32).  LIBRA_F32 forces
+ *   val          in   host, nnz values of type val_dtype (LIBRA_F16, LIBRA_BF16 or LIBRA_F32).  LIBRA_F32 forces
  *                     LIBRA_MODE_SCALAR_ONLY (CDNA4 has no reduced-precision-free fp32 matrix path worth using).
  *   opts         in   host, may be NULL (all defaults)
  *   out          out  receives a new plan; release with libra_plan_destroy.  The inputs are copied,
@@ -199,7 +199,8 @@ int libra_sddmm(const libra_plan_t *plan, const void *X, const void *Y, int32_t 
  * libra_edge_softmax - row-wise softmax over CSR-ordered scores (the step between SDDMM and SpMM in an
  * attention layer, Section 5.5): vals_out[p] = exp(scale*s[p] - mx_i) / sum_row exp(scale*s[q] - mx_i).
  *   scores    device, fp32[nnz], CSR order
- *   vals_out  device, nnz values of out_dtype (LIBRA_F16 or LIBRA_F32), CSR order; may not alias scores
+ *   vals_out  device, nnz values of out_dtype (LIBRA_F16, LIBRA_BF16 or LIBRA_F32; rounded to nearest even), CSR order;
+ *             may not alias scores
  * Errors: NULL, DTYPE, NOT_UPLOADED, HIP.
  */
 int libra_edge_softmax(const libra_plan_t *plan, const float *scores, float scale,

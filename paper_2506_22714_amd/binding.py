@@ -194,7 +194,7 @@ def libra_plan_export(plan, which: int) -> dict:
     """Copies of one sub-plan's host arrays as numpy arrays (0 = SpMM, 1 = SDDMM)."""
     v = SubplanView()
     _check(lib().libra_plan_export(plan, which, C.byref(v)), "libra_plan_export")
-    vt = np.float16 if v.value_dtype == F16 else np.float32
+    vt = {F16: np.float16, BF16: np.uint16, F32: np.float32}[v.value_dtype]      # bfloat16 comes back as bit patterns
     nb, KB, wpb = v.n_blocks, v.block_cols, v.words_per_block
     out = dict(n_windows=v.n_windows, n_blocks=nb, n_dense_nnz=v.n_dense_nnz, n_res_nnz=v.n_res_nnz,
                n_tasks=v.n_tasks, window_rows=v.window_rows, block_cols=KB, words_per_block=wpb,
@@ -223,16 +223,18 @@ def libra_plan_stats(plan) -> dict:
 
 # ---- convenience wrapper: a plan handle plus the torch buffer that backs its device copy ----
 class Plan:
-    def __init__(self, M, Kc, rowptr, col, val, **opts):
+    def __init__(self, M, Kc, rowptr, col, val, val_dtype: int | None = None, **opts):
+        """`val_dtype=BF16` with `val` as uint16 bit patterns builds a bfloat16 plan (numpy has no such type)."""
         self.M, self.Kc = int(M), int(Kc)
-        self.val_dtype = _np_dtype_code(np.asarray(val))
-        self.handle = libra_plan(self.M, self.Kc, rowptr, col, val, PlanOpts(**opts) if opts else None)
+        self.val_dtype = _np_dtype_code(np.asarray(val)) if val_dtype is None else int(val_dtype)
+        self.handle = libra_plan(self.M, self.Kc, rowptr, col, val, PlanOpts(**opts) if opts else None,
+                                 val_dtype=self.val_dtype)
         self.nnz = libra_plan_stats(self.handle)["nnz"]
         self._buf = None
 
     @classmethod
-    def from_csr(cls, csr, val=None, **opts):
-        return cls(csr.M, csr.Kc, csr.rowptr, csr.col, csr.val if val is None else val, **opts)
+    def from_csr(cls, csr, val=None, val_dtype: int | None = None, **opts):
+        return cls(csr.M, csr.Kc, csr.rowptr, csr.col, csr.val if val is None else val, val_dtype=val_dtype, **opts)
 
     def close(self):
         if self.handle is not None:
@@ -261,7 +263,7 @@ class Plan:
 
     def _torch_dtype(self):
         import torch
-        return torch.float16 if self.val_dtype == F16 else torch.float32
+        return {F16: torch.float16, BF16: torch.bfloat16, F32: torch.float32}[self.val_dtype]
 
     def spmm(self, B, out=None):
         import torch
@@ -290,7 +292,7 @@ class Plan:
         assert scores.is_cuda and scores.dtype == torch.float32 and scores.is_contiguous()
         if out is None:
             out = torch.empty(self.nnz, dtype=self._torch_dtype(), device=scores.device)
-        code = F16 if out.dtype == torch.float16 else F32
+        code = {torch.float16: F16, torch.bfloat16: BF16, torch.float32: F32}[out.dtype]
         libra_edge_softmax(self.handle, scores.data_ptr(), scale, out.data_ptr(), code,
                            torch.cuda.current_stream().cuda_stream)
         return out

@@ -32,6 +32,9 @@ typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
 typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
 typedef float float4_t __attribute__((ext_vector_type(4)));
 typedef short short4_t __attribute__((ext_vector_type(4)));
+typedef short short8_t __attribute__((ext_vector_type(8)));
+typedef __bf16 bf8_t __attribute__((ext_vector_type(8)));
+struct bf16_t { uint16_t bits; };     // bfloat16 storage: the upper half of a binary32
 
 namespace {
 
@@ -108,6 +111,29 @@ template <> struct Elem<half_t> {
         return (float)h;
     }
 };
+template <> struct Elem<bf16_t> : Elem<half_t> {
+    // same 16-byte pieces and entry records as binary16; only the widening differs (a shift)
+    __device__ static float widen(uint32_t bits16) { return __uint_as_float(bits16 << 16); }
+    __device__ static void fma(float v, const raw_t &r, float (&acc)[8]) {
+        const uint32_t w[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            acc[2 * e] = fmaf(v, __uint_as_float(w[e] << 16), acc[2 * e]);
+            acc[2 * e + 1] = fmaf(v, __uint_as_float(w[e] & 0xffff0000u), acc[2 * e + 1]);
+        }
+    }
+    __device__ static float dot(const raw_t &x, const raw_t &y, float s) {
+        const uint32_t a[4] = {x.x, x.y, x.z, x.w}, b[4] = {y.x, y.y, y.z, y.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            s = fmaf(__uint_as_float(a[e] << 16), __uint_as_float(b[e] << 16), s);
+            s = fmaf(__uint_as_float(a[e] & 0xffff0000u), __uint_as_float(b[e] & 0xffff0000u), s);
+        }
+        return s;
+    }
+    __device__ static float ent_val(const ent_t &e) { return widen(e.val); }
+    __device__ static float word_val(uint32_t bits) { return widen(bits & 0xffffu); }
+};
 template <> struct Elem<float> {
     static constexpr int PER_LANE = 4;                   // 16 bytes
     typedef float4_t raw_t;
@@ -157,6 +183,41 @@ __device__ inline void global_add(float *p, float v) {
     __hip_atomic_fetch_add(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+// One 16x16 tile step on the matrix cores for either 16-bit storage type; operands are passed as raw bits.
+template <class T>
+__device__ inline float4_t mfma_k16(short4_t a, short4_t b, float4_t c) {
+    if constexpr (std::is_same<T, half_t>::value) {
+        half4_t ha, hb;
+        __builtin_memcpy(&ha, &a, 8);
+        __builtin_memcpy(&hb, &b, 8);
+        return __builtin_amdgcn_mfma_f32_16x16x16f16(ha, hb, c, 0, 0, 0);
+    } else {
+        return __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a, b, c, 0, 0, 0);
+    }
+}
+template <class T>
+__device__ inline float4_t mfma_k32(const uint4 &a, const uint4 &b, float4_t c) {
+    if constexpr (std::is_same<T, half_t>::value) {
+        half8_t ha, hb;
+        __builtin_memcpy(&ha, &a, 16);
+        __builtin_memcpy(&hb, &b, 16);
+        return __builtin_amdgcn_mfma_f32_16x16x32_f16(ha, hb, c, 0, 0, 0);
+    } else {
+        bf8_t ba, bb;
+        __builtin_memcpy(&ba, &a, 16);
+        __builtin_memcpy(&bb, &b, 16);
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(ba, bb, c, 0, 0, 0);
+    }
+}
+// fp32 -> storage type of the softmax output (round to nearest even)
+template <class TO> __device__ inline TO to_storage(float x) { return (TO)x; }
+template <> __device__ inline bf16_t to_storage<bf16_t>(float x) {
+    uint32_t u = __float_as_uint(x);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return bf16_t{(uint16_t)((u >> 16) | 0x40u)};      // NaN stays NaN
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return bf16_t{(uint16_t)(u >> 16)};
+}
+
 // ---------------------------------------------------------------------------------------
 // SpMM.  N = feature columns handled by this launch, T = storage type of values and B.
 //
@@ -181,7 +242,7 @@ template <class T, int N>
 __global__ __launch_bounds__(WAVE) void spmm_task_kernel(SpmmArgs a) {
     using E = Elem<T>;
     typedef typename E::ent_t ent_t;
-    constexpr bool DENSE = std::is_same<T, half_t>::value;
+    constexpr bool DENSE = !std::is_same<T, float>::value;     // 16-bit storage: the matrix-core path exists
     constexpr int PL = E::PER_LANE;          // elements of a row per lane
     constexpr int LPR = N / PL;              // lanes per row
     constexpr int RPW = WAVE / LPR;          // lane groups per wave
@@ -259,7 +320,7 @@ __global__ __launch_bounds__(WAVE) void spmm_task_kernel(SpmmArgs a) {
             constexpr int H = N <= 128 ? 2 : 1;                  // staged groups per round trip (more costs registers, i.e. waves)
             constexpr int FPI = BPI * H;                         // blocks fetched per round trip
             static_assert(BPI * KB % RPW == 0 && PASSES >= 1, "stage shape");
-            half_t *stage = reinterpret_cast<half_t *>(smem);
+            uint16_t *stage = reinterpret_cast<uint16_t *>(smem);
             const int g = lane >> 4, j = lane & 15;
             float4_t acc[NT];
 #pragma unroll
@@ -286,14 +347,14 @@ __global__ __launch_bounds__(WAVE) void spmm_task_kernel(SpmmArgs a) {
                             // (so that it keeps the fetch outside any branch)
                             uint32_t keep = (k < nb * KB && c >= 0) ? 0xffffffffu : 0u;
                             asm volatile("" : "+v"(keep));
-                            raw[h][ps] = Elem<half_t>::load_row(a.B, keep ? c : 0, ldb_bytes, sub);
+                            raw[h][ps] = E::load_row(a.B, keep ? c : 0, ldb_bytes, sub);
                             raw[h][ps].x &= keep; raw[h][ps].y &= keep; raw[h][ps].z &= keep; raw[h][ps].w &= keep;
                         }
                     // ... and this lane's 4 A elements (row j, slots 4g..4g+3) of each block, decoded from its bitmap
-                    half4_t af[FPI];
+                    short4_t af[FPI];
 #pragma unroll
                     for (int x = 0; x < FPI; ++x) {
-                        af[x] = half4_t{(half_t)0, (half_t)0, (half_t)0, (half_t)0};
+                        af[x] = short4_t{0, 0, 0, 0};
                         if (x < nb) {
                             const uint64_t *bm = &bm_lds[(bb + x) * 4];
                             const uint64_t w0 = bm[0], w1 = bm[1], w2 = bm[2], w3 = bm[3];
@@ -304,14 +365,14 @@ __global__ __launch_bounds__(WAVE) void spmm_task_kernel(SpmmArgs a) {
                             const int bitpos = (j & 3) * 16 + 4 * g;
                             prefix += __popcll(word & ((1ull << bitpos) - 1ull));
                             const unsigned nib = (unsigned)(word >> bitpos) & 0xFu;
-                            const half_t *vals = reinterpret_cast<const half_t *>(a.dense_val) + vbase + prefix;
+                            const short *vals = reinterpret_cast<const short *>(a.dense_val) + vbase + prefix;
                             // unconditional loads (an unset slot reads a neighbouring value, at most 3 halves past the
                             // array's end, inside its 16 spare bytes) and a select afterwards
-                            half_t av[4];
+                            short av[4];
 #pragma unroll
                             for (int e = 0; e < 4; ++e) av[e] = vals[__popc(nib & ((1u << e) - 1u))];
 #pragma unroll
-                            for (int e = 0; e < 4; ++e) af[x][e] = (nib >> e & 1u) ? av[e] : (half_t)0;
+                            for (int e = 0; e < 4; ++e) af[x][e] = (nib >> e & 1u) ? av[e] : (short)0;
                             vbase += c0 + c1 + c2 + c3;
                         }
                     }
@@ -331,14 +392,12 @@ __global__ __launch_bounds__(WAVE) void spmm_task_kernel(SpmmArgs a) {
                                 if (h * BPI + x < nb) {
                                     // lane i of a 16-lane block points at row i/4, halves 4(i%4)..+3 of the 32-byte row piece;
                                     // the transposing read hands lane j the four rows' element j: B[4g+e][16n+j], e = 0..3
-                                    const half_t *src = &stage[(x * KB + 4 * g + (j >> 2)) * LDBS + 4 * (j & 3)];
+                                    const uint16_t *src = &stage[(x * KB + 4 * g + (j >> 2)) * LDBS + 4 * (j & 3)];
 #pragma unroll
                                     for (int n = 0; n < NT; ++n) {
                                         const short4_t r = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
                                             (short4_t __attribute__((address_space(3))) *)(src + 16 * n));
-                                        half4_t bf;
-                                        __builtin_memcpy(&bf, &r, 8);
-                                        acc[n] = __builtin_amdgcn_mfma_f32_16x16x16f16(af[h * BPI + x], bf, acc[n], 0, 0, 0);
+                                        acc[n] = mfma_k16<T>(af[h * BPI + x], r, acc[n]);
                                     }
                                 }
                             }
@@ -535,19 +594,19 @@ __device__ inline float group_sum(float s) {
 // Blocks are handled BB at a time so that each dependent step (column ids and bitmaps; Y rows;
 // value/position records) is one batch of loads for the whole group.  All loads are unconditional
 // from clamped addresses; only the final stores are predicated.
-template <int K>
+template <class T, int K>
 __device__ inline void sddmm_window_task(const SddmmArgs &a, const DevTask &t) {
     constexpr int KS = K / 32;               // MFMA k-steps
     constexpr int BB = K <= 64 ? 4 : 2;      // blocks per batch
     const int lane = threadIdx.x;
     const int g = lane >> 4, j = lane & 15;
-    const half_t *X = reinterpret_cast<const half_t *>(a.X);
-    const half_t *Y = reinterpret_cast<const half_t *>(a.Y);
+    const uint16_t *X = reinterpret_cast<const uint16_t *>(a.X);
+    const uint16_t *Y = reinterpret_cast<const uint16_t *>(a.Y);
     // A operand: row j of the window, k = 32*s + 8g .. +7 (rows past M repeat the last row; never sampled)
     const int64_t xr = min((int64_t)t.id * W + j, a.M - 1);
-    half8_t xa[KS];
+    uint4 xa[KS];
 #pragma unroll
-    for (int s = 0; s < KS; ++s) xa[s] = *reinterpret_cast<const half8_t *>(X + xr * K + 32 * s + 8 * g);
+    for (int s = 0; s < KS; ++s) xa[s] = *reinterpret_cast<const uint4 *>(X + xr * K + 32 * s + 8 * g);
     for (int b0 = t.blk_begin; b0 < t.blk_end; b0 += BB) {
         int col[BB], vptr[BB];
         uint64_t word[BB];
@@ -558,12 +617,12 @@ __device__ inline void sddmm_window_task(const SddmmArgs &a, const DevTask &t) {
             word[x] = a.blk_bitmap[(int64_t)b * 4 + g];          // rows 4g..4g+3 of the block, bit e*16 + j
             vptr[x] = a.blk_valptr[b];
         }
-        half8_t yb[BB][KS];
+        uint4 yb[BB][KS];
 #pragma unroll
         for (int x = 0; x < BB; ++x) {
             const int c = max(col[x], 0);                        // padding slot: no bit is set in its column
 #pragma unroll
-            for (int s = 0; s < KS; ++s) yb[x][s] = *reinterpret_cast<const half8_t *>(Y + (int64_t)c * K + 32 * s + 8 * g);
+            for (int s = 0; s < KS; ++s) yb[x][s] = *reinterpret_cast<const uint4 *>(Y + (int64_t)c * K + 32 * s + 8 * g);
         }
         // where each of this lane's (up to 4 per block) outputs sits among the block's packed values
         int slot[BB][4];
@@ -586,14 +645,14 @@ __device__ inline void sddmm_window_task(const SddmmArgs &a, const DevTask &t) {
         for (int x = 0; x < BB; ++x) {
             d[x] = float4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int s = 0; s < KS; ++s) d[x] = __builtin_amdgcn_mfma_f32_16x16x32_f16(xa[s], yb[x][s], d[x], 0, 0, 0);
+            for (int s = 0; s < KS; ++s) d[x] = mfma_k32<T>(xa[s], yb[x][s], d[x]);
         }
 #pragma unroll
         for (int x = 0; x < BB; ++x)
 #pragma unroll
             for (int e = 0; e < 4; ++e)
                 if (b0 + x < t.blk_end && (word[x] >> (e * 16 + j) & 1ull))
-                    a.out[(int32_t)pv[x][e].x] = Elem<half_t>::word_val(pv[x][e].y) * d[x][e];
+                    a.out[(int32_t)pv[x][e].x] = Elem<T>::word_val(pv[x][e].y) * d[x][e];
     }
 }
 
@@ -632,9 +691,9 @@ __device__ inline void sddmm_segment_task(const SddmmArgs &a, const DevTask &t) 
 template <class T, int K>
 __global__ __launch_bounds__(WAVE) void sddmm_task_kernel(SddmmArgs a) {
     const DevTask t = a.tasks[blockIdx.x];
-    if constexpr (std::is_same<T, half_t>::value) {
+    if constexpr (!std::is_same<T, float>::value) {
         if (t.kind == LIBRA_TASK_WINDOW) {
-            sddmm_window_task<K>(a, t);
+            sddmm_window_task<T, K>(a, t);
             return;
         }
     }
@@ -681,7 +740,7 @@ __global__ __launch_bounds__(256) void edge_softmax_rows_kernel(const int32_t *r
             const float inv = 1.f / group_sum<16>(den);
 #pragma unroll
             for (int k = 0; k < 4; ++k)
-                if (l + 16 * k < n) out[s + l + 16 * k] = (TO)(ex[k] * inv);
+                if (l + 16 * k < n) out[s + l + 16 * k] = to_storage<TO>(ex[k] * inv);
         }
     }
 }
@@ -703,7 +762,7 @@ __global__ __launch_bounds__(256) void edge_softmax_medium_kernel(const int32_t 
 #pragma unroll
     for (int m = 1; m < WAVE; m <<= 1) den += __shfl_xor(den, m, WAVE);
     const float inv = 1.f / den;
-    for (int q = lane; q < n; q += WAVE) out[s + q] = (TO)(__expf(scale * score[s + q] - mx) * inv);
+    for (int q = lane; q < n; q += WAVE) out[s + q] = to_storage<TO>(__expf(scale * score[s + q] - mx) * inv);
 }
 
 // Long rows (listed at plan time): one 256-thread workgroup per row.
@@ -728,7 +787,7 @@ __global__ __launch_bounds__(256) void edge_softmax_long_kernel(const int32_t *r
     if (lane == 0) red[wave] = den;
     __syncthreads();
     const float inv = 1.f / (red[0] + red[1] + red[2] + red[3]);
-    for (int q = tid; q < n; q += 256) out[s + q] = (TO)(__expf(scale * score[s + q] - mx) * inv);
+    for (int q = tid; q < n; q += 256) out[s + q] = to_storage<TO>(__expf(scale * score[s + q] - mx) * inv);
 }
 
 // dst[i * stride + offset] (as T) = src[perm[i]]: new values into a packed array or into entry records
@@ -764,6 +823,13 @@ int spmm_piece(const libra_plan_t *P, const void *B, int n, int64_t ldb, float *
         case 64: return launch_spmm<half_t, 64>(a, nt, s);
         case 128: return launch_spmm<half_t, 128>(a, nt, s);
         case 256: return launch_spmm<half_t, 256>(a, nt, s);
+        }
+    } else if (P->vdt == LIBRA_BF16) {
+        switch (n) {
+        case 32: return launch_spmm<bf16_t, 32>(a, nt, s);
+        case 64: return launch_spmm<bf16_t, 64>(a, nt, s);
+        case 128: return launch_spmm<bf16_t, 128>(a, nt, s);
+        case 256: return launch_spmm<bf16_t, 256>(a, nt, s);
         }
     } else {
         switch (n) {
@@ -834,7 +900,7 @@ void layout(libra_plan_t *P, Uploader &u, Staging *st) {
     u.putv(P->long_rows, P->d_long_rows);
     u.putv(P->medium_rows, P->d_medium_rows);
     SubPlan &sa = P->spmm, &sd = P->sddmm;
-    const bool f16 = P->vdt == LIBRA_F16;
+    const bool f16 = P->vdt != LIBRA_F32;      // 16-bit storage (binary16 or bfloat16): same records
     // ---- SpMM ----
     if (st) st->tasks_a = pack_tasks(P, sa, true);
     u.put(st ? (const void *)st->tasks_a.data() : nullptr, sa.tasks.size() * sizeof(DevTask), sa.dev.tasks);
@@ -924,11 +990,11 @@ extern "C" int libra_spmm(const libra_plan_t *P, const void *B, int32_t N, int64
     if (!P->o.build_spmm) return LIBRA_ERR_NOT_BUILT;
     if (!P->dev_base) return LIBRA_ERR_NOT_UPLOADED;
     if (P->o.W != W || P->o.KB != KB) return LIBRA_ERR_UNSUPPORTED;
-    const int unit = P->vdt == LIBRA_F16 ? 32 : 16;
+    const int unit = P->vdt != LIBRA_F32 ? 32 : 16;
     if (N < unit || N > 512) return LIBRA_ERR_SHAPE;
     if (N % unit) return LIBRA_ERR_UNSUPPORTED;
     if (ldb < N || ldc < N || ldb > (1ll << 30)) return LIBRA_ERR_SHAPE;
-    if (ldb % (P->vdt == LIBRA_F16 ? 8 : 4) || ldc % 4) return LIBRA_ERR_UNSUPPORTED;
+    if (ldb % (P->vdt != LIBRA_F32 ? 8 : 4) || ldc % 4) return LIBRA_ERR_UNSUPPORTED;
     if (((uintptr_t)B & 15) || ((uintptr_t)C & 15)) return LIBRA_ERR_BUFFER;
     hipStream_t s = (hipStream_t)stream;
     const int esz = P->vsize;
@@ -959,13 +1025,19 @@ extern "C" int libra_sddmm(const libra_plan_t *P, const void *X, const void *Y, 
                 reinterpret_cast<const SdEnt *>(sp.dev.res_ent), X, Y, out, P->M};
     const int64_t nt = (int64_t)sp.tasks.size();
     if (nt == 0) return LIBRA_OK;
-    if (sp.n_window_tasks > 0 && P->vdt != LIBRA_F16) return LIBRA_ERR_UNSUPPORTED;
+    if (sp.n_window_tasks > 0 && P->vdt == LIBRA_F32) return LIBRA_ERR_UNSUPPORTED;
     const dim3 grid((unsigned)nt), block(WAVE);
     if (P->vdt == LIBRA_F16) {
         switch (K) {
         case 32: hipLaunchKernelGGL((sddmm_task_kernel<half_t, 32>), grid, block, 0, s, a); break;
         case 64: hipLaunchKernelGGL((sddmm_task_kernel<half_t, 64>), grid, block, 0, s, a); break;
         case 128: hipLaunchKernelGGL((sddmm_task_kernel<half_t, 128>), grid, block, 0, s, a); break;
+        }
+    } else if (P->vdt == LIBRA_BF16) {
+        switch (K) {
+        case 32: hipLaunchKernelGGL((sddmm_task_kernel<bf16_t, 32>), grid, block, 0, s, a); break;
+        case 64: hipLaunchKernelGGL((sddmm_task_kernel<bf16_t, 64>), grid, block, 0, s, a); break;
+        case 128: hipLaunchKernelGGL((sddmm_task_kernel<bf16_t, 128>), grid, block, 0, s, a); break;
         }
     } else {
         switch (K) {
@@ -981,21 +1053,22 @@ extern "C" int libra_sddmm(const libra_plan_t *P, const void *X, const void *Y, 
 extern "C" int libra_edge_softmax(const libra_plan_t *P, const float *scores, float scale, void *vals_out, int out_dtype, void *stream) {
     if (!P) return LIBRA_ERR_NULL;
     if ((!scores || !vals_out) && P->nnz > 0) return LIBRA_ERR_NULL;
-    if (out_dtype != LIBRA_F16 && out_dtype != LIBRA_F32) return LIBRA_ERR_DTYPE;
+    if (out_dtype != LIBRA_F16 && out_dtype != LIBRA_BF16 && out_dtype != LIBRA_F32) return LIBRA_ERR_DTYPE;
     if (!P->dev_base) return LIBRA_ERR_NOT_UPLOADED;
     hipStream_t s = (hipStream_t)stream;
     if (P->nnz == 0) return LIBRA_OK;
     const unsigned blocks = (unsigned)std::min<int64_t>((P->M + 15) / 16, 1 << 18);
     const unsigned nlong = (unsigned)P->long_rows.size(), nmed = (unsigned)P->medium_rows.size();
-    if (out_dtype == LIBRA_F16) {
-        hipLaunchKernelGGL((edge_softmax_rows_kernel<half_t>), dim3(blocks), dim3(256), 0, s, P->d_rowptr, P->M, scores, scale, (half_t *)vals_out);
-        if (nmed) hipLaunchKernelGGL((edge_softmax_medium_kernel<half_t>), dim3((nmed + 3) / 4), dim3(256), 0, s, P->d_rowptr, P->d_medium_rows, (int)nmed, scores, scale, (half_t *)vals_out);
-        if (nlong) hipLaunchKernelGGL((edge_softmax_long_kernel<half_t>), dim3(nlong), dim3(256), 0, s, P->d_rowptr, P->d_long_rows, scores, scale, (half_t *)vals_out);
-    } else {
-        hipLaunchKernelGGL((edge_softmax_rows_kernel<float>), dim3(blocks), dim3(256), 0, s, P->d_rowptr, P->M, scores, scale, (float *)vals_out);
-        if (nmed) hipLaunchKernelGGL((edge_softmax_medium_kernel<float>), dim3((nmed + 3) / 4), dim3(256), 0, s, P->d_rowptr, P->d_medium_rows, (int)nmed, scores, scale, (float *)vals_out);
-        if (nlong) hipLaunchKernelGGL((edge_softmax_long_kernel<float>), dim3(nlong), dim3(256), 0, s, P->d_rowptr, P->d_long_rows, scores, scale, (float *)vals_out);
-    }
+    auto run = [&](auto tag) {
+        typedef decltype(tag) TO;
+        TO *o = reinterpret_cast<TO *>(vals_out);
+        hipLaunchKernelGGL((edge_softmax_rows_kernel<TO>), dim3(blocks), dim3(256), 0, s, P->d_rowptr, P->M, scores, scale, o);
+        if (nmed) hipLaunchKernelGGL((edge_softmax_medium_kernel<TO>), dim3((nmed + 3) / 4), dim3(256), 0, s, P->d_rowptr, P->d_medium_rows, (int)nmed, scores, scale, o);
+        if (nlong) hipLaunchKernelGGL((edge_softmax_long_kernel<TO>), dim3(nlong), dim3(256), 0, s, P->d_rowptr, P->d_long_rows, scores, scale, o);
+    };
+    if (out_dtype == LIBRA_F16) run(half_t{});
+    else if (out_dtype == LIBRA_BF16) run(bf16_t{});
+    else run(float{});
     return hip_rc(hipGetLastError());
 }
 
@@ -1005,7 +1078,7 @@ extern "C" int libra_plan_set_values(libra_plan_t *P, const void *vals, int dtyp
     if (dtype != P->vdt) return LIBRA_ERR_DTYPE;
     if (!P->dev_base) return LIBRA_ERR_NOT_UPLOADED;
     hipStream_t s = (hipStream_t)stream;
-    const bool f16 = dtype == LIBRA_F16;
+    const bool f16 = dtype != LIBRA_F32;       // 16-bit values are moved as raw bits
     const int vs = P->vsize;
     struct Seg { const int32_t *perm; void *dst; int64_t n; int stride, offset; };
     const SubPlan &sa = P->spmm, &sd = P->sddmm;
@@ -1018,7 +1091,7 @@ extern "C" int libra_plan_set_values(libra_plan_t *P, const void *vals, int dtyp
         if (g.n == 0) continue;
         const unsigned blocks = (unsigned)std::min<int64_t>((g.n + 255) / 256, 1 << 16);
         if (f16)
-            hipLaunchKernelGGL((scatter_values_kernel<half_t>), dim3(blocks), dim3(256), 0, s, (const half_t *)vals, g.perm, g.n, g.dst, g.stride, g.offset);
+            hipLaunchKernelGGL((scatter_values_kernel<uint16_t>), dim3(blocks), dim3(256), 0, s, (const uint16_t *)vals, g.perm, g.n, g.dst, g.stride, g.offset);
         else
             hipLaunchKernelGGL((scatter_values_kernel<float>), dim3(blocks), dim3(256), 0, s, (const float *)vals, g.perm, g.n, g.dst, g.stride, g.offset);
         if (hipGetLastError() != hipSuccess) return LIBRA_ERR_HIP;

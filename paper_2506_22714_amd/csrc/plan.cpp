@@ -336,8 +336,7 @@ extern "C" int libra_plan(int64_t M, int64_t Kc, const int32_t *rowptr, const in
     if (!rowptr) return LIBRA_ERR_NULL;
     if (M < 1 || Kc < 1) return LIBRA_ERR_SHAPE;
     if (M >= (1ll << 31) - 64 || Kc >= (1ll << 31)) return LIBRA_ERR_TOO_LARGE;
-    if (val_dtype == LIBRA_BF16) return LIBRA_ERR_UNSUPPORTED;
-    if (val_dtype != LIBRA_F16 && val_dtype != LIBRA_F32) return LIBRA_ERR_DTYPE;
+    if (val_dtype != LIBRA_F16 && val_dtype != LIBRA_BF16 && val_dtype != LIBRA_F32) return LIBRA_ERR_DTYPE;
     Resolved o{};
     if (int rc = resolve(opts, val_dtype, o)) return rc;
     // ---- validate the CSR arrays, O(nnz) ----

@@ -71,6 +71,12 @@ def dense_normal(rows: int, cols: int, seed: int, dtype=np.float16) -> np.ndarra
     return out
 
 
+def to_bf16_bits(a: np.ndarray) -> np.ndarray:
+    """float32 -> bfloat16 bit patterns (uint16), round to nearest even; finite inputs only."""
+    u = np.ascontiguousarray(a, dtype=np.float32).view(np.uint32).astype(np.uint64)
+    return ((u + 0x7FFF + ((u >> 16) & 1)) >> 16).astype(np.uint16)
+
+
 def dense_small_int(rows: int, cols: int, seed: int, lo=-4, hi=5, dtype=np.float16) -> np.ndarray:
     """Small integers: products and short sums are exact in fp16/fp32/fp64."""
     rng = np.random.default_rng(seed)

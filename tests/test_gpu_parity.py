@@ -298,6 +298,85 @@ def test_edge_softmax_and_set_values_attention_head():
     assert np.max(np.abs(a32 - ref32) / ref32) < 1e-5
 
 
+# ------------------------------------------------------------- bfloat16
+def dev_bf16(bits):
+    return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda().view(torch.bfloat16)
+
+
+def bf16_inputs(A, widths, seed):
+    vb = wl.to_bf16_bits(A.val.astype(np.float32) * 1.37)          # values that are not exact in 8 bits before rounding
+    mats = [wl.to_bf16_bits(wl.dense_normal(r, c, seed=seed + i, dtype=np.float32)) for i, (r, c) in enumerate(widths)]
+    return vb, mats
+
+
+@pytest.mark.parametrize("N", [32, 128, 256])
+def test_bf16_spmm_matches_oracle(N):
+    """bfloat16 storage on both paths (products of bfloat16 numbers are exact in fp32, so the derived bound holds)."""
+    A = mixed_matrix()
+    vb, (B,) = bf16_inputs(A, [(A.Kc, N)], seed=300 + N)
+    for mode in (lb.MODE_HYBRID, lb.MODE_SCALAR_ONLY, lb.MODE_DENSE_ONLY):
+        p = lb.Plan.from_csr(A, val=vb, val_dtype=lb.BF16, mode=mode, flags=lb.FLAG_NO_SDDMM).upload()
+        C = p.spmm(dev_bf16(B))
+        torch.cuda.synchronize()
+        st = p.stats()
+        p.close()
+        if mode == lb.MODE_HYBRID:
+            assert 0 < st["spmm_dense_nnz"] < A.nnz
+        ref, S = oracle.spmm(A.rowptr, A.col, vb, B, bf16=True)
+        deg = np.diff(A.rowptr).astype(np.float64)
+        err = oracle.graded_error(C.cpu().numpy(), ref, S, deg[:, None])
+        assert err <= bound(TOL_F16, deg.max()), (mode, err)
+
+
+@pytest.mark.parametrize("K", [32, 64, 128])
+def test_bf16_sddmm_matches_oracle(K):
+    A = mixed_matrix(seed=5)
+    vb, (X, Y) = bf16_inputs(A, [(A.M, K), (A.Kc, K)], seed=400 + K)
+    for mode in (lb.MODE_HYBRID, lb.MODE_SCALAR_ONLY):
+        p = lb.Plan.from_csr(A, val=vb, val_dtype=lb.BF16, mode=mode, flags=lb.FLAG_NO_SPMM).upload()
+        out = torch.full((p.nnz,), float("nan"), dtype=torch.float32, device="cuda")
+        p.sddmm(dev_bf16(X), dev_bf16(Y), out=out)
+        torch.cuda.synchronize()
+        st = p.stats()
+        p.close()
+        if mode == lb.MODE_HYBRID:
+            assert 0 < st["sddmm_dense_nnz"] < A.nnz
+        ref, S = oracle.sddmm(A.rowptr, A.col, vb, X, Y, bf16=True)
+        got = out.cpu().numpy()
+        assert np.all(np.isfinite(got))
+        err = oracle.graded_error(got, ref, S, K)
+        assert err <= bound(TOL_F16, K), (mode, err)
+
+
+def test_bf16_attention_head():
+    """SDDMM -> softmax with bfloat16 output -> new values -> SpMM, all in bfloat16 storage."""
+    A = wl.make("gat", small=True)
+    K = 64
+    vb, (X, Y) = bf16_inputs(A, [(A.M, K), (A.Kc, K)], seed=77)
+    vb = wl.to_bf16_bits(np.ones(A.nnz, dtype=np.float32))
+    scale = 1.0 / np.sqrt(K)
+    p = lb.Plan.from_csr(A, val=vb, val_dtype=lb.BF16).upload()
+    Yd = dev_bf16(Y)
+    scores = p.sddmm(dev_bf16(X), Yd)
+    alpha = p.edge_softmax(scores, scale)
+    assert alpha.dtype == torch.bfloat16
+    p.set_values(alpha)
+    C = p.spmm(Yd)
+    torch.cuda.synchronize()
+    s_ref, S = oracle.sddmm(A.rowptr, A.col, vb, X, Y, bf16=True)
+    assert oracle.graded_error(scores.cpu().numpy(), s_ref, S, K) <= bound(TOL_F16, K)
+    a_ref = oracle.edge_softmax(A.rowptr, scores.cpu().numpy().astype(np.float64), scale)
+    a_bits = alpha.view(torch.int16).cpu().numpy().view(np.uint16)
+    a = oracle.widen(a_bits, bf16=True)
+    assert np.max(np.abs(a - a_ref) / a_ref) <= 2.0 ** -8 * 1.01        # one rounding to 8 significant bits
+    # round-to-nearest-even, not truncation: the mean signed error is far below half an ulp
+    assert abs(np.mean((a - a_ref) / a_ref)) < 2.0 ** -12
+    deg = np.diff(A.rowptr).astype(np.float64)
+    ref, S2 = oracle.spmm(A.rowptr, A.col, a_bits, Y, bf16=True)
+    err = oracle.graded_error(C.cpu().numpy(), ref, S2, np.maximum(deg, 1)[:, None])
+    assert err <= bound(TOL_F16, deg.max())
+
+
 # ------------------------------------------- reduced instances of configs 2-4
 @pytest.mark.parametrize("name,N,K", [("powerlaw", 128, 32), ("community", 64, 64), ("irregular", 32, 32)])
 def test_small_instances_of_the_configs(name, N, K):

@@ -57,7 +57,7 @@ def test_invalid_inputs_are_rejected_with_codes():
     assert _plan_rc(2, 3, rp, np.array([2, 0, 1]), val) == lb.ERR["UNSORTED"]
     assert _plan_rc(2, 3, rp, np.array([1, 1, 1]), val) == lb.ERR["UNSORTED"]       # duplicate
     assert _plan_rc(2, 3, rp, col, val, dtype=7) == lb.ERR["DTYPE"]
-    assert _plan_rc(2, 3, rp, col, val, dtype=lb.BF16) == lb.ERR["UNSUPPORTED"]
+    assert _plan_rc(2, 3, rp, col, val.view(np.uint16), dtype=lb.BF16) == 0
     assert _plan_rc(2, 3, rp, col, val, opts=lb.PlanOpts(window_rows=33)) == lb.ERR["OPTION"]
     assert _plan_rc(2, 3, rp, col, val, opts=lb.PlanOpts(mode=5)) == lb.ERR["OPTION"]
     bad = lb.PlanOpts()
@@ -198,3 +198,20 @@ def test_fp32_values_force_the_scalar_path():
     assert st["spmm_dense_nnz"] == 0 and st["sddmm_dense_nnz"] == 0 and st["spmm_res_nnz"] == A.nnz
     ex = p.export(0)
     assert ex["res_val"].dtype == np.float32 and np.array_equal(ex["res_val"], A.val.astype(np.float32))
+
+
+def test_bfloat16_plan_has_the_same_structure_and_carries_the_bits():
+    """The storage type only changes how the 16 value bits are read: same pattern, same plan, bits copied."""
+    A = wl.make("powerlaw", small=True)
+    bits = wl.to_bf16_bits(np.linspace(-3.0, 3.0, A.nnz, dtype=np.float32) + 0.01)
+    pf = lb.Plan.from_csr(A, val=bits.view(np.float16))
+    pb = lb.Plan.from_csr(A, val=bits, val_dtype=lb.BF16)
+    for which in (0, 1):
+        ef, eb = pf.export(which), pb.export(which)
+        for k in ("blk_cols", "blk_bitmap", "blk_valptr", "dense_perm", "res_row", "res_col", "res_perm", "zero_rows"):
+            assert np.array_equal(ef[k], eb[k]), k
+        assert np.array_equal(ef["tasks"], eb["tasks"])
+        assert np.array_equal(eb["dense_val"], bits[eb["dense_perm"]])
+        assert np.array_equal(eb["res_val"], bits[eb["res_perm"]])
+    pf.close()
+    pb.close()
