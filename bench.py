@@ -58,6 +58,8 @@ def main() -> int:
     ap.add_argument("--ts", type=int, default=0)
     ap.add_argument("--cs", type=int, default=0)
     ap.add_argument("--natural-order", action="store_true")
+    ap.add_argument("--xcd-order", action="store_true", help="group tasks of neighbouring windows on one accelerator die")
+    ap.add_argument("--no-xcd-order", action="store_true", help="never do that (default: the planner decides from the matrix)")
     ap.add_argument("--dtype", default="f16", choices=["f16", "bf16"], help="storage type of A's values and the dense operands")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run only a 1 GiB device copy (5 times): the known-size kernel that scales the rocprofv3 "
@@ -99,7 +101,8 @@ def main() -> int:
     val = wl.to_bf16_bits(A.val.astype(np.float32)) if bf16 else None
     t0 = time.perf_counter()
     plan = lb.Plan.from_csr(A, val=val, val_dtype=lb.BF16 if bf16 else None, mode=args.mode, spmm_min_vec_nnz=args.tau_spmm, sddmm_min_blk_nnz=args.tau_sddmm,
-                            ts=args.ts, cs=args.cs, flags=lb.FLAG_NATURAL_ORDER if args.natural_order else 0)
+                            ts=args.ts, cs=args.cs, flags=(lb.FLAG_NATURAL_ORDER if args.natural_order else 0) | (lb.FLAG_XCD_ORDER if args.xcd_order else 0)
+                            | (lb.FLAG_NO_XCD_ORDER if args.no_xcd_order else 0))
     plan_s = time.perf_counter() - t0
     t0 = time.perf_counter()
     plan.upload()
@@ -174,7 +177,7 @@ def main() -> int:
     spmm_avg_s = float(spmm_ms.mean()) * 1e-3
     achieved = bytes_spmm / spmm_avg_s / 1e9
     default_cfg = (not args.small and not bf16 and args.mode == 0 and not (args.tau_spmm or args.tau_sddmm or args.ts or args.cs)
-                   and not args.natural_order)
+                   and not args.natural_order and not args.xcd_order and not args.no_xcd_order)
     traffic = MEASURED_TRAFFIC_BYTES.get((args.workload, N)) if default_cfg else None
 
     out = {
@@ -211,7 +214,8 @@ def main() -> int:
                  "sddmm_dense_share": round(st["sddmm_dense_nnz"] / max(A.nnz, 1), 4),
                  "nnz1_vector_ratio": round(st["n_vectors_nnz1"] / max(st["n_vectors"], 1), 4),
                  "spmm_tasks": st["spmm_tasks"], "spmm_chunk_tasks": st["spmm_chunk_tasks"],
-                 "spmm_gather_rows": st["spmm_gather_rows"]},
+                 "spmm_gather_rows": st["spmm_gather_rows"], "neighbour_share": round(st["neighbour_share"], 3),
+                 "xcd_order": st["xcd_order"]},
     }
 
     if not args.no_cpu_baseline:

@@ -68,6 +68,11 @@ extern "C" {
 #define LIBRA_FLAG_NO_SPMM          2u  /* skip the SpMM sub-plan */
 #define LIBRA_FLAG_NO_SDDMM         4u  /* skip the SDDMM sub-plan */
 #define LIBRA_FLAG_NATURAL_ORDER    8u  /* keep tasks in window order instead of heaviest-first */
+#define LIBRA_FLAG_XCD_ORDER       16u  /* heaviest-first by groups of 4 neighbouring windows, one group per accelerator die
+                                           (own L2): neighbours that read the same dense-operand rows share them; the
+                                           task table then holds a few empty tasks (no work).  Without this flag and the
+                                           next one the planner decides from the sampled neighbour_share statistic */
+#define LIBRA_FLAG_NO_XCD_ORDER    32u  /* never use the die-aware order */
 
 typedef struct libra_plan_s libra_plan_t;   /* opaque; immutable after libra_plan() except for its values */
 
@@ -141,6 +146,9 @@ typedef struct {
     int64_t sddmm_tasks;
     int64_t sddmm_gather_rows;    /* per dense block m + real columns, per residual nonzero 2 (Eq. 4, summed) */
     double  plan_seconds;
+    double  neighbour_share;      /* sampled: distinct columns of 4 neighbouring windows taken together / taken one by
+                                     one (1 = neighbours share no dense-operand row, 0.25 = they read the same rows) */
+    int64_t xcd_order;            /* 1 if the task tables are in the die-aware order */
 } libra_stats_t;
 
 /*

@@ -298,6 +298,72 @@ void concat(SubPlan &dst, SubPlan &src, bool spmm) {
     src = SubPlan();
 }
 
+// XCD-aware placement.  Workgroup k of a launch runs on XCD k mod LIBRA_XCDS and every XCD has its own L2, so
+// two tasks share fetched rows of the dense operand only if they sit in the same residue class of the task table
+// and close to each other.  Tasks of neighbouring windows (they tend to reference the same columns) form a group;
+// groups go heaviest first, dealt in snake order to LIBRA_XCDS queues; the table interleaves the queues.  Queues
+// of different length are levelled with empty tasks (no blocks, no entries, no output rows).
+template <class GroupOf>
+void xcd_order(std::vector<libra_task_t> &tasks, size_t begin, size_t end, GroupOf group_of, int noop_kind) {
+    const size_t n = end - begin;
+    if (n < 2 * LIBRA_XCDS) return;
+    std::vector<std::pair<int64_t, size_t>> key(n);                 // (group, position in the heaviest-first list)
+    for (size_t i = 0; i < n; ++i) key[i] = {group_of(tasks[begin + i], i), i};
+    std::sort(key.begin(), key.end());
+    struct Group { uint64_t cost; int64_t gid; size_t first, count; };
+    std::vector<Group> groups;
+    for (size_t i = 0; i < n;) {
+        size_t j = i;
+        uint64_t cost = 0;
+        while (j < n && key[j].first == key[i].first) cost += tasks[begin + key[j++].second].cost;
+        groups.push_back({cost, key[i].first, i, j - i});
+        i = j;
+    }
+    std::stable_sort(groups.begin(), groups.end(), [](const Group &a, const Group &b) { return a.cost > b.cost; });
+    std::vector<size_t> queue[LIBRA_XCDS];
+    for (size_t r = 0; r < groups.size(); ++r) {
+        const size_t round = r / LIBRA_XCDS, x = r % LIBRA_XCDS;
+        std::vector<size_t> &q = queue[round & 1 ? LIBRA_XCDS - 1 - x : x];
+        for (size_t k = 0; k < groups[r].count; ++k) q.push_back(key[groups[r].first + k].second);
+    }
+    size_t maxlen = 0;
+    for (auto &q : queue) maxlen = std::max(maxlen, q.size());
+    const libra_task_t noop{noop_kind, 0, 0, 0, 0, 0, 0u, 0u, 0u, 0u};
+    std::vector<libra_task_t> out;
+    out.reserve(maxlen * LIBRA_XCDS);
+    for (size_t j = 0; j < maxlen; ++j)
+        for (int x = 0; x < LIBRA_XCDS; ++x) out.push_back(j < queue[x].size() ? tasks[begin + queue[x][j]] : noop);
+    while (!out.empty() && out.back().cost == 0 && out.back().blk_begin == out.back().blk_end &&
+           out.back().res_begin == out.back().res_end && out.back().store_mask == 0 && out.back().atomic_mask == 0)
+        out.pop_back();                                             // empty tasks after the last real one
+    tasks.erase(tasks.begin() + begin, tasks.begin() + end);
+    tasks.insert(tasks.begin() + begin, out.begin(), out.end());
+}
+
+// How much neighbouring windows overlap in the columns they reference, on an evenly spaced sample of groups of
+// LIBRA_LOCALITY_WINDOWS windows: distinct columns of the group / sum of the distinct columns of its windows.
+double neighbour_share(int64_t M, const int32_t *rowptr, const int32_t *col, int W) {
+    const int64_t rows_per_group = (int64_t)W * LIBRA_LOCALITY_WINDOWS;
+    const int64_t ngroups = (M + rows_per_group - 1) / rows_per_group;
+    const int64_t nsample = std::min<int64_t>(ngroups, 256);
+    std::vector<uint64_t> keys;
+    int64_t together = 0, apart = 0;
+    for (int64_t k = 0; k < nsample; ++k) {
+        const int64_t g = k * ngroups / nsample;
+        const int64_t r0 = g * rows_per_group, r1 = std::min(M, r0 + rows_per_group);
+        keys.clear();
+        for (int64_t i = r0; i < r1; ++i)
+            for (int32_t p = rowptr[i]; p < rowptr[i + 1]; ++p)
+                keys.push_back(((uint64_t)((i - r0) / W) << 32) | (uint32_t)col[p]);
+        std::sort(keys.begin(), keys.end());
+        apart += std::unique(keys.begin(), keys.end()) - keys.begin();
+        for (auto &x : keys) x &= 0xffffffffull;
+        std::sort(keys.begin(), keys.end());
+        together += std::unique(keys.begin(), keys.end()) - keys.begin();
+    }
+    return apart ? (double)together / (double)apart : 1.0;
+}
+
 int resolve(const libra_plan_opts_t *in, int vdt, Resolved &o) {
     libra_plan_opts_t z{};
     if (in) {
@@ -323,7 +389,9 @@ int resolve(const libra_plan_opts_t *in, int vdt, Resolved &o) {
     o.build_spmm = !(z.flags & LIBRA_FLAG_NO_SPMM);
     o.build_sddmm = !(z.flags & LIBRA_FLAG_NO_SDDMM);
     o.heavy_first = !(z.flags & LIBRA_FLAG_NATURAL_ORDER);
-    if (z.flags & ~15u) return LIBRA_ERR_OPTION;
+    if ((z.flags & LIBRA_FLAG_XCD_ORDER) && (z.flags & LIBRA_FLAG_NO_XCD_ORDER)) return LIBRA_ERR_OPTION;
+    o.xcd_order = !o.heavy_first || (z.flags & LIBRA_FLAG_NO_XCD_ORDER) ? 0 : (z.flags & LIBRA_FLAG_XCD_ORDER) ? 1 : -1;
+    if (z.flags & ~63u) return LIBRA_ERR_OPTION;
     return LIBRA_OK;
 }
 
@@ -414,6 +482,7 @@ extern "C" int libra_plan(int64_t M, int64_t Kc, const int32_t *rowptr, const in
             }
         }
         // ---- ordering: heaviest first, so that the tail of the launch is made of light tasks ----
+        st.neighbour_share = neighbour_share(M, rowptr, col, o.W);
         if (o.heavy_first) {
             auto heavier = [](const libra_task_t &a, const libra_task_t &b) { return a.cost > b.cost; };
             std::stable_sort(sa.tasks.begin(), sa.tasks.end(), heavier);
@@ -421,6 +490,20 @@ extern "C" int libra_plan(int64_t M, int64_t Kc, const int32_t *rowptr, const in
             auto mid = std::stable_partition(sd.tasks.begin(), sd.tasks.end(),
                                              [](const libra_task_t &t) { return t.kind == LIBRA_TASK_WINDOW; });
             std::stable_sort(sd.tasks.begin(), mid, heavier);
+            if (o.xcd_order < 0) P->o.xcd_order = o.xcd_order = st.neighbour_share <= LIBRA_SHARE_THRESHOLD;
+            st.xcd_order = o.xcd_order;
+            if (o.xcd_order) {
+                const int W = o.W;
+                xcd_order(sa.tasks, 0, sa.tasks.size(), [W](const libra_task_t &t, size_t) {
+                    return (int64_t)(t.kind == LIBRA_TASK_WINDOW ? t.id : t.id / W) / LIBRA_LOCALITY_WINDOWS; }, LIBRA_TASK_WINDOW);
+                // SDDMM: window tasks by window; the flat segments (still in CSR order here) in runs of consecutive segments
+                const size_t nwt = (size_t)(mid - sd.tasks.begin());
+                const size_t nseg = sd.tasks.size() - nwt;
+                xcd_order(sd.tasks, nwt, nwt + nseg, [](const libra_task_t &, size_t i) {
+                    return (int64_t)(i / LIBRA_LOCALITY_SEGMENTS); }, LIBRA_TASK_CHUNK);
+                xcd_order(sd.tasks, 0, nwt, [](const libra_task_t &t, size_t) {
+                    return (int64_t)t.id / LIBRA_LOCALITY_WINDOWS; }, LIBRA_TASK_CHUNK);
+            }
         }
         for (SubPlan *sp : {&sa, &sd})
             for (auto &t : sp->tasks) (t.kind == LIBRA_TASK_WINDOW ? sp->n_window_tasks : sp->n_chunk_tasks)++;

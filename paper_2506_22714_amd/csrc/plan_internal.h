@@ -8,6 +8,10 @@
 #include "libra.h"
 
 #define LIBRA_SOFTMAX_LONG_ROW 2048
+#define LIBRA_XCDS 8                 // accelerator dies of an MI355X; workgroup k runs on die k mod 8
+#define LIBRA_LOCALITY_WINDOWS 4     // neighbouring windows whose tasks are kept on one die (XCD-aware order)
+#define LIBRA_LOCALITY_SEGMENTS 8    // consecutive SDDMM residual segments kept on one die
+#define LIBRA_SHARE_THRESHOLD 0.67   // die-aware order when 4 neighbouring windows together have at most this share of their separate columns
 
 namespace libra {
 
@@ -77,6 +81,7 @@ struct SubPlan {
 struct Resolved {
     int mode, W, KB, tau_spmm, tau_sddmm, Ts, Cs, short_len, sddmm_Cs, threads;
     bool fill, build_spmm, build_sddmm, heavy_first;
+    int xcd_order;       // 1 on, 0 off, -1 decide from the matrix
 };
 
 }  // namespace libra

@@ -298,6 +298,31 @@ def test_edge_softmax_and_set_values_attention_head():
     assert np.max(np.abs(a32 - ref32) / ref32) < 1e-5
 
 
+def test_die_aware_task_order_changes_no_result():
+    """The order of the task table (and the empty tasks the die-aware order adds) is invisible in the results."""
+    A = wl.make("community", small=True)
+    B = wl.dense_normal(A.Kc, 128, seed=31)
+    X = wl.dense_normal(A.M, 32, seed=32)
+    Y = wl.dense_normal(A.Kc, 32, seed=33)
+    res = []
+    for fl in (lb.FLAG_NO_XCD_ORDER, lb.FLAG_XCD_ORDER, 0):
+        p = lb.Plan.from_csr(A, flags=fl).upload()
+        C = p.spmm(dev(B))
+        out = torch.full((p.nnz,), float("nan"), dtype=torch.float32, device="cuda")
+        p.sddmm(dev(X), dev(Y), out=out)
+        torch.cuda.synchronize()
+        st = p.stats()
+        res.append((C.cpu().numpy(), out.cpu().numpy(), st))
+        p.close()
+    assert res[0][2]["xcd_order"] == 0 and res[1][2]["xcd_order"] == 1 and res[2][2]["xcd_order"] == 1
+    assert res[1][2]["spmm_tasks"] >= res[0][2]["spmm_tasks"]
+    assert res[0][2]["spmm_zero_rows"] == 0          # no row is decomposed here: every row has one writer, sums have one order
+    for k in (1, 2):
+        assert np.array_equal(res[0][0], res[k][0]) and np.array_equal(res[0][1], res[k][1])
+    check_spmm(A, B, res[1][0], TOL_F16)
+    check_sddmm(A, X, Y, res[1][1], TOL_F16)
+
+
 # ------------------------------------------------------------- bfloat16
 def dev_bf16(bits):
     return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda().view(torch.bfloat16)

@@ -90,7 +90,13 @@ def test_compute_calls_without_device_copy_fail_cleanly():
 
 
 # ------------------------------------------------- plan == reference planner
+def is_empty_task(t):
+    """Filler of the die-aware order: no blocks, no entries, no output rows."""
+    return t["blk_begin"] == t["blk_end"] and t["res_begin"] == t["res_end"] and t["atomic_mask"] == 0 and t["store_mask"] == 0
+
+
 def canon_tasks(tasks):
+    tasks = [t for t in tasks if not is_empty_task(t)]
     return sorted((int(t["kind"]), int(t["id"]), int(t["blk_begin"]), int(t["blk_end"]), int(t["res_begin"]),
                    int(t["res_end"]), int(t["scalar_mask"]), int(t["atomic_mask"]), int(t["store_mask"])) for t in tasks)
 
@@ -125,7 +131,8 @@ def check_subplan(A: wl.Csr, ex: dict, ref: pr.SubPlan, spmm: bool):
         assert sorted(ex["zero_rows"]) == ref.zero_rows
     else:
         assert np.all(np.diff(ex["res_perm"]) > 0)
-    assert canon_tasks(ex["tasks"]) == sorted(ref.tasks)
+    # tasks that do nothing (the die-aware order adds some; a window whose rows are all decomposed is one) are not compared
+    assert canon_tasks(ex["tasks"]) == sorted(t for t in ref.tasks if not (t[2] == t[3] and t[4] == t[5] and t[7] == 0 and t[8] == 0))
 
 
 CASES = [
@@ -179,10 +186,12 @@ def test_planner_matches_reference_bit_for_bit(case):
 
 def test_plan_does_not_depend_on_thread_count_and_orders_heaviest_first():
     A = wl.rmat(scale=11, avg_degree=8, seed=4)
-    e1 = lb.Plan.from_csr(A, threads=1, cs=16, ts=2).export(0)
-    e7 = lb.Plan.from_csr(A, threads=7, cs=16, ts=2).export(0)
+    e1 = lb.Plan.from_csr(A, threads=1, cs=16, ts=2, flags=lb.FLAG_NO_XCD_ORDER).export(0)
+    e7 = lb.Plan.from_csr(A, threads=7, cs=16, ts=2, flags=lb.FLAG_NO_XCD_ORDER).export(0)
     for k in e1:
         assert np.array_equal(e1[k], e7[k]), k
+    a1, a7 = (lb.Plan.from_csr(A, threads=t, cs=16, ts=2).export(0) for t in (1, 7))       # order decided from the matrix
+    assert np.array_equal(a1["tasks"], a7["tasks"])
     cost = e1["tasks"]["cost"].astype(np.int64)
     assert np.all(np.diff(cost) <= 0)
     nat = lb.Plan.from_csr(A, cs=16, ts=2, flags=lb.FLAG_NATURAL_ORDER).export(0)
@@ -215,3 +224,24 @@ def test_bfloat16_plan_has_the_same_structure_and_carries_the_bits():
         assert np.array_equal(eb["res_val"], bits[eb["res_perm"]])
     pf.close()
     pb.close()
+
+
+def test_xcd_order_keeps_the_tasks_and_puts_neighbouring_windows_on_one_die():
+    A = wl.community(n_blocks=64, seed=3)
+    for which in (0, 1):
+        base = lb.Plan.from_csr(A, flags=lb.FLAG_NO_XCD_ORDER).export(which)["tasks"]
+        auto = lb.Plan.from_csr(A)
+        assert auto.stats()["xcd_order"] == 1 and auto.stats()["neighbour_share"] < 0.6      # diagonal blocks: decided from the matrix
+        grp = auto.export(which)["tasks"]
+        assert np.array_equal(grp, lb.Plan.from_csr(A, flags=lb.FLAG_XCD_ORDER).export(which)["tasks"])
+        empty = np.array([bool(is_empty_task(t)) for t in grp])
+        assert canon_tasks(grp[~empty]) == canon_tasks(base)           # same work, a few empty tasks added
+        assert empty.sum() <= 8 * 64 and not empty[-1]
+        # the four windows of a group sit in one residue class modulo 8 (= one die), next to each other
+        pos = {}
+        for k, t in enumerate(grp):
+            if not empty[k] and t["kind"] == lb.TASK_WINDOW:
+                pos.setdefault(int(t["id"]) // 4, []).append(k)
+        for g, ks in pos.items():
+            assert len({k % 8 for k in ks}) == 1, g
+            assert max(ks) - min(ks) == 8 * (len(ks) - 1), g
