@@ -342,7 +342,7 @@ void xcd_order(std::vector<libra_task_t> &tasks, size_t begin, size_t end, Group
 
 // How much neighbouring windows overlap in the columns they reference, on an evenly spaced sample of groups of
 // LIBRA_LOCALITY_WINDOWS windows: distinct columns of the group / sum of the distinct columns of its windows.
-double neighbour_share(int64_t M, const int32_t *rowptr, const int32_t *col, int W) {
+double neighbour_share(int64_t M, const int32_t *rowptr, const ColumnFetch &cols, int W) {
     const int64_t rows_per_group = (int64_t)W * LIBRA_LOCALITY_WINDOWS;
     const int64_t ngroups = (M + rows_per_group - 1) / rows_per_group;
     const int64_t nsample = std::min<int64_t>(ngroups, 256);
@@ -352,6 +352,7 @@ double neighbour_share(int64_t M, const int32_t *rowptr, const int32_t *col, int
         const int64_t g = k * ngroups / nsample;
         const int64_t r0 = g * rows_per_group, r1 = std::min(M, r0 + rows_per_group);
         keys.clear();
+        const int32_t *col = cols(rowptr[r0], rowptr[r1]) - rowptr[r0];      // indexable by CSR position
         for (int64_t i = r0; i < r1; ++i)
             for (int32_t p = rowptr[i]; p < rowptr[i + 1]; ++p)
                 keys.push_back(((uint64_t)((i - r0) / W) << 32) | (uint32_t)col[p]);
@@ -364,7 +365,9 @@ double neighbour_share(int64_t M, const int32_t *rowptr, const int32_t *col, int
     return apart ? (double)together / (double)apart : 1.0;
 }
 
-int resolve(const libra_plan_opts_t *in, int vdt, Resolved &o) {
+}  // namespace
+
+int libra::resolve_options(const libra_plan_opts_t *in, int vdt, Resolved &o) {
     libra_plan_opts_t z{};
     if (in) {
         if (in->struct_size != sizeof(libra_plan_opts_t)) return LIBRA_ERR_OPTION;
@@ -395,7 +398,74 @@ int resolve(const libra_plan_opts_t *in, int vdt, Resolved &o) {
     return LIBRA_OK;
 }
 
-}  // namespace
+// Shared tail of the host and the device planner: the flat SDDMM residual segments, the order of the task
+// tables and the statistics.  Expects the sub-plans with their tasks in window order.
+void libra::finish_plan(libra_plan_t *P, const ColumnFetch &cols) {
+    const Resolved o = P->o;
+    const int64_t M = P->M, nnz = P->nnz;
+    const int32_t *rowptr = P->rowptr.data();
+    SubPlan &sa = P->spmm, &sd = P->sddmm;
+    libra_stats_t &st = P->stats;
+    const int64_t nwin = (M + o.W - 1) / o.W;
+    int xcd = o.xcd_order;
+    for (int64_t i = 0; i < M; ++i) {       // row lists of the edge softmax
+        const int32_t n = rowptr[i + 1] - rowptr[i];
+        if (n > LIBRA_SOFTMAX_LONG_ROW) P->long_rows.push_back((int32_t)i);
+        else if (n > 64) P->medium_rows.push_back((int32_t)i);
+    }
+    if (!o.build_spmm) sa = SubPlan();
+    if (!o.build_sddmm) sd = SubPlan();
+    if (o.build_sddmm) {
+        // scalar segments over the flat residual list (no atomics needed: each output has one writer)
+        const int32_t nres = (int32_t)sd.res_perm.size();
+        for (int32_t q = 0; q < nres; q += o.sddmm_Cs) {
+            int32_t q1 = std::min(nres, q + o.sddmm_Cs);
+            sd.tasks.push_back({LIBRA_TASK_CHUNK, 0, 0, 0, q, q1, 0u, 0u, 0u, (uint32_t)(2 * (q1 - q))});
+        }
+    }
+    // ---- ordering: heaviest first, so that the tail of the launch is made of light tasks ----
+    st.neighbour_share = neighbour_share(M, rowptr, cols, o.W);
+    if (o.heavy_first) {
+        auto heavier = [](const libra_task_t &a, const libra_task_t &b) { return a.cost > b.cost; };
+        std::stable_sort(sa.tasks.begin(), sa.tasks.end(), heavier);
+        // SDDMM window tasks first (heaviest first); the flat residual segments stay behind them in order
+        auto mid = std::stable_partition(sd.tasks.begin(), sd.tasks.end(),
+                                         [](const libra_task_t &t) { return t.kind == LIBRA_TASK_WINDOW; });
+        std::stable_sort(sd.tasks.begin(), mid, heavier);
+        if (xcd < 0) P->o.xcd_order = xcd = st.neighbour_share <= LIBRA_SHARE_THRESHOLD;
+        st.xcd_order = xcd;
+        if (xcd) {
+            const int W = o.W;
+            xcd_order(sa.tasks, 0, sa.tasks.size(), [W](const libra_task_t &t, size_t) {
+                return (int64_t)(t.kind == LIBRA_TASK_WINDOW ? t.id : t.id / W) / LIBRA_LOCALITY_WINDOWS; }, LIBRA_TASK_WINDOW);
+            // SDDMM: window tasks by window; the flat segments (still in CSR order here) in runs of consecutive segments
+            const size_t nwt = (size_t)(mid - sd.tasks.begin());
+            const size_t nseg = sd.tasks.size() - nwt;
+            xcd_order(sd.tasks, nwt, nwt + nseg, [](const libra_task_t &, size_t i) {
+                return (int64_t)(i / LIBRA_LOCALITY_SEGMENTS); }, LIBRA_TASK_CHUNK);
+            xcd_order(sd.tasks, 0, nwt, [](const libra_task_t &t, size_t) {
+                return (int64_t)t.id / LIBRA_LOCALITY_WINDOWS; }, LIBRA_TASK_CHUNK);
+        }
+    }
+    for (SubPlan *sp : {&sa, &sd})
+        for (auto &t : sp->tasks) (t.kind == LIBRA_TASK_WINDOW ? sp->n_window_tasks : sp->n_chunk_tasks)++;
+
+    st.M = M; st.Kc = P->Kc; st.nnz = nnz; st.n_windows = nwin;
+    if (o.build_spmm) {
+        st.spmm_dense_vectors = sa.dense_vectors; st.spmm_blocks = sa.n_blocks(); st.spmm_pad_slots = sa.pad_slots;
+        st.spmm_dense_nnz = (int64_t)sa.dense_perm.size(); st.spmm_res_nnz = (int64_t)sa.res_perm.size();
+        st.spmm_tasks = (int64_t)sa.tasks.size(); st.spmm_chunk_tasks = sa.n_chunk_tasks;
+        st.spmm_zero_rows = (int64_t)sa.zero_rows.size();
+        st.spmm_short_rows = sa.short_rows; st.spmm_long_rows = sa.long_rows; st.spmm_split_rows = sa.split_rows;
+        st.spmm_gather_rows = sa.dense_vectors + st.spmm_res_nnz;
+    }
+    if (o.build_sddmm) {
+        st.sddmm_dense_vectors = sd.dense_vectors; st.sddmm_blocks = sd.n_blocks(); st.sddmm_pad_slots = sd.pad_slots;
+        st.sddmm_dense_nnz = (int64_t)sd.dense_perm.size(); st.sddmm_res_nnz = (int64_t)sd.res_perm.size();
+        st.sddmm_tasks = (int64_t)sd.tasks.size();
+        st.sddmm_gather_rows = sd.dense_vectors + (int64_t)o.W * sd.n_blocks() + 2 * st.sddmm_res_nnz;
+    }
+}
 
 extern "C" int libra_plan(int64_t M, int64_t Kc, const int32_t *rowptr, const int32_t *col, const void *val,
                           int val_dtype, const libra_plan_opts_t *opts, libra_plan_t **out) {
@@ -406,7 +476,7 @@ extern "C" int libra_plan(int64_t M, int64_t Kc, const int32_t *rowptr, const in
     if (M >= (1ll << 31) - 64 || Kc >= (1ll << 31)) return LIBRA_ERR_TOO_LARGE;
     if (val_dtype != LIBRA_F16 && val_dtype != LIBRA_BF16 && val_dtype != LIBRA_F32) return LIBRA_ERR_DTYPE;
     Resolved o{};
-    if (int rc = resolve(opts, val_dtype, o)) return rc;
+    if (int rc = resolve_options(opts, val_dtype, o)) return rc;
     // ---- validate the CSR arrays, O(nnz) ----
     if (rowptr[0] != 0) return LIBRA_ERR_ROWPTR;
     for (int64_t i = 0; i < M; ++i)
@@ -426,12 +496,6 @@ extern "C" int libra_plan(int64_t M, int64_t Kc, const int32_t *rowptr, const in
         P->M = M; P->Kc = Kc; P->nnz = nnz; P->vdt = val_dtype; P->vsize = val_dtype == LIBRA_F32 ? 4 : 2;
         P->o = o;
         P->rowptr.assign(rowptr, rowptr + M + 1);
-        for (int64_t i = 0; i < M; ++i)
-        {
-            const int32_t n = rowptr[i + 1] - rowptr[i];
-            if (n > LIBRA_SOFTMAX_LONG_ROW) P->long_rows.push_back((int32_t)i);
-            else if (n > 64) P->medium_rows.push_back((int32_t)i);
-        }
         Ctx c{M, nnz, rowptr, col, (const uint8_t *)val, P->vsize, o, (o.W * o.KB + 63) / 64};
         const int64_t nwin = (M + o.W - 1) / o.W;
         int nthr = o.threads ? o.threads : (int)std::thread::hardware_concurrency();
@@ -471,58 +535,7 @@ extern "C" int libra_plan(int64_t M, int64_t Kc, const int32_t *rowptr, const in
             if (o.build_sddmm) concat(sd, pt.sddmm, false);
         }
         parts.clear();
-        if (!o.build_spmm) sa = SubPlan();
-        if (!o.build_sddmm) sd = SubPlan();
-        if (o.build_sddmm) {
-            // scalar segments over the flat residual list (no atomics needed: each output has one writer)
-            const int32_t nres = (int32_t)sd.res_perm.size();
-            for (int32_t q = 0; q < nres; q += o.sddmm_Cs) {
-                int32_t q1 = std::min(nres, q + o.sddmm_Cs);
-                sd.tasks.push_back({LIBRA_TASK_CHUNK, 0, 0, 0, q, q1, 0u, 0u, 0u, (uint32_t)(2 * (q1 - q))});
-            }
-        }
-        // ---- ordering: heaviest first, so that the tail of the launch is made of light tasks ----
-        st.neighbour_share = neighbour_share(M, rowptr, col, o.W);
-        if (o.heavy_first) {
-            auto heavier = [](const libra_task_t &a, const libra_task_t &b) { return a.cost > b.cost; };
-            std::stable_sort(sa.tasks.begin(), sa.tasks.end(), heavier);
-            // SDDMM window tasks first (heaviest first); the flat residual segments stay behind them in order
-            auto mid = std::stable_partition(sd.tasks.begin(), sd.tasks.end(),
-                                             [](const libra_task_t &t) { return t.kind == LIBRA_TASK_WINDOW; });
-            std::stable_sort(sd.tasks.begin(), mid, heavier);
-            if (o.xcd_order < 0) P->o.xcd_order = o.xcd_order = st.neighbour_share <= LIBRA_SHARE_THRESHOLD;
-            st.xcd_order = o.xcd_order;
-            if (o.xcd_order) {
-                const int W = o.W;
-                xcd_order(sa.tasks, 0, sa.tasks.size(), [W](const libra_task_t &t, size_t) {
-                    return (int64_t)(t.kind == LIBRA_TASK_WINDOW ? t.id : t.id / W) / LIBRA_LOCALITY_WINDOWS; }, LIBRA_TASK_WINDOW);
-                // SDDMM: window tasks by window; the flat segments (still in CSR order here) in runs of consecutive segments
-                const size_t nwt = (size_t)(mid - sd.tasks.begin());
-                const size_t nseg = sd.tasks.size() - nwt;
-                xcd_order(sd.tasks, nwt, nwt + nseg, [](const libra_task_t &, size_t i) {
-                    return (int64_t)(i / LIBRA_LOCALITY_SEGMENTS); }, LIBRA_TASK_CHUNK);
-                xcd_order(sd.tasks, 0, nwt, [](const libra_task_t &t, size_t) {
-                    return (int64_t)t.id / LIBRA_LOCALITY_WINDOWS; }, LIBRA_TASK_CHUNK);
-            }
-        }
-        for (SubPlan *sp : {&sa, &sd})
-            for (auto &t : sp->tasks) (t.kind == LIBRA_TASK_WINDOW ? sp->n_window_tasks : sp->n_chunk_tasks)++;
-
-        st.M = M; st.Kc = Kc; st.nnz = nnz; st.n_windows = nwin;
-        if (o.build_spmm) {
-            st.spmm_dense_vectors = sa.dense_vectors; st.spmm_blocks = sa.n_blocks(); st.spmm_pad_slots = sa.pad_slots;
-            st.spmm_dense_nnz = (int64_t)sa.dense_perm.size(); st.spmm_res_nnz = (int64_t)sa.res_perm.size();
-            st.spmm_tasks = (int64_t)sa.tasks.size(); st.spmm_chunk_tasks = sa.n_chunk_tasks;
-            st.spmm_zero_rows = (int64_t)sa.zero_rows.size();
-            st.spmm_short_rows = sa.short_rows; st.spmm_long_rows = sa.long_rows; st.spmm_split_rows = sa.split_rows;
-            st.spmm_gather_rows = sa.dense_vectors + st.spmm_res_nnz;
-        }
-        if (o.build_sddmm) {
-            st.sddmm_dense_vectors = sd.dense_vectors; st.sddmm_blocks = sd.n_blocks(); st.sddmm_pad_slots = sd.pad_slots;
-            st.sddmm_dense_nnz = (int64_t)sd.dense_perm.size(); st.sddmm_res_nnz = (int64_t)sd.res_perm.size();
-            st.sddmm_tasks = (int64_t)sd.tasks.size();
-            st.sddmm_gather_rows = sd.dense_vectors + (int64_t)o.W * sd.n_blocks() + 2 * st.sddmm_res_nnz;
-        }
+        finish_plan(P, [col](int64_t p0, int64_t) { return col + p0; });
         st.plan_seconds = std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count();
     } catch (...) {
         delete P;

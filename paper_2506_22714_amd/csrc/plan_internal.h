@@ -3,6 +3,7 @@
 #pragma once
 
 #include <cstdint>
+#include <functional>
 #include <vector>
 
 #include "libra.h"
@@ -103,3 +104,11 @@ struct libra_plan_s {
     const int32_t *d_long_rows = nullptr;
     const int32_t *d_medium_rows = nullptr;
 };
+
+namespace libra {
+// Host pointer to the column indices of CSR positions [p0, p1).
+typedef std::function<const int32_t *(int64_t p0, int64_t p1)> ColumnFetch;
+int resolve_options(const libra_plan_opts_t *in, int value_dtype, Resolved &out);
+// Shared tail of the host and the device planner (segments of the SDDMM residual list, task order, statistics).
+void finish_plan(libra_plan_s *plan, const ColumnFetch &cols);
+}  // namespace libra
