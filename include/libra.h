@@ -149,6 +149,7 @@ typedef struct {
     double  neighbour_share;      /* sampled: distinct columns of 4 neighbouring windows taken together / taken one by
                                      one (1 = neighbours share no dense-operand row, 0.25 = they read the same rows) */
     int64_t xcd_order;            /* 1 if the task tables are in the die-aware order */
+    double  device_seconds;       /* libra_plan_device: time until the device passes had finished (0 for libra_plan) */
 } libra_stats_t;
 
 /*
@@ -165,6 +166,24 @@ typedef struct {
  */
 int libra_plan(int64_t M, int64_t Kc, const int32_t *rowptr, const int32_t *col,
                const void *val, int val_dtype, const libra_plan_opts_t *opts, libra_plan_t **out);
+
+/*
+ * libra_plan_device - the same plan, bit for bit, built on the GPU from a CSR matrix that is already in device
+ * memory (the paper's GPU-accelerated preprocessing, Section 4.5, Algorithm 1: per-window census by sorting,
+ * prefix sums for every offset).  Only the kernels' shape is supported (window_rows = block_cols = 16).
+ *   d_rowptr, d_col, d_val   device, as in libra_plan; nnz must equal d_rowptr[M]
+ *   workspace                device, 256-byte aligned, at least libra_plan_device_workspace() bytes; only used
+ *                            during the call, the caller may free it afterwards
+ *   stream                   the passes are enqueued on it; the call synchronises it several times
+ * The finished arrays are copied into the plan's host memory (so libra_plan_export and libra_plan_upload work as
+ * for a host-built plan); the order of the task tables and the statistics are made on the host by the same code as
+ * in libra_plan.  A matrix without nonzeros needs no device pass.
+ * Errors: as libra_plan, plus UNSUPPORTED (window shape), BUFFER (workspace too small or misaligned), HIP.
+ */
+int libra_plan_device_workspace(int64_t M, int64_t nnz, const libra_plan_opts_t *opts, size_t *bytes);
+int libra_plan_device(int64_t M, int64_t Kc, int64_t nnz, const int32_t *d_rowptr, const int32_t *d_col,
+                      const void *d_val, int val_dtype, const libra_plan_opts_t *opts,
+                      void *workspace, size_t workspace_bytes, void *stream, libra_plan_t **out);
 
 /* Bytes of device memory the plan's arrays need (256-byte aligned layout). */
 int libra_plan_device_bytes(const libra_plan_t *plan, size_t *bytes);

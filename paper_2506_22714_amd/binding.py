@@ -77,7 +77,7 @@ _STATS_I64 = ["M", "Kc", "nnz", "n_windows", "n_vectors", "n_vectors_nnz1",
 
 class Stats(C.Structure):
     _fields_ = [(n, C.c_int64) for n in _STATS_I64] + [("plan_seconds", C.c_double), ("neighbour_share", C.c_double),
-                                                               ("xcd_order", C.c_int64)]
+                                                               ("xcd_order", C.c_int64), ("device_seconds", C.c_double)]
 
 
 _lib = None
@@ -93,6 +93,8 @@ def lib() -> C.CDLL:
         L = C.CDLL(LIB_PATH)
         vp, i32, i64, sz = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t
         L.libra_plan.argtypes = [i64, i64, vp, vp, vp, C.c_int, C.POINTER(PlanOpts), C.POINTER(vp)]
+        L.libra_plan_device_workspace.argtypes = [i64, i64, C.POINTER(PlanOpts), C.POINTER(sz)]
+        L.libra_plan_device.argtypes = [i64, i64, i64, vp, vp, vp, C.c_int, C.POINTER(PlanOpts), vp, sz, vp, C.POINTER(vp)]
         L.libra_plan_device_bytes.argtypes = [vp, C.POINTER(sz)]
         L.libra_plan_upload.argtypes = [vp, vp, sz, vp]
         L.libra_spmm.argtypes = [vp, vp, i32, i64, vp, i64, vp]
@@ -149,6 +151,23 @@ def libra_plan(M: int, Kc: int, rowptr: np.ndarray, col: np.ndarray, val: np.nda
                           _np_dtype_code(val) if val_dtype is None else val_dtype,
                           C.byref(opts) if opts is not None else None, C.byref(handle))
     _check(rc, "libra_plan")
+    return handle
+
+
+def libra_plan_device_workspace(M: int, nnz: int, opts: PlanOpts | None = None) -> int:
+    n = C.c_size_t()
+    _check(lib().libra_plan_device_workspace(M, nnz, C.byref(opts) if opts is not None else None, C.byref(n)),
+           "libra_plan_device_workspace")
+    return int(n.value)
+
+
+def libra_plan_device(M: int, Kc: int, nnz: int, rowptr_ptr: int, col_ptr: int, val_ptr: int, val_dtype: int,
+                      opts: PlanOpts | None, ws_ptr: int, ws_bytes: int, stream: int = 0) -> C.c_void_p:
+    handle = C.c_void_p()
+    rc = lib().libra_plan_device(M, Kc, nnz, C.c_void_p(rowptr_ptr), C.c_void_p(col_ptr), C.c_void_p(val_ptr), val_dtype,
+                                 C.byref(opts) if opts is not None else None, C.c_void_p(ws_ptr), ws_bytes,
+                                 C.c_void_p(stream), C.byref(handle))
+    _check(rc, "libra_plan_device")
     return handle
 
 
@@ -232,6 +251,29 @@ class Plan:
                                  val_dtype=self.val_dtype)
         self.nnz = libra_plan_stats(self.handle)["nnz"]
         self._buf = None
+
+    @classmethod
+    def from_device_csr(cls, M, Kc, rowptr, col, val, **opts):
+        """Plan built on the GPU from torch tensors (int32 rowptr/col, float16 / bfloat16 / float32 values)."""
+        import torch
+        assert rowptr.is_cuda and rowptr.dtype == torch.int32 and rowptr.is_contiguous() and rowptr.numel() == M + 1
+        nnz = int(col.numel())
+        assert col.is_cuda and col.dtype == torch.int32 and col.is_contiguous() and val.is_cuda and val.is_contiguous()
+        assert val.numel() == nnz
+        self = cls.__new__(cls)
+        self.M, self.Kc = int(M), int(Kc)
+        self.val_dtype = {torch.float16: F16, torch.bfloat16: BF16, torch.float32: F32}[val.dtype]
+        o = PlanOpts(**opts) if opts else None
+        ws_bytes = libra_plan_device_workspace(self.M, nnz, o)
+        ws = torch.empty(ws_bytes, dtype=torch.uint8, device=rowptr.device)
+        self.handle = None
+        self._buf = None
+        self.handle = libra_plan_device(self.M, self.Kc, nnz, rowptr.data_ptr(), col.data_ptr() if nnz else 0,
+                                        val.data_ptr() if nnz else 0, self.val_dtype, o, ws.data_ptr(), ws_bytes,
+                                        torch.cuda.current_stream().cuda_stream)
+        del ws
+        self.nnz = libra_plan_stats(self.handle)["nnz"]
+        return self
 
     @classmethod
     def from_csr(cls, csr, val=None, val_dtype: int | None = None, **opts):
