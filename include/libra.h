@@ -174,16 +174,26 @@ int libra_plan(int64_t M, int64_t Kc, const int32_t *rowptr, const int32_t *col,
  *   d_rowptr, d_col, d_val   device, as in libra_plan; nnz must equal d_rowptr[M]
  *   workspace                device, 256-byte aligned, at least libra_plan_device_workspace() bytes; only used
  *                            during the call, the caller may free it afterwards
+ *   plan_buf, plan_bytes     device, 256-byte aligned, or NULL.  If given, the plan's device copy is written
+ *                            there directly from the workspace (no trip through host memory) and the plan is
+ *                            ready for the compute calls; it needs libra_plan_device_bytes() of the finished
+ *                            plan, which libra_plan_device_buffer_bound() bounds from M and nnz beforehand.
+ *                            The plan borrows it until libra_plan_destroy.  NULL: call libra_plan_upload later.
+ *   keep_host_copy           nonzero: the arrays are also copied into the plan's host memory, so that
+ *                            libra_plan_export and libra_plan_upload work as for a host-built plan.  Zero (only
+ *                            with plan_buf): they are not; those two calls then return LIBRA_ERR_NOT_BUILT.
  *   stream                   the passes are enqueued on it; the call synchronises it several times
- * The finished arrays are copied into the plan's host memory (so libra_plan_export and libra_plan_upload work as
- * for a host-built plan); the order of the task tables and the statistics are made on the host by the same code as
- * in libra_plan.  A matrix without nonzeros needs no device pass.
- * Errors: as libra_plan, plus UNSUPPORTED (window shape), BUFFER (workspace too small or misaligned), HIP.
+ * The task tables always pass through the host: their order and the statistics are made by the same code as in
+ * libra_plan.  A matrix without nonzeros needs no device pass.
+ * Errors: as libra_plan, plus UNSUPPORTED (window shape), BUFFER (workspace or plan buffer too small or
+ * misaligned), HIP.
  */
 int libra_plan_device_workspace(int64_t M, int64_t nnz, const libra_plan_opts_t *opts, size_t *bytes);
+int libra_plan_device_buffer_bound(int64_t M, int64_t nnz, int val_dtype, const libra_plan_opts_t *opts, size_t *bytes);
 int libra_plan_device(int64_t M, int64_t Kc, int64_t nnz, const int32_t *d_rowptr, const int32_t *d_col,
                       const void *d_val, int val_dtype, const libra_plan_opts_t *opts,
-                      void *workspace, size_t workspace_bytes, void *stream, libra_plan_t **out);
+                      void *workspace, size_t workspace_bytes, void *plan_buf, size_t plan_bytes,
+                      int keep_host_copy, void *stream, libra_plan_t **out);
 
 /* Bytes of device memory the plan's arrays need (256-byte aligned layout). */
 int libra_plan_device_bytes(const libra_plan_t *plan, size_t *bytes);

@@ -94,7 +94,9 @@ def lib() -> C.CDLL:
         vp, i32, i64, sz = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t
         L.libra_plan.argtypes = [i64, i64, vp, vp, vp, C.c_int, C.POINTER(PlanOpts), C.POINTER(vp)]
         L.libra_plan_device_workspace.argtypes = [i64, i64, C.POINTER(PlanOpts), C.POINTER(sz)]
-        L.libra_plan_device.argtypes = [i64, i64, i64, vp, vp, vp, C.c_int, C.POINTER(PlanOpts), vp, sz, vp, C.POINTER(vp)]
+        L.libra_plan_device_buffer_bound.argtypes = [i64, i64, C.c_int, C.POINTER(PlanOpts), C.POINTER(sz)]
+        L.libra_plan_device.argtypes = [i64, i64, i64, vp, vp, vp, C.c_int, C.POINTER(PlanOpts), vp, sz, vp, sz, C.c_int,
+                                        vp, C.POINTER(vp)]
         L.libra_plan_device_bytes.argtypes = [vp, C.POINTER(sz)]
         L.libra_plan_upload.argtypes = [vp, vp, sz, vp]
         L.libra_spmm.argtypes = [vp, vp, i32, i64, vp, i64, vp]
@@ -161,11 +163,20 @@ def libra_plan_device_workspace(M: int, nnz: int, opts: PlanOpts | None = None) 
     return int(n.value)
 
 
+def libra_plan_device_buffer_bound(M: int, nnz: int, val_dtype: int, opts: PlanOpts | None = None) -> int:
+    n = C.c_size_t()
+    _check(lib().libra_plan_device_buffer_bound(M, nnz, val_dtype, C.byref(opts) if opts is not None else None, C.byref(n)),
+           "libra_plan_device_buffer_bound")
+    return int(n.value)
+
+
 def libra_plan_device(M: int, Kc: int, nnz: int, rowptr_ptr: int, col_ptr: int, val_ptr: int, val_dtype: int,
-                      opts: PlanOpts | None, ws_ptr: int, ws_bytes: int, stream: int = 0) -> C.c_void_p:
+                      opts: PlanOpts | None, ws_ptr: int, ws_bytes: int, plan_ptr: int = 0, plan_bytes: int = 0,
+                      keep_host_copy: bool = True, stream: int = 0) -> C.c_void_p:
     handle = C.c_void_p()
     rc = lib().libra_plan_device(M, Kc, nnz, C.c_void_p(rowptr_ptr), C.c_void_p(col_ptr), C.c_void_p(val_ptr), val_dtype,
                                  C.byref(opts) if opts is not None else None, C.c_void_p(ws_ptr), ws_bytes,
+                                 C.c_void_p(plan_ptr), plan_bytes, 1 if keep_host_copy else 0,
                                  C.c_void_p(stream), C.byref(handle))
     _check(rc, "libra_plan_device")
     return handle
@@ -253,8 +264,9 @@ class Plan:
         self._buf = None
 
     @classmethod
-    def from_device_csr(cls, M, Kc, rowptr, col, val, **opts):
-        """Plan built on the GPU from torch tensors (int32 rowptr/col, float16 / bfloat16 / float32 values)."""
+    def from_device_csr(cls, M, Kc, rowptr, col, val, resident: bool = False, keep_host_copy: bool = True, **opts):
+        """Plan built on the GPU from torch tensors (int32 rowptr/col, float16 / bfloat16 / float32 values).
+        ``resident``: the device copy is written during planning into a buffer of the bound size (no upload)."""
         import torch
         assert rowptr.is_cuda and rowptr.dtype == torch.int32 and rowptr.is_contiguous() and rowptr.numel() == M + 1
         nnz = int(col.numel())
@@ -268,9 +280,13 @@ class Plan:
         ws = torch.empty(ws_bytes, dtype=torch.uint8, device=rowptr.device)
         self.handle = None
         self._buf = None
+        if resident:
+            nb = libra_plan_device_buffer_bound(self.M, nnz, self.val_dtype, o)
+            self._buf = torch.empty(nb, dtype=torch.uint8, device=rowptr.device)
         self.handle = libra_plan_device(self.M, self.Kc, nnz, rowptr.data_ptr(), col.data_ptr() if nnz else 0,
                                         val.data_ptr() if nnz else 0, self.val_dtype, o, ws.data_ptr(), ws_bytes,
-                                        torch.cuda.current_stream().cuda_stream)
+                                        self._buf.data_ptr() if resident else 0, self._buf.numel() if resident else 0,
+                                        keep_host_copy or not resident, torch.cuda.current_stream().cuda_stream)
         del ws
         self.nnz = libra_plan_stats(self.handle)["nnz"]
         return self

@@ -810,10 +810,10 @@ int spmm_piece(const libra_plan_t *P, const void *B, int n, int64_t ldb, float *
     const SubPlan &sp = P->spmm;
     SpmmArgs a{sp.dev.tasks, sp.dev.blk_cols, sp.dev.blk_bitmap, sp.dev.blk_valptr, sp.dev.dense_val,
                sp.dev.res_ent, B, C, ldb, ldc};
-    if (!sp.zero_rows.empty()) {
-        const int64_t total = (int64_t)sp.zero_rows.size() * (n / 4);
+    if (sp.n.zero_rows) {
+        const int64_t total = sp.n.zero_rows * (n / 4);
         const unsigned blocks = (unsigned)std::min<int64_t>((total + 255) / 256, 65536);
-        hipLaunchKernelGGL(zero_rows_kernel, dim3(blocks), dim3(256), 0, s, sp.dev.zero_rows, (int64_t)sp.zero_rows.size(), C, ldc, n / 4);
+        hipLaunchKernelGGL(zero_rows_kernel, dim3(blocks), dim3(256), 0, s, sp.dev.zero_rows, sp.n.zero_rows, C, ldc, n / 4);
         if (hipGetLastError() != hipSuccess) return LIBRA_ERR_HIP;
     }
     const int64_t nt = (int64_t)sp.tasks.size();
@@ -851,22 +851,24 @@ int spmm_piece(const libra_plan_t *P, const void *B, int n, int64_t ldb, float *
 namespace {
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
-// Lays arrays out back to back (256-byte aligned, 16 spare bytes each) and copies them.
+// Lays arrays out back to back (256-byte aligned, 16 spare bytes each) and copies them from host memory, from
+// device memory, or only reserves their place (arrays that a kernel packs afterwards).
 struct Uploader {
     char *base = nullptr;     // nullptr: size pass only
     size_t off = 0;
     hipStream_t s = nullptr;
     bool ok = true;
     template <class P>
-    void put(const void *src, size_t bytes, P *&dst) {
+    void put(const void *host_src, const void *dev_src, size_t bytes, P *&dst) {
         if (base) {
             dst = reinterpret_cast<P *>(base + off);
-            if (bytes && hipMemcpyAsync(base + off, src, bytes, hipMemcpyHostToDevice, s) != hipSuccess) ok = false;
+            if (bytes && host_src && hipMemcpyAsync(base + off, host_src, bytes, hipMemcpyHostToDevice, s) != hipSuccess) ok = false;
+            if (bytes && !host_src && dev_src && hipMemcpyAsync(base + off, dev_src, bytes, hipMemcpyDeviceToDevice, s) != hipSuccess) ok = false;
         }
         off += align256(bytes + 16);
     }
     template <class V, class P>
-    void putv(const V &v, P *&dst) { put(v.data(), v.size() * sizeof(v[0]), dst); }
+    void putv(const V &v, P *&dst) { put(v.data(), nullptr, v.size() * sizeof(v[0]), dst); }
 };
 
 std::vector<DevTask> pack_tasks(const libra_plan_t *P, const SubPlan &sp, bool spmm) {
@@ -895,22 +897,49 @@ struct Staging {
     std::vector<SdPv> sdpv;
 };
 
-void layout(libra_plan_t *P, Uploader &u, Staging *st) {
-    u.putv(P->rowptr, P->d_rowptr);
+// Record layouts written on the device when the arrays come from the device planner.
+template <class ENT, class V>
+__global__ __launch_bounds__(256) void pack_spmm_entries_kernel(const int32_t *col, const V *val, const int32_t *row, int64_t n, ENT *out) {
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
+        ENT e{};
+        e.col = col[i];
+        e.val = val[i];
+        e.row = (decltype(e.row))(row[i] % W);
+        out[i] = e;
+    }
+}
+template <class V>
+__global__ __launch_bounds__(256) void pack_sddmm_entries_kernel(const int32_t *row, const int32_t *col, const int32_t *perm, const V *val, int64_t n, SdEnt *out) {
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x)
+        out[i] = SdEnt{row[i], col[i], perm[i], (uint32_t)val[i]};
+}
+template <class V>
+__global__ __launch_bounds__(256) void pack_sddmm_values_kernel(const int32_t *perm, const V *val, int64_t n, SdPv *out) {
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x)
+        out[i] = SdPv{perm[i], (uint32_t)val[i]};
+}
+
+// st == nullptr: size pass.  da/dd == nullptr: the arrays come from the plan's host vectors; otherwise from
+// device memory, and the packed record arrays are only reserved here (adopt_device_arrays fills them).
+void layout(libra_plan_t *P, Uploader &u, Staging *st, const DeviceSource *da, const DeviceSource *dd) {
+    u.put(st ? (const void *)P->rowptr.data() : nullptr, nullptr, (size_t)(P->M + 1) * 4, P->d_rowptr);
     u.putv(P->long_rows, P->d_long_rows);
     u.putv(P->medium_rows, P->d_medium_rows);
     SubPlan &sa = P->spmm, &sd = P->sddmm;
     const bool f16 = P->vdt != LIBRA_F32;      // 16-bit storage (binary16 or bfloat16): same records
+    const size_t vs = (size_t)P->vsize;
+    const bool from_host = st && !da;
+    auto H = [&](const void *p) { return from_host ? p : nullptr; };
     // ---- SpMM ----
     if (st) st->tasks_a = pack_tasks(P, sa, true);
-    u.put(st ? (const void *)st->tasks_a.data() : nullptr, sa.tasks.size() * sizeof(DevTask), sa.dev.tasks);
-    u.putv(sa.blk_cols, sa.dev.blk_cols);
-    u.putv(sa.blk_bitmap, sa.dev.blk_bitmap);
-    u.putv(sa.blk_valptr, sa.dev.blk_valptr);
-    u.putv(sa.dense_val, sa.dev.dense_val);
-    u.putv(sa.dense_perm, sa.dev.dense_perm);
-    const size_t nres = sa.res_perm.size();
-    if (st) {
+    u.put(st ? (const void *)st->tasks_a.data() : nullptr, nullptr, (size_t)sa.n.tasks * sizeof(DevTask), sa.dev.tasks);
+    u.put(H(sa.blk_cols.data()), da ? da->blk_cols : nullptr, (size_t)sa.n.col_slots * 4, sa.dev.blk_cols);
+    u.put(H(sa.blk_bitmap.data()), da ? da->blk_bitmap : nullptr, (size_t)sa.n.bitmap_words * 8, sa.dev.blk_bitmap);
+    u.put(H(sa.blk_valptr.data()), da ? da->blk_valptr : nullptr, P->o.build_spmm ? (size_t)(sa.n.blocks + 1) * 4 : 0, sa.dev.blk_valptr);
+    u.put(H(sa.dense_val.data()), da ? da->dense_val : nullptr, (size_t)sa.n.dense * vs, sa.dev.dense_val);
+    u.put(H(sa.dense_perm.data()), da ? da->dense_perm : nullptr, (size_t)sa.n.dense * 4, sa.dev.dense_perm);
+    const size_t nres = (size_t)sa.n.res;
+    if (from_host) {
         const int Wp = P->o.W;
         if (f16) {
             st->ent16.resize(nres);
@@ -922,51 +951,101 @@ void layout(libra_plan_t *P, Uploader &u, Staging *st) {
             for (size_t i = 0; i < nres; ++i) st->ent32[i] = {sa.res_col[i], v[i], sa.res_row[i] % Wp, 0};
         }
     }
-    if (f16) u.put(st ? (const void *)st->ent16.data() : nullptr, nres * sizeof(ResEnt16), sa.dev.res_ent);
-    else u.put(st ? (const void *)st->ent32.data() : nullptr, nres * sizeof(ResEnt32), sa.dev.res_ent);
-    u.putv(sa.res_perm, sa.dev.res_perm);
-    u.putv(sa.zero_rows, sa.dev.zero_rows);
+    if (f16) u.put(from_host ? (const void *)st->ent16.data() : nullptr, nullptr, nres * sizeof(ResEnt16), sa.dev.res_ent);
+    else u.put(from_host ? (const void *)st->ent32.data() : nullptr, nullptr, nres * sizeof(ResEnt32), sa.dev.res_ent);
+    u.put(H(sa.res_perm.data()), da ? da->res_perm : nullptr, nres * 4, sa.dev.res_perm);
+    u.put(H(sa.zero_rows.data()), da ? da->zero_rows : nullptr, (size_t)sa.n.zero_rows * 4, sa.dev.zero_rows);
     // ---- SDDMM ----
     if (st) st->tasks_d = pack_tasks(P, sd, false);
-    u.put(st ? (const void *)st->tasks_d.data() : nullptr, sd.tasks.size() * sizeof(DevTask), sd.dev.tasks);
-    u.putv(sd.blk_cols, sd.dev.blk_cols);
-    u.putv(sd.blk_bitmap, sd.dev.blk_bitmap);
-    u.putv(sd.blk_valptr, sd.dev.blk_valptr);
-    const size_t ndd = sd.dense_perm.size();
-    if (st) {
+    u.put(st ? (const void *)st->tasks_d.data() : nullptr, nullptr, (size_t)sd.n.tasks * sizeof(DevTask), sd.dev.tasks);
+    u.put(H(sd.blk_cols.data()), dd ? dd->blk_cols : nullptr, (size_t)sd.n.col_slots * 4, sd.dev.blk_cols);
+    u.put(H(sd.blk_bitmap.data()), dd ? dd->blk_bitmap : nullptr, (size_t)sd.n.bitmap_words * 8, sd.dev.blk_bitmap);
+    u.put(H(sd.blk_valptr.data()), dd ? dd->blk_valptr : nullptr, P->o.build_sddmm ? (size_t)(sd.n.blocks + 1) * 4 : 0, sd.dev.blk_valptr);
+    const size_t ndd = (size_t)sd.n.dense;
+    if (from_host) {
         st->sdpv.resize(ndd);
         for (size_t i = 0; i < ndd; ++i) {
             uint32_t bits = 0;
-            std::memcpy(&bits, sd.dense_val.data() + i * P->vsize, P->vsize);
+            std::memcpy(&bits, sd.dense_val.data() + i * vs, vs);
             st->sdpv[i] = {sd.dense_perm[i], bits};
         }
     }
-    u.put(st ? (const void *)st->sdpv.data() : nullptr, ndd * sizeof(SdPv), sd.dev.dense_pv);
-    u.putv(sd.dense_perm, sd.dev.dense_perm);
-    const size_t nrd = sd.res_perm.size();
-    if (st) {
+    u.put(from_host ? (const void *)st->sdpv.data() : nullptr, nullptr, ndd * sizeof(SdPv), sd.dev.dense_pv);
+    u.put(H(sd.dense_perm.data()), dd ? dd->dense_perm : nullptr, ndd * 4, sd.dev.dense_perm);
+    const size_t nrd = (size_t)sd.n.res;
+    if (from_host) {
         st->sdent.resize(nrd);
         for (size_t i = 0; i < nrd; ++i) {
             uint32_t bits = 0;
-            std::memcpy(&bits, sd.res_val.data() + i * P->vsize, P->vsize);
+            std::memcpy(&bits, sd.res_val.data() + i * vs, vs);
             st->sdent[i] = {sd.res_row[i], sd.res_col[i], sd.res_perm[i], bits};
         }
     }
-    u.put(st ? (const void *)st->sdent.data() : nullptr, nrd * sizeof(SdEnt), sd.dev.res_ent);
-    u.putv(sd.res_perm, sd.dev.res_perm);
+    u.put(from_host ? (const void *)st->sdent.data() : nullptr, nullptr, nrd * sizeof(SdEnt), sd.dev.res_ent);
+    u.put(H(sd.res_perm.data()), dd ? dd->res_perm : nullptr, nrd * 4, sd.dev.res_perm);
 }
 }  // namespace
 
+size_t libra::plan_buffer_bytes(const libra_plan_t *plan) {
+    Uploader u;
+    layout(const_cast<libra_plan_t *>(plan), u, nullptr, nullptr, nullptr);
+    return u.off + 256;
+}
+
+int libra::adopt_device_arrays(libra_plan_t *P, const DeviceSource &da, const DeviceSource &dd, void *dev_buf, size_t bytes, void *stream) {
+    if (!dev_buf) return LIBRA_ERR_NULL;
+    if (bytes < plan_buffer_bytes(P) || ((uintptr_t)dev_buf & 255)) return LIBRA_ERR_BUFFER;
+    hipStream_t s = (hipStream_t)stream;
+    try {
+        Staging st;
+        Uploader u;
+        u.base = (char *)dev_buf;
+        u.s = s;
+        layout(P, u, &st, &da, &dd);
+        auto grid = [](int64_t n) { return dim3((unsigned)std::min<int64_t>((n + 255) / 256, 1 << 16)); };
+        const SubPlan &sa = P->spmm, &sd = P->sddmm;
+        if (sa.n.res) {
+            if (P->vdt == LIBRA_F32)
+                hipLaunchKernelGGL((pack_spmm_entries_kernel<ResEnt32, float>), grid(sa.n.res), dim3(256), 0, s, da.res_col,
+                                   (const float *)da.res_val, da.res_row, sa.n.res, (ResEnt32 *)sa.dev.res_ent);
+            else
+                hipLaunchKernelGGL((pack_spmm_entries_kernel<ResEnt16, uint16_t>), grid(sa.n.res), dim3(256), 0, s, da.res_col,
+                                   (const uint16_t *)da.res_val, da.res_row, sa.n.res, (ResEnt16 *)sa.dev.res_ent);
+        }
+        if (sd.n.res) {
+            if (P->vdt == LIBRA_F32)
+                hipLaunchKernelGGL((pack_sddmm_entries_kernel<uint32_t>), grid(sd.n.res), dim3(256), 0, s, dd.res_row, dd.res_col, dd.res_perm,
+                                   (const uint32_t *)dd.res_val, sd.n.res, (SdEnt *)sd.dev.res_ent);
+            else
+                hipLaunchKernelGGL((pack_sddmm_entries_kernel<uint16_t>), grid(sd.n.res), dim3(256), 0, s, dd.res_row, dd.res_col, dd.res_perm,
+                                   (const uint16_t *)dd.res_val, sd.n.res, (SdEnt *)sd.dev.res_ent);
+        }
+        if (sd.n.dense) {
+            if (P->vdt == LIBRA_F32)
+                hipLaunchKernelGGL((pack_sddmm_values_kernel<uint32_t>), grid(sd.n.dense), dim3(256), 0, s, dd.dense_perm,
+                                   (const uint32_t *)dd.dense_val, sd.n.dense, (SdPv *)sd.dev.dense_pv);
+            else
+                hipLaunchKernelGGL((pack_sddmm_values_kernel<uint16_t>), grid(sd.n.dense), dim3(256), 0, s, dd.dense_perm,
+                                   (const uint16_t *)dd.dense_val, sd.n.dense, (SdPv *)sd.dev.dense_pv);
+        }
+        if (hipGetLastError() != hipSuccess || hipStreamSynchronize(s) != hipSuccess || !u.ok) return LIBRA_ERR_HIP;
+    } catch (...) {
+        return LIBRA_ERR_NOMEM;
+    }
+    P->dev_base = dev_buf;
+    P->dev_bytes = bytes;
+    return LIBRA_OK;
+}
+
 extern "C" int libra_plan_device_bytes(const libra_plan_t *plan, size_t *bytes) {
     if (!plan || !bytes) return LIBRA_ERR_NULL;
-    Uploader u;
-    layout(const_cast<libra_plan_t *>(plan), u, nullptr);
-    *bytes = u.off + 256;
+    *bytes = plan_buffer_bytes(plan);
     return LIBRA_OK;
 }
 
 extern "C" int libra_plan_upload(libra_plan_t *plan, void *dev_buf, size_t bytes, void *stream) {
     if (!plan || !dev_buf) return LIBRA_ERR_NULL;
+    if (!plan->host_arrays) return LIBRA_ERR_NOT_BUILT;      // built on the device without a host copy: nothing to upload
     size_t need = 0;
     libra_plan_device_bytes(plan, &need);
     if (bytes < need || ((uintptr_t)dev_buf & 255)) return LIBRA_ERR_BUFFER;
@@ -975,7 +1054,7 @@ extern "C" int libra_plan_upload(libra_plan_t *plan, void *dev_buf, size_t bytes
         Uploader u;
         u.base = (char *)dev_buf;
         u.s = (hipStream_t)stream;
-        layout(plan, u, &st);
+        layout(plan, u, &st, nullptr, nullptr);
         if (hipStreamSynchronize(u.s) != hipSuccess || !u.ok) return LIBRA_ERR_HIP;
     } catch (...) {
         return LIBRA_ERR_NOMEM;
@@ -1021,7 +1100,7 @@ extern "C" int libra_sddmm(const libra_plan_t *P, const void *X, const void *Y, 
     hipStream_t s = (hipStream_t)stream;
     const SubPlan &sp = P->sddmm;
     SddmmArgs a{sp.dev.tasks, sp.dev.blk_cols, sp.dev.blk_bitmap, sp.dev.blk_valptr,
-                reinterpret_cast<const uint2 *>(sp.dev.dense_pv), (int32_t)sp.dense_perm.size(),
+                reinterpret_cast<const uint2 *>(sp.dev.dense_pv), (int32_t)sp.n.dense,
                 reinterpret_cast<const SdEnt *>(sp.dev.res_ent), X, Y, out, P->M};
     const int64_t nt = (int64_t)sp.tasks.size();
     if (nt == 0) return LIBRA_OK;
@@ -1083,10 +1162,10 @@ extern "C" int libra_plan_set_values(libra_plan_t *P, const void *vals, int dtyp
     struct Seg { const int32_t *perm; void *dst; int64_t n; int stride, offset; };
     const SubPlan &sa = P->spmm, &sd = P->sddmm;
     const Seg segs[4] = {
-        {sa.dev.dense_perm, sa.dev.dense_val, (int64_t)sa.dense_perm.size(), vs, 0},
-        {sa.dev.res_perm, sa.dev.res_ent, (int64_t)sa.res_perm.size(), f16 ? (int)sizeof(ResEnt16) : (int)sizeof(ResEnt32), 4},
-        {sd.dev.dense_perm, sd.dev.dense_pv, (int64_t)sd.dense_perm.size(), (int)sizeof(SdPv), 4},
-        {sd.dev.res_perm, sd.dev.res_ent, (int64_t)sd.res_perm.size(), (int)sizeof(SdEnt), 12}};
+        {sa.dev.dense_perm, sa.dev.dense_val, sa.n.dense, vs, 0},
+        {sa.dev.res_perm, sa.dev.res_ent, sa.n.res, f16 ? (int)sizeof(ResEnt16) : (int)sizeof(ResEnt32), 4},
+        {sd.dev.dense_perm, sd.dev.dense_pv, sd.n.dense, (int)sizeof(SdPv), 4},
+        {sd.dev.res_perm, sd.dev.res_ent, sd.n.res, (int)sizeof(SdEnt), 12}};
     for (const Seg &g : segs) {
         if (g.n == 0) continue;
         const unsigned blocks = (unsigned)std::min<int64_t>((g.n + 255) / 256, 1 << 16);

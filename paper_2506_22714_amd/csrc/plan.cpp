@@ -345,11 +345,11 @@ void xcd_order(std::vector<libra_task_t> &tasks, size_t begin, size_t end, Group
 double neighbour_share(int64_t M, const int32_t *rowptr, const ColumnFetch &cols, int W) {
     const int64_t rows_per_group = (int64_t)W * LIBRA_LOCALITY_WINDOWS;
     const int64_t ngroups = (M + rows_per_group - 1) / rows_per_group;
-    const int64_t nsample = std::min<int64_t>(ngroups, 256);
+    const int64_t nsample = share_samples(ngroups);
     std::vector<uint64_t> keys;
     int64_t together = 0, apart = 0;
     for (int64_t k = 0; k < nsample; ++k) {
-        const int64_t g = k * ngroups / nsample;
+        const int64_t g = sampled_group(k, ngroups, nsample);
         const int64_t r0 = g * rows_per_group, r1 = std::min(M, r0 + rows_per_group);
         keys.clear();
         const int32_t *col = cols(rowptr[r0], rowptr[r1]) - rowptr[r0];      // indexable by CSR position
@@ -400,7 +400,7 @@ int libra::resolve_options(const libra_plan_opts_t *in, int vdt, Resolved &o) {
 
 // Shared tail of the host and the device planner: the flat SDDMM residual segments, the order of the task
 // tables and the statistics.  Expects the sub-plans with their tasks in window order.
-void libra::finish_plan(libra_plan_t *P, const ColumnFetch &cols) {
+void libra::finish_plan(libra_plan_t *P, const ColumnFetch &cols, const int64_t *share) {
     const Resolved o = P->o;
     const int64_t M = P->M, nnz = P->nnz;
     const int32_t *rowptr = P->rowptr.data();
@@ -415,16 +415,20 @@ void libra::finish_plan(libra_plan_t *P, const ColumnFetch &cols) {
     }
     if (!o.build_spmm) sa = SubPlan();
     if (!o.build_sddmm) sd = SubPlan();
+    if (P->host_arrays) {
+        sa.count_host_arrays();
+        sd.count_host_arrays();
+    }
     if (o.build_sddmm) {
         // scalar segments over the flat residual list (no atomics needed: each output has one writer)
-        const int32_t nres = (int32_t)sd.res_perm.size();
+        const int32_t nres = (int32_t)sd.n.res;
         for (int32_t q = 0; q < nres; q += o.sddmm_Cs) {
             int32_t q1 = std::min(nres, q + o.sddmm_Cs);
             sd.tasks.push_back({LIBRA_TASK_CHUNK, 0, 0, 0, q, q1, 0u, 0u, 0u, (uint32_t)(2 * (q1 - q))});
         }
     }
     // ---- ordering: heaviest first, so that the tail of the launch is made of light tasks ----
-    st.neighbour_share = neighbour_share(M, rowptr, cols, o.W);
+    st.neighbour_share = share ? (share[1] ? (double)share[0] / (double)share[1] : 1.0) : neighbour_share(M, rowptr, cols, o.W);
     if (o.heavy_first) {
         auto heavier = [](const libra_task_t &a, const libra_task_t &b) { return a.cost > b.cost; };
         std::stable_sort(sa.tasks.begin(), sa.tasks.end(), heavier);
@@ -447,23 +451,25 @@ void libra::finish_plan(libra_plan_t *P, const ColumnFetch &cols) {
                 return (int64_t)t.id / LIBRA_LOCALITY_WINDOWS; }, LIBRA_TASK_CHUNK);
         }
     }
-    for (SubPlan *sp : {&sa, &sd})
+    for (SubPlan *sp : {&sa, &sd}) {
         for (auto &t : sp->tasks) (t.kind == LIBRA_TASK_WINDOW ? sp->n_window_tasks : sp->n_chunk_tasks)++;
+        sp->n.tasks = (int64_t)sp->tasks.size();
+    }
 
     st.M = M; st.Kc = P->Kc; st.nnz = nnz; st.n_windows = nwin;
     if (o.build_spmm) {
-        st.spmm_dense_vectors = sa.dense_vectors; st.spmm_blocks = sa.n_blocks(); st.spmm_pad_slots = sa.pad_slots;
-        st.spmm_dense_nnz = (int64_t)sa.dense_perm.size(); st.spmm_res_nnz = (int64_t)sa.res_perm.size();
+        st.spmm_dense_vectors = sa.dense_vectors; st.spmm_blocks = sa.n.blocks; st.spmm_pad_slots = sa.pad_slots;
+        st.spmm_dense_nnz = sa.n.dense; st.spmm_res_nnz = sa.n.res;
         st.spmm_tasks = (int64_t)sa.tasks.size(); st.spmm_chunk_tasks = sa.n_chunk_tasks;
-        st.spmm_zero_rows = (int64_t)sa.zero_rows.size();
+        st.spmm_zero_rows = sa.n.zero_rows;
         st.spmm_short_rows = sa.short_rows; st.spmm_long_rows = sa.long_rows; st.spmm_split_rows = sa.split_rows;
         st.spmm_gather_rows = sa.dense_vectors + st.spmm_res_nnz;
     }
     if (o.build_sddmm) {
-        st.sddmm_dense_vectors = sd.dense_vectors; st.sddmm_blocks = sd.n_blocks(); st.sddmm_pad_slots = sd.pad_slots;
-        st.sddmm_dense_nnz = (int64_t)sd.dense_perm.size(); st.sddmm_res_nnz = (int64_t)sd.res_perm.size();
+        st.sddmm_dense_vectors = sd.dense_vectors; st.sddmm_blocks = sd.n.blocks; st.sddmm_pad_slots = sd.pad_slots;
+        st.sddmm_dense_nnz = sd.n.dense; st.sddmm_res_nnz = sd.n.res;
         st.sddmm_tasks = (int64_t)sd.tasks.size();
-        st.sddmm_gather_rows = sd.dense_vectors + (int64_t)o.W * sd.n_blocks() + 2 * st.sddmm_res_nnz;
+        st.sddmm_gather_rows = sd.dense_vectors + (int64_t)o.W * sd.n.blocks + 2 * st.sddmm_res_nnz;
     }
 }
 
@@ -574,6 +580,7 @@ static void fill_view(const libra_plan_t *P, const SubPlan &sp, bool spmm, libra
 
 extern "C" int libra_plan_export(const libra_plan_t *plan, int which, libra_subplan_view_t *view) {
     if (!plan || !view) return LIBRA_ERR_NULL;
+    if (!plan->host_arrays) return LIBRA_ERR_NOT_BUILT;      // built on the device without a host copy
     if (which == 0) {
         if (!plan->o.build_spmm) return LIBRA_ERR_NOT_BUILT;
         fill_view(plan, plan->spmm, true, view);

@@ -23,6 +23,8 @@
 #include <hip/hip_runtime.h>
 
 #include <chrono>
+#include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 
@@ -37,7 +39,7 @@ namespace {
 constexpr int W = 16, KB = 16;
 typedef unsigned long long u64;
 
-enum Counter { C_NV = 0, C_NNZ1, C_SHORT, C_LONG, C_SPLIT, C_DV_A, C_PAD_A, C_DV_D, C_PAD_D, C_ERR, C_COUNT };
+enum Counter { C_NV = 0, C_NNZ1, C_SHORT, C_LONG, C_SPLIT, C_DV_A, C_PAD_A, C_DV_D, C_PAD_D, C_ERR, C_TOGETHER, C_APART, C_COUNT };
 
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
@@ -269,6 +271,40 @@ __global__ __launch_bounds__(256) void k_sorted(const int32_t *sv, const int32_t
     const int v = sv[k];
     scnt[k] = vinfo[v] & 0xff;
     srank[v] = k - win_vptr[vwin[v]];
+}
+
+// The sampled column-sharing statistic (one workgroup per sampled group of LIBRA_LOCALITY_WINDOWS windows): how
+// many distinct columns the windows have together (a vector counts unless an earlier window of the group has its
+// column) and one by one.
+__global__ __launch_bounds__(256) void k_share(const int32_t *win_vptr, const int32_t *vcol, int nw, int64_t ngroups, int64_t nsample, u64 *ctr) {
+    __shared__ int together;
+    if (threadIdx.x == 0) together = 0;
+    __syncthreads();
+    const int64_t g = sampled_group(blockIdx.x, ngroups, nsample);
+    const int w0 = (int)(g * LIBRA_LOCALITY_WINDOWS), w1 = (int)min((int64_t)nw, (g + 1) * LIBRA_LOCALITY_WINDOWS);
+    const int v0 = win_vptr[w0], v1 = win_vptr[w1];
+    int mine = 0;
+    for (int v = v0 + (int)threadIdx.x; v < v1; v += (int)blockDim.x) {
+        const int c = vcol[v];
+        bool seen = false;
+        for (int w = w0; w < w1 && !seen; ++w) {
+            const int a = win_vptr[w], b = win_vptr[w + 1];
+            if (b > v) break;                     // only the windows before the vector's own
+            int lo = a, hi = b;                   // first position with column >= c
+            while (lo < hi) {
+                const int mid = (lo + hi) >> 1;
+                if (vcol[mid] < c) lo = mid + 1; else hi = mid;
+            }
+            seen = lo < b && vcol[lo] == c;
+        }
+        mine += seen ? 0 : 1;
+    }
+    if (mine) atomicAdd(&together, mine);
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        atomicAdd(&ctr[C_TOGETHER], (u64)together);
+        atomicAdd(&ctr[C_APART], (u64)(v1 - v0));
+    }
 }
 
 struct Rule {
@@ -610,9 +646,37 @@ extern "C" int libra_plan_device_workspace(int64_t M, int64_t nnz, const libra_p
     return LIBRA_OK;
 }
 
+extern "C" int libra_plan_device_buffer_bound(int64_t M, int64_t nnz, int val_dtype, const libra_plan_opts_t *opts, size_t *bytes) {
+    if (!bytes) return LIBRA_ERR_NULL;
+    if (M < 1 || nnz < 0) return LIBRA_ERR_SHAPE;
+    if (M >= (1ll << 31) - 64 || nnz >= (1ll << 31) - 64) return LIBRA_ERR_TOO_LARGE;
+    if (val_dtype != LIBRA_F16 && val_dtype != LIBRA_BF16 && val_dtype != LIBRA_F32) return LIBRA_ERR_DTYPE;
+    Resolved o{};
+    if (int rc = resolve_options(opts, val_dtype, o)) return rc;
+    if (o.W != W || o.KB != KB) return LIBRA_ERR_UNSUPPORTED;
+    try {
+        // a plan with the largest arrays this matrix size can produce (only the sizes matter)
+        const Sizes z = make_sizes(M, std::max<int64_t>(nnz, 1), o);
+        libra_plan_t fake;
+        fake.M = M; fake.nnz = nnz; fake.vdt = val_dtype; fake.vsize = val_dtype == LIBRA_F32 ? 4 : 2;
+        fake.o = o;
+        for (SubPlan *sp : {&fake.spmm, &fake.sddmm}) {
+            sp->n.blocks = z.nbmax; sp->n.col_slots = z.nbmax * KB; sp->n.bitmap_words = z.nbmax * 4;
+            sp->n.dense = nnz; sp->n.res = nnz;
+        }
+        fake.spmm.n.zero_rows = M;
+        fake.spmm.n.tasks = 2 * z.tasks_a_max + 64;                                // the die-aware order may add empty tasks
+        fake.sddmm.n.tasks = 2 * (z.tasks_d_max + nnz / o.sddmm_Cs + 1) + 64;
+        *bytes = plan_buffer_bytes(&fake) + 2 * align256((size_t)M * 4 + 16);      // + the two row lists of the edge softmax
+    } catch (...) {
+        return LIBRA_ERR_NOMEM;
+    }
+    return LIBRA_OK;
+}
+
 extern "C" int libra_plan_device(int64_t M, int64_t Kc, int64_t nnz, const int32_t *d_rowptr, const int32_t *d_col, const void *d_val,
-                                 int val_dtype, const libra_plan_opts_t *opts, void *workspace, size_t workspace_bytes, void *stream,
-                                 libra_plan_t **out) {
+                                 int val_dtype, const libra_plan_opts_t *opts, void *workspace, size_t workspace_bytes,
+                                 void *plan_buf, size_t plan_bytes, int keep_host_copy, void *stream, libra_plan_t **out) {
     if (!out) return LIBRA_ERR_NULL;
     *out = nullptr;
     if (!d_rowptr) return LIBRA_ERR_NULL;
@@ -623,8 +687,15 @@ extern "C" int libra_plan_device(int64_t M, int64_t Kc, int64_t nnz, const int32
     if (int rc = resolve_options(opts, val_dtype, o)) return rc;
     if (o.W != W || o.KB != KB) return LIBRA_ERR_UNSUPPORTED;
     if (nnz > 0 && (!d_col || !d_val || !workspace)) return LIBRA_ERR_NULL;
+    if (!plan_buf) keep_host_copy = 1;          // the plan has to live somewhere
     hipStream_t s = (hipStream_t)stream;
     const auto t0 = std::chrono::steady_clock::now();
+    // LIBRA_TRACE=1 in the environment prints where the call's time goes (stderr)
+    const bool trace = std::getenv("LIBRA_TRACE") != nullptr;
+    auto mark = [&](const char *what) {
+        if (trace) std::fprintf(stderr, "[libra_plan_device] %-28s %8.3f ms\n", what,
+                                1e3 * std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count());
+    };
 
     libra_plan_t *P = new (std::nothrow) libra_plan_t();
     if (!P) return LIBRA_ERR_NOMEM;
@@ -640,8 +711,14 @@ extern "C" int libra_plan_device(int64_t M, int64_t Kc, int64_t nnz, const int32
             // nothing to sort or scan: the plan of a matrix without nonzeros (one empty task per window) needs no device work
             const std::vector<int32_t> rp = P->rowptr;
             delete P;
-            return libra_plan(M, Kc, rp.data(), nullptr, nullptr, val_dtype, opts, out);
+            int rc = libra_plan(M, Kc, rp.data(), nullptr, nullptr, val_dtype, opts, out);
+            if (rc == LIBRA_OK && plan_buf && (rc = libra_plan_upload(*out, plan_buf, plan_bytes, stream)) != LIBRA_OK) {
+                libra_plan_destroy(*out);
+                *out = nullptr;
+            }
+            return rc;
         }
+        mark("rowptr on the host, checked");
         const Sizes z = make_sizes(M, nnz, o);
         const Layout L = make_layout(z, P->vsize, workspace);
         if (((uintptr_t)workspace & 255) || workspace_bytes < L.total) throw Fail{LIBRA_ERR_BUFFER};
@@ -677,6 +754,7 @@ extern "C" int libra_plan_device(int64_t M, int64_t Kc, int64_t nnz, const int32
         if (ctr[C_ERR] & 2) throw Fail{LIBRA_ERR_UNSORTED};
         const int nv = (int)ctr[C_NV];
         if (nv < 1 || nv > n) throw Fail{LIBRA_ERR_HIP};
+        mark("census (sort 1, vectors)");
         // order of a window's vectors: NNZ descending, column ascending
         {
             size_t sz = L.tmp_bytes;
@@ -697,6 +775,7 @@ extern "C" int libra_plan_device(int64_t M, int64_t Kc, int64_t nnz, const int32
         scan(L, L.d.nb, L.d.blkptr, (size_t)nw + 1, s);
         const int nbA = peek(L.a.blkptr + nw, s), nbD = peek(L.d.blkptr + nw, s);
         if (nbA < 0 || nbD < 0 || nbA > z.nbmax || nbD > z.nbmax) throw Fail{LIBRA_ERR_HIP};
+        mark("sort 2, window counts");
         // ---- 4. slots, blocks, packed values ----
         fill_bytes(L.a.slotvec, 0xff, (size_t)nbA * KB * sizeof(int32_t), s);
         fill_bytes(L.d.slotvec, 0xff, (size_t)nbD * KB * sizeof(int32_t), s);
@@ -743,6 +822,8 @@ extern "C" int libra_plan_device(int64_t M, int64_t Kc, int64_t nnz, const int32
                            L.a.blkptr, L.a.blkmask, L.a.blkncols, L.d.blkptr, L.d.blkncols,
                            L.a.ntasks, L.nzero, L.nres, L.d.ntasks, L.ctr, L.a.tbase, L.zbase, L.resptr, L.d.tbase,
                            L.a.tasks, L.zero_rows, L.d.tasks);
+        const int64_t ngroups = (nw + LIBRA_LOCALITY_WINDOWS - 1) / LIBRA_LOCALITY_WINDOWS, nsample = share_samples(ngroups);
+        hipLaunchKernelGGL(k_share, dim3((unsigned)nsample), dim3(256), 0, s, L.win_vptr, L.vcol, nw, ngroups, nsample, L.ctr);
         hipLaunchKernelGGL(k_residual_fill, dim3((unsigned)nw), dim3(64), 0, s, d_rowptr, d_col, val, vsize, M, R,
                            L.a.resf, L.a.rescan, L.resptr, L.a.res_perm, L.a.res_row, L.a.res_col, L.a.res_val,
                            L.d.resf, L.d.rescan, L.d.res_perm, L.d.res_row, L.d.res_col, L.d.res_val);
@@ -750,28 +831,33 @@ extern "C" int libra_plan_device(int64_t M, int64_t Kc, int64_t nnz, const int32
         hip_ok(hipStreamSynchronize(s));
         if (hipGetLastError() != hipSuccess) throw Fail{LIBRA_ERR_HIP};
         P->stats.device_seconds = std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count();
+        mark("blocks, residual, tasks");
 
-        // ---- copy to the plan's host arrays (host planner's format) ----
+        // ---- sizes; the task tables always come to the host (their order is made there); the big arrays only on request ----
         SubPlan &sa = P->spmm, &sd = P->sddmm;
         const int nts[2] = {ntA, ntD}, nres2[2] = {nresA, nresD}, dn[2] = {dnnzA, dnnzD};
         SubPlan *hs[2] = {&sa, &sd};
+        P->host_arrays = keep_host_copy != 0;
         for (int k = 0; k < 2; ++k) {
             if (!(k == 0 ? o.build_spmm : o.build_sddmm)) continue;
             const SubOut &S = *subs[k];
             SubPlan &H = *hs[k];
+            H.n.blocks = nbs[k]; H.n.col_slots = (int64_t)nbs[k] * KB; H.n.bitmap_words = (int64_t)nbs[k] * 4;
+            H.n.dense = dn[k]; H.n.res = nres2[k]; H.n.zero_rows = k == 0 ? nz : 0;
+            fetch(H.tasks, S.tasks, (size_t)nts[k], s);
+            fetch(H.blk_valptr, S.blk_valptr, (size_t)nbs[k] + 1, s);
+            if (!keep_host_copy) continue;
             fetch(H.win_blkptr, S.blkptr, (size_t)nw + 1, s);
             fetch(H.blk_cols, S.blk_cols, (size_t)nbs[k] * KB, s);
             fetch(H.blk_bitmap, S.bitmap, (size_t)nbs[k] * 4, s);
-            fetch(H.blk_valptr, S.blk_valptr, (size_t)nbs[k] + 1, s);
             fetch(H.dense_perm, S.dense_perm, (size_t)dn[k], s);
             fetch(H.dense_val, S.dense_val, (size_t)dn[k] * vsize, s);
             fetch(H.res_perm, S.res_perm, (size_t)nres2[k], s);
             fetch(H.res_row, S.res_row, (size_t)nres2[k], s);
             fetch(H.res_col, S.res_col, (size_t)nres2[k], s);
             fetch(H.res_val, S.res_val, (size_t)nres2[k] * vsize, s);
-            fetch(H.tasks, S.tasks, (size_t)nts[k], s);
         }
-        if (o.build_spmm) {
+        if (o.build_spmm && keep_host_copy) {
             fetch(sa.win_resptr, L.resptr, (size_t)nw + 1, s);
             fetch(sa.zero_rows, L.zero_rows, (size_t)nz, s);
         }
@@ -781,16 +867,19 @@ extern "C" int libra_plan_device(int64_t M, int64_t Kc, int64_t nnz, const int32
         sa.short_rows = (int64_t)ctr[C_SHORT]; sa.long_rows = (int64_t)ctr[C_LONG]; sa.split_rows = (int64_t)ctr[C_SPLIT];
         P->stats.n_vectors = nv;
         P->stats.n_vectors_nnz1 = (int64_t)ctr[C_NNZ1];
-        // the sampled column-sharing statistic reads a few hundred short column ranges
-        std::vector<int32_t> colbuf;
-        finish_plan(P, [&](int64_t p0, int64_t p1) -> const int32_t * {
-            colbuf.resize((size_t)std::max<int64_t>(p1 - p0, 1));
-            if (p1 > p0) {
-                hip_ok(hipMemcpyAsync(colbuf.data(), d_col + p0, (size_t)(p1 - p0) * sizeof(int32_t), hipMemcpyDeviceToHost, s));
-                hip_ok(hipStreamSynchronize(s));
-            }
-            return colbuf.data();
-        });
+        mark("copies to the host");
+        const int64_t share[2] = {(int64_t)ctr[C_TOGETHER], (int64_t)ctr[C_APART]};
+        finish_plan(P, nullptr, share);
+        mark("task order, statistics");
+        if (plan_buf) {
+            // the plan's device copy straight from the workspace: no round trip through host memory
+            auto src = [&](const SubOut &S, const int32_t *zero_rows) {
+                return DeviceSource{S.blk_cols, S.blk_valptr, S.dense_perm, S.res_perm, S.res_row, S.res_col, zero_rows,
+                                    reinterpret_cast<const uint64_t *>(S.bitmap), S.dense_val, S.res_val};
+            };
+            if (int rc = adopt_device_arrays(P, src(L.a, L.zero_rows), src(L.d, nullptr), plan_buf, plan_bytes, stream)) throw Fail{rc};
+        }
+        mark("plan buffer written");
         P->stats.plan_seconds = std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count();
     } catch (const Fail &f) {
         delete P;

@@ -8,6 +8,12 @@
 
 #include "libra.h"
 
+#ifdef __HIPCC__
+#define LIBRA_HD __host__ __device__
+#else
+#define LIBRA_HD
+#endif
+
 #define LIBRA_SOFTMAX_LONG_ROW 2048
 #define LIBRA_XCDS 8                 // accelerator dies of an MI355X; workgroup k runs on die k mod 8
 #define LIBRA_LOCALITY_WINDOWS 4     // neighbouring windows whose tasks are kept on one die (XCD-aware order)
@@ -66,7 +72,21 @@ struct SubPlanDev {
     const int32_t *zero_rows = nullptr;
 };
 
+// Sizes of a sub-plan's arrays.  Set by finish_plan from the host vectors, or by the device planner when the
+// arrays only exist in device memory.
+struct Counts {
+    int64_t blocks = 0, col_slots = 0, bitmap_words = 0, dense = 0, res = 0, zero_rows = 0, tasks = 0;
+};
+
+// Where the device planner left a sub-plan's arrays (host planner's format, device memory).
+struct DeviceSource {
+    const int32_t *blk_cols, *blk_valptr, *dense_perm, *res_perm, *res_row, *res_col, *zero_rows;
+    const uint64_t *blk_bitmap;
+    const void *dense_val, *res_val;
+};
+
 struct SubPlan {
+    Counts n;
     std::vector<int32_t> win_blkptr, blk_cols, blk_valptr, dense_perm;
     std::vector<uint64_t> blk_bitmap;
     std::vector<uint8_t> dense_val, res_val;        // raw bytes, value dtype
@@ -76,7 +96,15 @@ struct SubPlan {
     int64_t dense_vectors = 0, pad_slots = 0;
     int64_t short_rows = 0, long_rows = 0, split_rows = 0;
     SubPlanDev dev;
-    int64_t n_blocks() const { return (int64_t)blk_valptr.size() - 1; }
+    int64_t n_blocks() const { return (int64_t)blk_valptr.size() - 1; }     // while the host planner appends
+    void count_host_arrays() {
+        n.blocks = blk_valptr.empty() ? 0 : (int64_t)blk_valptr.size() - 1;
+        n.col_slots = (int64_t)blk_cols.size();
+        n.bitmap_words = (int64_t)blk_bitmap.size();
+        n.dense = (int64_t)dense_perm.size();
+        n.res = (int64_t)res_perm.size();
+        n.zero_rows = (int64_t)zero_rows.size();
+    }
 };
 
 struct Resolved {
@@ -96,6 +124,7 @@ struct libra_plan_s {
     std::vector<int32_t> long_rows;     // rows with more than LIBRA_SOFTMAX_LONG_ROW nonzeros (edge softmax)
     std::vector<int32_t> medium_rows;   // rows with 65 .. LIBRA_SOFTMAX_LONG_ROW nonzeros
     libra::SubPlan spmm, sddmm;
+    bool host_arrays = true;            // false: built on the device without a host copy (nothing to export or upload)
     libra_stats_t stats{};
     // device copy
     void *dev_base = nullptr;
@@ -110,5 +139,15 @@ namespace libra {
 typedef std::function<const int32_t *(int64_t p0, int64_t p1)> ColumnFetch;
 int resolve_options(const libra_plan_opts_t *in, int value_dtype, Resolved &out);
 // Shared tail of the host and the device planner (segments of the SDDMM residual list, task order, statistics).
-void finish_plan(libra_plan_s *plan, const ColumnFetch &cols);
+// `share` (optional): the two sums of the sampled column-sharing statistic {together, apart} if the caller has
+// already counted them; otherwise they are counted from `cols`.
+void finish_plan(libra_plan_s *plan, const ColumnFetch &cols, const int64_t *share = nullptr);
+// The sample of that statistic: group k of `nsample` is sampled_group(k, ...) out of `ngroups` groups of
+// LIBRA_LOCALITY_WINDOWS windows.
+LIBRA_HD inline int64_t share_samples(int64_t ngroups) { return ngroups < 256 ? ngroups : 256; }
+LIBRA_HD inline int64_t sampled_group(int64_t k, int64_t ngroups, int64_t nsample) { return k * ngroups / nsample; }
+// Lay the plan out in `dev_buf` taking the big arrays from device memory (device planner) instead of the host vectors.
+int adopt_device_arrays(libra_plan_s *plan, const DeviceSource &spmm, const DeviceSource &sddmm, void *dev_buf, size_t bytes, void *stream);
+// Bytes libra_plan_upload / adopt_device_arrays need for a plan with these array sizes.
+size_t plan_buffer_bytes(const libra_plan_s *plan);
 }  // namespace libra

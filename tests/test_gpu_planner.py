@@ -127,6 +127,60 @@ def test_device_planner_value_types_and_results():
     assert torch.allclose(Ch, Cd, rtol=1e-4, atol=1e-3)
 
 
+def _run_all(p, A, B, X, Y):
+    """Every compute call on a ready plan; SpMM rows with several writers are returned separately."""
+    C1 = p.spmm(B)
+    out = torch.full((p.nnz,), float("nan"), dtype=torch.float32, device="cuda")
+    p.sddmm(X, Y, out=out)
+    alpha = p.edge_softmax(out, 0.25)
+    p.set_values(alpha)
+    C2 = p.spmm(B)
+    out2 = p.sddmm(X, Y)
+    torch.cuda.synchronize()
+    return C1, out, alpha, C2, out2
+
+
+@pytest.mark.parametrize("keep_host_copy", [True, False])
+@pytest.mark.parametrize("dtype", ["f16", "bf16", "f32"])
+def test_resident_device_plan_computes_like_an_uploaded_host_plan(dtype, keep_host_copy):
+    """The plan's device copy written by the planner itself (no host round trip) against libra_plan + libra_plan_upload."""
+    A = wl.make("powerlaw", small=True)
+    N, K = 64, 32
+    if dtype == "f32":
+        val, code, tdt = A.val.astype(np.float32) * 0.75, lb.F32, torch.float32
+        mk = lambda r, c, seed: torch.from_numpy(wl.dense_normal(r, c, seed=seed, dtype=np.float32)).cuda()
+    elif dtype == "bf16":
+        val, code, tdt = wl.to_bf16_bits(A.val.astype(np.float32) * 0.75), lb.BF16, torch.bfloat16
+        mk = lambda r, c, seed: torch.from_numpy(wl.dense_normal(r, c, seed=seed, dtype=np.float32)).cuda().to(torch.bfloat16)
+    else:
+        val, code, tdt = A.val, lb.F16, torch.float16
+        mk = lambda r, c, seed: torch.from_numpy(wl.dense_normal(r, c, seed=seed)).cuda()
+    B, X, Y = mk(A.Kc, N, 1), mk(A.M, K, 2), mk(A.Kc, K, 3)
+    kw = dict(cs=40, ts=2)
+    ph = lb.Plan.from_csr(A, val=val, val_dtype=code, **kw).upload()
+    pd = lb.Plan.from_device_csr(A.M, A.Kc, torch.from_numpy(A.rowptr.astype(np.int32)).cuda(), torch.from_numpy(A.col.astype(np.int32)).cuda(),
+                                 dev_val(val, code), resident=True, keep_host_copy=keep_host_copy, **kw)
+    assert lb.libra_plan_device_bytes(pd.handle) == lb.libra_plan_device_bytes(ph.handle) <= pd._buf.numel()
+    if keep_host_copy:
+        assert_same_plan(ph, pd)
+    else:
+        for call in (lambda: pd.export(0), lambda: pd.upload()):
+            with pytest.raises(lb.LibraError) as e:
+                call()
+            assert e.value.code == lb.ERR["NOT_BUILT"]
+        sh, sd = ph.stats(), pd.stats()
+        assert all(sh[k] == sd[k] for k in sh if k not in TIMES)
+    one_writer = torch.ones(A.M, dtype=torch.bool, device="cuda")
+    one_writer[torch.from_numpy(ph.export(0)["zero_rows"]).cuda().long()] = False
+    assert 0 < int(one_writer.sum()) < A.M
+    rh, rd = _run_all(ph, A, B, X, Y), _run_all(pd, A, B, X, Y)
+    for k in (1, 2, 4):                                     # SDDMM, softmax: one writer per output
+        assert torch.equal(rh[k], rd[k]), k
+    for k in (0, 3):
+        assert torch.equal(rh[k][one_writer], rd[k][one_writer]), k
+        assert torch.allclose(rh[k], rd[k], rtol=1e-3, atol=1e-3), k
+
+
 def test_device_planner_rejects_what_the_host_planner_rejects():
     A = wl.random_pattern(64, 64, 0.2, seed=3)
     rp = torch.from_numpy(A.rowptr.astype(np.int32)).cuda()
@@ -175,3 +229,19 @@ def test_device_planner_full_configs(name):
     print(f"{name}: host planner {t_host:.3f} s, device planner {t_dev:.3f} s "
           f"(device passes {pd.stats()['device_seconds']:.4f} s)", flush=True)
     assert_same_plan(ph, pd)
+    # plan + device copy: host planner + upload against the resident device plan without a host copy
+    t0 = time.perf_counter()
+    ph.upload()
+    torch.cuda.synchronize()
+    t_up = time.perf_counter() - t0
+    lb.Plan.from_device_csr(A.M, A.Kc, rp, col, val, resident=True, keep_host_copy=False).close()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    pr = lb.Plan.from_device_csr(A.M, A.Kc, rp, col, val, resident=True, keep_host_copy=False)
+    torch.cuda.synchronize()
+    t_res = time.perf_counter() - t0
+    print(f"{name}: ready to compute: host plan + upload {t_host + t_up:.3f} s, resident device plan {t_res:.4f} s", flush=True)
+    B = torch.from_numpy(wl.dense_normal(A.Kc, 32, seed=5)).cuda()
+    one_writer = torch.ones(A.M, dtype=torch.bool, device="cuda")
+    one_writer[torch.from_numpy(ph.export(0)["zero_rows"]).cuda().long()] = False
+    assert torch.equal(ph.spmm(B)[one_writer], pr.spmm(B)[one_writer])
