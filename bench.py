@@ -60,6 +60,9 @@ def main() -> int:
     ap.add_argument("--natural-order", action="store_true")
     ap.add_argument("--xcd-order", action="store_true", help="group tasks of neighbouring windows on one accelerator die")
     ap.add_argument("--no-xcd-order", action="store_true", help="never do that (default: the planner decides from the matrix)")
+    ap.add_argument("--host-plan", action="store_true",
+                    help="run the compute calls on the host-built, uploaded plan (default: on the plan the device planner "
+                         "wrote; the two plans are identical and both planners are timed either way)")
     ap.add_argument("--dtype", default="f16", choices=["f16", "bf16"], help="storage type of A's values and the dense operands")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run only a 1 GiB device copy (5 times): the known-size kernel that scales the rocprofv3 "
@@ -99,14 +102,34 @@ def main() -> int:
 
     bf16 = args.dtype == "bf16"
     val = wl.to_bf16_bits(A.val.astype(np.float32)) if bf16 else None
+    opts = dict(mode=args.mode, spmm_min_vec_nnz=args.tau_spmm, sddmm_min_blk_nnz=args.tau_sddmm, ts=args.ts, cs=args.cs,
+                flags=(lb.FLAG_NATURAL_ORDER if args.natural_order else 0) | (lb.FLAG_XCD_ORDER if args.xcd_order else 0)
+                | (lb.FLAG_NO_XCD_ORDER if args.no_xcd_order else 0))
+    # the plan is built once per matrix, outside the timed region, by both planners: on the host (+ upload) and on the
+    # device (the plan's device copy written directly, no host copy kept)
     t0 = time.perf_counter()
-    plan = lb.Plan.from_csr(A, val=val, val_dtype=lb.BF16 if bf16 else None, mode=args.mode, spmm_min_vec_nnz=args.tau_spmm, sddmm_min_blk_nnz=args.tau_sddmm,
-                            ts=args.ts, cs=args.cs, flags=(lb.FLAG_NATURAL_ORDER if args.natural_order else 0) | (lb.FLAG_XCD_ORDER if args.xcd_order else 0)
-                            | (lb.FLAG_NO_XCD_ORDER if args.no_xcd_order else 0))
+    host_plan = lb.Plan.from_csr(A, val=val, val_dtype=lb.BF16 if bf16 else None, **opts)
     plan_s = time.perf_counter() - t0
     t0 = time.perf_counter()
-    plan.upload()
+    host_plan.upload()
+    torch.cuda.synchronize()
     upload_s = time.perf_counter() - t0
+    rp_d, col_d = torch.from_numpy(A.rowptr.astype(np.int32)).cuda(), torch.from_numpy(A.col.astype(np.int32)).cuda()
+    val_d = (torch.from_numpy(val.view(np.int16)).cuda().view(torch.bfloat16) if bf16 else torch.from_numpy(A.val).cuda())
+    dev_s = []
+    dev_plan = None
+    for _ in range(3):                      # the first call pays for module loading and the allocator
+        if dev_plan is not None:
+            dev_plan.close()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        dev_plan = lb.Plan.from_device_csr(A.M, A.Kc, rp_d, col_d, val_d, resident=True, keep_host_copy=False, **opts)
+        torch.cuda.synchronize()
+        dev_s.append(time.perf_counter() - t0)
+    hs, ds = host_plan.stats(), dev_plan.stats()
+    assert all(hs[k] == ds[k] for k in hs if k not in ("plan_seconds", "device_seconds")), "the two planners disagree"
+    plan = host_plan if args.host_plan else dev_plan
+    (dev_plan if args.host_plan else host_plan).close()
     st = plan.stats()
 
     if bf16:
@@ -209,7 +232,9 @@ def main() -> int:
                   "median_us": round(float(np.median(sddmm_ms)) * 1e3, 2), "min_us": round(float(sddmm_ms.min()) * 1e3, 2),
                   "cold_median_us": round(float(np.median(sddmm_cold)) * 1e3, 2), "bytes": bytes_sddmm,
                   "hbm_frac": round(bytes_sddmm / (float(sddmm_ms.mean()) * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)},
-        "plan": {"plan_s": round(plan_s, 4), "upload_s": round(upload_s, 4),
+        "plan": {"used": "host planner + upload" if args.host_plan else "device planner (resident)",
+                 "host_plan_s": round(plan_s, 4), "host_upload_s": round(upload_s, 4),
+                 "device_plan_s": round(min(dev_s[1:]), 5), "device_passes_s": round(ds["device_seconds"], 5),
                  "spmm_dense_share": round(st["spmm_dense_nnz"] / max(A.nnz, 1), 4),
                  "sddmm_dense_share": round(st["sddmm_dense_nnz"] / max(A.nnz, 1), 4),
                  "nnz1_vector_ratio": round(st["n_vectors_nnz1"] / max(st["n_vectors"], 1), 4),
