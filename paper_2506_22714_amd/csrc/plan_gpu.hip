@@ -882,9 +882,11 @@ extern "C" int libra_plan_device(int64_t M, int64_t Kc, int64_t nnz, const int32
         mark("plan buffer written");
         P->stats.plan_seconds = std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count();
     } catch (const Fail &f) {
+        (void)hipStreamSynchronize(s);       // queued passes may still use the workspace the caller is about to free
         delete P;
         return f.code;
     } catch (...) {
+        (void)hipStreamSynchronize(s);
         delete P;
         return LIBRA_ERR_NOMEM;
     }

@@ -447,8 +447,10 @@ def test_full_powerlaw_config_as_benchmarked():
     A = _full("powerlaw")
     N, K = 128, 32
     B = wl.dense_normal(A.Kc, N, seed=wl.BASE_SEED + 201)
-    p = lb.Plan.from_csr(A).upload()
-    _plan_invariants(p, A)
+    _plan_invariants(lb.Plan.from_csr(A), A)
+    # the benchmark runs on the plan the device planner writes straight into device memory
+    p = lb.Plan.from_device_csr(A.M, A.Kc, dev(A.rowptr.astype(np.int32)), dev(A.col.astype(np.int32)), dev(A.val),
+                                resident=True, keep_host_copy=False)
     C = p.spmm(dev(B))
     torch.cuda.synchronize()
     Ch = C.cpu().numpy()
