@@ -233,6 +233,13 @@ int libra_sddmm(const libra_plan_t *plan, const void *X, const void *Y, int32_t 
                 float *out, void *stream);
 
 /*
+ * libra_sddmm_pattern - as libra_sddmm without A's values: out[p] = <X[i,:], Y[col[p],:]>.  The gradient of SpMM with
+ * respect to A's values is this product of dC and B (the training use of the operators, Section 5.5).
+ */
+int libra_sddmm_pattern(const libra_plan_t *plan, const void *X, const void *Y, int32_t K,
+                        float *out, void *stream);
+
+/*
  * libra_edge_softmax - row-wise softmax over CSR-ordered scores (the step between SDDMM and SpMM in an
  * attention layer, Section 5.5): vals_out[p] = exp(scale*s[p] - mx_i) / sum_row exp(scale*s[q] - mx_i).
  *   scores    device, fp32[nnz], CSR order
@@ -242,6 +249,31 @@ int libra_sddmm(const libra_plan_t *plan, const void *X, const void *Y, int32_t 
  */
 int libra_edge_softmax(const libra_plan_t *plan, const float *scores, float scale,
                        void *vals_out, int out_dtype, void *stream);
+
+/*
+ * libra_edge_softmax_backward - gradient of libra_edge_softmax with respect to the scores:
+ * dscores[p] = scale * alpha[p] * (dalpha[p] - sum over the row of alpha[q] * dalpha[q]).
+ *   alpha     device, nnz values of alpha_dtype (what the forward call wrote), CSR order
+ *   dalpha    device, fp32[nnz]; dscores  device, fp32[nnz], may not alias the inputs
+ * Errors: NULL, DTYPE, NOT_UPLOADED, HIP.
+ */
+int libra_edge_softmax_backward(const libra_plan_t *plan, const void *alpha, int alpha_dtype, const float *dalpha,
+                                float scale, float *dscores, void *stream);
+
+/*
+ * libra_csr_transpose_device - CSR pattern of the transposed matrix, on the device (the backward pass of SpMM,
+ * dB = A^T dC, runs on a plan of A^T; Section 5.5 trains GNNs with these operators).
+ *   d_rowptr, d_col      device, the M x Kc matrix (as in libra_plan_device; not validated here)
+ *   d_rowptr_t           device, int32[Kc+1] out
+ *   d_col_t, d_perm_t    device, int32[nnz] out: row index and CSR position in A of every nonzero of A^T, so that
+ *                        values of A^T are values_of_A[d_perm_t[q]]
+ *   workspace            device, 256-byte aligned, libra_csr_transpose_workspace(nnz) bytes, free after the call
+ * The call synchronises the stream.  Errors: NULL, SHAPE, TOO_LARGE, BUFFER, HIP.
+ */
+int libra_csr_transpose_workspace(int64_t nnz, size_t *bytes);
+int libra_csr_transpose_device(int64_t M, int64_t Kc, int64_t nnz, const int32_t *d_rowptr, const int32_t *d_col,
+                               int32_t *d_rowptr_t, int32_t *d_col_t, int32_t *d_perm_t,
+                               void *workspace, size_t workspace_bytes, void *stream);
 
 /*
  * libra_plan_set_values - replace A's values (same pattern): scatters CSR-ordered device values into the

@@ -101,7 +101,11 @@ def lib() -> C.CDLL:
         L.libra_plan_upload.argtypes = [vp, vp, sz, vp]
         L.libra_spmm.argtypes = [vp, vp, i32, i64, vp, i64, vp]
         L.libra_sddmm.argtypes = [vp, vp, vp, i32, vp, vp]
+        L.libra_sddmm_pattern.argtypes = [vp, vp, vp, i32, vp, vp]
         L.libra_edge_softmax.argtypes = [vp, vp, C.c_float, vp, C.c_int, vp]
+        L.libra_edge_softmax_backward.argtypes = [vp, vp, C.c_int, vp, C.c_float, vp, vp]
+        L.libra_csr_transpose_workspace.argtypes = [i64, C.POINTER(sz)]
+        L.libra_csr_transpose_device.argtypes = [i64, i64, i64, vp, vp, vp, vp, vp, vp, sz, vp]
         L.libra_plan_set_values.argtypes = [vp, vp, C.c_int, vp]
         L.libra_plan_export.argtypes = [vp, C.c_int, C.POINTER(SubplanView)]
         L.libra_plan_stats.argtypes = [vp, C.POINTER(Stats)]
@@ -199,6 +203,46 @@ def libra_spmm(plan, B_ptr: int, N: int, ldb: int, C_ptr: int, ldc: int, stream:
 def libra_sddmm(plan, X_ptr: int, Y_ptr: int, K: int, out_ptr: int, stream: int = 0):
     _check(lib().libra_sddmm(plan, C.c_void_p(X_ptr), C.c_void_p(Y_ptr), K, C.c_void_p(out_ptr), C.c_void_p(stream)),
            "libra_sddmm")
+
+
+def libra_sddmm_pattern(plan, X_ptr: int, Y_ptr: int, K: int, out_ptr: int, stream: int = 0):
+    _check(lib().libra_sddmm_pattern(plan, C.c_void_p(X_ptr), C.c_void_p(Y_ptr), K, C.c_void_p(out_ptr), C.c_void_p(stream)),
+           "libra_sddmm_pattern")
+
+
+def libra_edge_softmax_backward(plan, alpha_ptr: int, alpha_dtype: int, dalpha_ptr: int, scale: float, dscores_ptr: int,
+                                stream: int = 0):
+    _check(lib().libra_edge_softmax_backward(plan, C.c_void_p(alpha_ptr), alpha_dtype, C.c_void_p(dalpha_ptr), C.c_float(scale),
+                                             C.c_void_p(dscores_ptr), C.c_void_p(stream)), "libra_edge_softmax_backward")
+
+
+def libra_csr_transpose_workspace(nnz: int) -> int:
+    n = C.c_size_t()
+    _check(lib().libra_csr_transpose_workspace(nnz, C.byref(n)), "libra_csr_transpose_workspace")
+    return int(n.value)
+
+
+def libra_csr_transpose_device(M: int, Kc: int, nnz: int, rowptr_ptr: int, col_ptr: int, rowptr_t_ptr: int, col_t_ptr: int,
+                               perm_t_ptr: int, ws_ptr: int, ws_bytes: int, stream: int = 0):
+    _check(lib().libra_csr_transpose_device(M, Kc, nnz, C.c_void_p(rowptr_ptr), C.c_void_p(col_ptr), C.c_void_p(rowptr_t_ptr),
+                                            C.c_void_p(col_t_ptr), C.c_void_p(perm_t_ptr), C.c_void_p(ws_ptr), ws_bytes,
+                                            C.c_void_p(stream)), "libra_csr_transpose_device")
+
+
+def transpose_csr(M: int, Kc: int, rowptr, col):
+    """(rowptr_t, col_t, perm_t) of the transposed pattern, torch int32 tensors on the device of the inputs."""
+    import torch
+    nnz = int(col.numel())
+    assert rowptr.is_cuda and rowptr.dtype == torch.int32 and rowptr.numel() == M + 1 and col.dtype == torch.int32
+    rowptr_t = torch.empty(Kc + 1, dtype=torch.int32, device=rowptr.device)
+    col_t = torch.empty(nnz, dtype=torch.int32, device=rowptr.device)
+    perm_t = torch.empty(nnz, dtype=torch.int32, device=rowptr.device)
+    nb = libra_csr_transpose_workspace(nnz)
+    ws = torch.empty(nb, dtype=torch.uint8, device=rowptr.device)
+    libra_csr_transpose_device(M, Kc, nnz, rowptr.data_ptr(), col.data_ptr() if nnz else 0, rowptr_t.data_ptr(),
+                               col_t.data_ptr() if nnz else 0, perm_t.data_ptr() if nnz else 0, ws.data_ptr(), nb,
+                               torch.cuda.current_stream().cuda_stream)
+    return rowptr_t, col_t, perm_t
 
 
 def libra_edge_softmax(plan, scores_ptr: int, scale: float, out_ptr: int, out_dtype: int, stream: int = 0):
@@ -335,15 +379,15 @@ class Plan:
                    torch.cuda.current_stream().cuda_stream)
         return out
 
-    def sddmm(self, X, Y, out=None):
+    def sddmm(self, X, Y, out=None, pattern_only: bool = False):
         import torch
         assert X.is_cuda and Y.is_cuda and X.dtype == Y.dtype == self._torch_dtype()
         assert X.is_contiguous() and Y.is_contiguous() and X.shape[1] == Y.shape[1]
         if out is None:
             out = torch.empty(self.nnz, dtype=torch.float32, device=X.device)
         assert out.is_cuda and out.dtype == torch.float32 and out.numel() == self.nnz and out.is_contiguous()
-        libra_sddmm(self.handle, X.data_ptr(), Y.data_ptr(), X.shape[1], out.data_ptr(),
-                    torch.cuda.current_stream().cuda_stream)
+        (libra_sddmm_pattern if pattern_only else libra_sddmm)(self.handle, X.data_ptr(), Y.data_ptr(), X.shape[1], out.data_ptr(),
+                                                               torch.cuda.current_stream().cuda_stream)
         return out
 
     def edge_softmax(self, scores, scale: float, out=None):
@@ -354,6 +398,17 @@ class Plan:
         code = {torch.float16: F16, torch.bfloat16: BF16, torch.float32: F32}[out.dtype]
         libra_edge_softmax(self.handle, scores.data_ptr(), scale, out.data_ptr(), code,
                            torch.cuda.current_stream().cuda_stream)
+        return out
+
+    def edge_softmax_backward(self, alpha, dalpha, scale: float, out=None):
+        import torch
+        assert alpha.is_cuda and alpha.is_contiguous() and alpha.numel() == self.nnz
+        assert dalpha.is_cuda and dalpha.dtype == torch.float32 and dalpha.is_contiguous() and dalpha.numel() == self.nnz
+        if out is None:
+            out = torch.empty(self.nnz, dtype=torch.float32, device=alpha.device)
+        code = {torch.float16: F16, torch.bfloat16: BF16, torch.float32: F32}[alpha.dtype]
+        libra_edge_softmax_backward(self.handle, alpha.data_ptr(), code, dalpha.data_ptr(), scale, out.data_ptr(),
+                                    torch.cuda.current_stream().cuda_stream)
         return out
 
     def set_values(self, vals):

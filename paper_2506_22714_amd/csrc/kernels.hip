@@ -572,6 +572,7 @@ struct SddmmArgs {
     const void *Y;
     float *out;
     int64_t M;
+    int32_t pattern_only;       // nonzero: out_p = <X_i, Y_j>, A's values are not applied
 };
 
 // Sum over the LPN consecutive lanes of a group; every lane of the group gets the total.
@@ -652,7 +653,7 @@ __device__ inline void sddmm_window_task(const SddmmArgs &a, const DevTask &t) {
 #pragma unroll
             for (int e = 0; e < 4; ++e)
                 if (b0 + x < t.blk_end && (word[x] >> (e * 16 + j) & 1ull))
-                    a.out[(int32_t)pv[x][e].x] = Elem<T>::word_val(pv[x][e].y) * d[x][e];
+                    a.out[(int32_t)pv[x][e].x] = (a.pattern_only ? 1.f : Elem<T>::word_val(pv[x][e].y)) * d[x][e];
     }
 }
 
@@ -682,7 +683,7 @@ __device__ inline void sddmm_segment_task(const SddmmArgs &a, const DevTask &t) 
         for (int u = 0; u < U; ++u) s[u] = group_sum<LPN>(E::dot(x[u], y[u], 0.f));
 #pragma unroll
         for (int u = 0; u < U; ++u)
-            if (sub == 0 && q0 + u * NPW + grp < t.res_end) a.out[(int32_t)ent[u].z] = E::word_val(ent[u].w) * s[u];
+            if (sub == 0 && q0 + u * NPW + grp < t.res_end) a.out[(int32_t)ent[u].z] = (a.pattern_only ? 1.f : E::word_val(ent[u].w)) * s[u];
     }
 }
 
@@ -788,6 +789,56 @@ __global__ __launch_bounds__(256) void edge_softmax_long_kernel(const int32_t *r
     __syncthreads();
     const float inv = 1.f / (red[0] + red[1] + red[2] + red[3]);
     for (int q = tid; q < n; q += 256) out[s + q] = to_storage<TO>(__expf(scale * score[s + q] - mx) * inv);
+}
+
+// Backward of the edge softmax: dscore_p = scale * alpha_p * (dalpha_p - sum_row alpha_q dalpha_q).  Same three row
+// classes as the forward kernels.
+template <class TA> __device__ inline float from_storage(TA x) { return (float)x; }
+template <> __device__ inline float from_storage<bf16_t>(bf16_t x) { return __uint_as_float((uint32_t)x.bits << 16); }
+
+template <class TA>
+__global__ __launch_bounds__(256) void edge_softmax_bwd_rows_kernel(const int32_t *rowptr, int64_t M, const TA *alpha, const float *dalpha, float scale, float *dscore) {
+    const int l = threadIdx.x & 15;
+    const int64_t group = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 4;
+    const int64_t ngroups = ((int64_t)gridDim.x * blockDim.x) >> 4;
+    for (int64_t i = group; i < M; i += ngroups) {
+        const int s = rowptr[i], n = rowptr[i + 1] - s;
+        if (n == 0 || n > 64) continue;
+        float a[4], g[4], dot = 0.f;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int q = l + 16 * k;
+            a[k] = q < n ? from_storage<TA>(alpha[s + q]) : 0.f;
+            g[k] = q < n ? dalpha[s + q] : 0.f;
+            dot += a[k] * g[k];
+        }
+        dot = group_sum<16>(dot);
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+            if (l + 16 * k < n) dscore[s + l + 16 * k] = scale * a[k] * (g[k] - dot);
+    }
+}
+
+// one wave per listed row (65 .. LIBRA_SOFTMAX_LONG_ROW nonzeros), or one 256-thread workgroup per listed long row
+template <class TA, int THREADS>
+__global__ __launch_bounds__(256) void edge_softmax_bwd_list_kernel(const int32_t *rowptr, const int32_t *rows, int nrows, const TA *alpha, const float *dalpha, float scale, float *dscore) {
+    __shared__ float red[4];
+    const int lane = threadIdx.x & 63;
+    const int tid = THREADS == WAVE ? lane : (int)threadIdx.x;
+    const int w = THREADS == WAVE ? (int)((blockIdx.x * blockDim.x + threadIdx.x) >> 6) : (int)blockIdx.x;
+    if (w >= nrows) return;             // whole waves (THREADS == WAVE) or whole workgroups leave together
+    const int64_t i = rows[w];
+    const int s = rowptr[i], n = rowptr[i + 1] - s;
+    float dot = 0.f;
+    for (int q = tid; q < n; q += THREADS) dot += from_storage<TA>(alpha[s + q]) * dalpha[s + q];
+#pragma unroll
+    for (int m = 1; m < WAVE; m <<= 1) dot += __shfl_xor(dot, m, WAVE);
+    if (THREADS > WAVE) {
+        if (lane == 0) red[threadIdx.x >> 6] = dot;
+        __syncthreads();
+        dot = red[0] + red[1] + red[2] + red[3];
+    }
+    for (int q = tid; q < n; q += THREADS) dscore[s + q] = scale * from_storage<TA>(alpha[s + q]) * (dalpha[s + q] - dot);
 }
 
 // dst[i * stride + offset] (as T) = src[perm[i]]: new values into a packed array or into entry records
@@ -1088,7 +1139,17 @@ extern "C" int libra_spmm(const libra_plan_t *P, const void *B, int32_t N, int64
     return LIBRA_OK;
 }
 
+namespace {
+int sddmm_call(const libra_plan_t *P, const void *X, const void *Y, int32_t K, float *out, void *stream, int pattern_only);
+}
 extern "C" int libra_sddmm(const libra_plan_t *P, const void *X, const void *Y, int32_t K, float *out, void *stream) {
+    return sddmm_call(P, X, Y, K, out, stream, 0);
+}
+extern "C" int libra_sddmm_pattern(const libra_plan_t *P, const void *X, const void *Y, int32_t K, float *out, void *stream) {
+    return sddmm_call(P, X, Y, K, out, stream, 1);
+}
+namespace {
+int sddmm_call(const libra_plan_t *P, const void *X, const void *Y, int32_t K, float *out, void *stream, int pattern_only) {
     if (!P || !X || !Y) return LIBRA_ERR_NULL;
     if (!out && P->nnz > 0) return LIBRA_ERR_NULL;           // a matrix without nonzeros has no output
     if (!P->o.build_sddmm) return LIBRA_ERR_NOT_BUILT;
@@ -1101,7 +1162,7 @@ extern "C" int libra_sddmm(const libra_plan_t *P, const void *X, const void *Y, 
     const SubPlan &sp = P->sddmm;
     SddmmArgs a{sp.dev.tasks, sp.dev.blk_cols, sp.dev.blk_bitmap, sp.dev.blk_valptr,
                 reinterpret_cast<const uint2 *>(sp.dev.dense_pv), (int32_t)sp.n.dense,
-                reinterpret_cast<const SdEnt *>(sp.dev.res_ent), X, Y, out, P->M};
+                reinterpret_cast<const SdEnt *>(sp.dev.res_ent), X, Y, out, P->M, pattern_only};
     const int64_t nt = (int64_t)sp.tasks.size();
     if (nt == 0) return LIBRA_OK;
     if (sp.n_window_tasks > 0 && P->vdt == LIBRA_F32) return LIBRA_ERR_UNSUPPORTED;
@@ -1128,6 +1189,7 @@ extern "C" int libra_sddmm(const libra_plan_t *P, const void *X, const void *Y, 
     if (hipGetLastError() != hipSuccess) return LIBRA_ERR_HIP;
     return LIBRA_OK;
 }
+}  // namespace
 
 extern "C" int libra_edge_softmax(const libra_plan_t *P, const float *scores, float scale, void *vals_out, int out_dtype, void *stream) {
     if (!P) return LIBRA_ERR_NULL;
@@ -1147,6 +1209,29 @@ extern "C" int libra_edge_softmax(const libra_plan_t *P, const float *scores, fl
     };
     if (out_dtype == LIBRA_F16) run(half_t{});
     else if (out_dtype == LIBRA_BF16) run(bf16_t{});
+    else run(float{});
+    return hip_rc(hipGetLastError());
+}
+
+extern "C" int libra_edge_softmax_backward(const libra_plan_t *P, const void *alpha, int alpha_dtype, const float *dalpha, float scale,
+                                           float *dscores, void *stream) {
+    if (!P) return LIBRA_ERR_NULL;
+    if ((!alpha || !dalpha || !dscores) && P->nnz > 0) return LIBRA_ERR_NULL;
+    if (alpha_dtype != LIBRA_F16 && alpha_dtype != LIBRA_BF16 && alpha_dtype != LIBRA_F32) return LIBRA_ERR_DTYPE;
+    if (!P->dev_base) return LIBRA_ERR_NOT_UPLOADED;
+    hipStream_t s = (hipStream_t)stream;
+    if (P->nnz == 0) return LIBRA_OK;
+    const unsigned blocks = (unsigned)std::min<int64_t>((P->M + 15) / 16, 1 << 18);
+    const unsigned nlong = (unsigned)P->long_rows.size(), nmed = (unsigned)P->medium_rows.size();
+    auto run = [&](auto tag) {
+        typedef decltype(tag) TA;
+        const TA *a = reinterpret_cast<const TA *>(alpha);
+        hipLaunchKernelGGL((edge_softmax_bwd_rows_kernel<TA>), dim3(blocks), dim3(256), 0, s, P->d_rowptr, P->M, a, dalpha, scale, dscores);
+        if (nmed) hipLaunchKernelGGL((edge_softmax_bwd_list_kernel<TA, WAVE>), dim3((nmed + 3) / 4), dim3(256), 0, s, P->d_rowptr, P->d_medium_rows, (int)nmed, a, dalpha, scale, dscores);
+        if (nlong) hipLaunchKernelGGL((edge_softmax_bwd_list_kernel<TA, 256>), dim3(nlong), dim3(256), 0, s, P->d_rowptr, P->d_long_rows, (int)nlong, a, dalpha, scale, dscores);
+    };
+    if (alpha_dtype == LIBRA_F16) run(half_t{});
+    else if (alpha_dtype == LIBRA_BF16) run(bf16_t{});
     else run(float{});
     return hip_rc(hipGetLastError());
 }

@@ -893,3 +893,89 @@ extern "C" int libra_plan_device(int64_t M, int64_t Kc, int64_t nnz, const int32
     *out = P;
     return LIBRA_OK;
 }
+
+// ------------------------------------------------------------------------------------------
+// Transposition of a CSR pattern on the device (the backward pass of SpMM multiplies by the transposed matrix).
+// ------------------------------------------------------------------------------------------
+namespace {
+// one wave per 16 rows: key = (column, CSR position); a sort by key lists the nonzeros column by column, rows ascending
+__global__ __launch_bounds__(64) void k_transpose_keys(const int32_t *rowptr, const int32_t *col, int64_t M, u64 *key, int32_t *row_of) {
+    const int64_t w = blockIdx.x;
+    const int lane = threadIdx.x;
+    for (int r = 0; r < W; ++r) {
+        const int64_t i = w * W + r;
+        if (i >= M) break;
+        const int s = rowptr[i], e = rowptr[i + 1];
+        for (int p = s + lane; p < e; p += 64) {
+            key[p] = ((u64)(uint32_t)col[p] << 32) | (u64)(uint32_t)p;
+            row_of[p] = (int32_t)i;
+        }
+    }
+}
+__global__ __launch_bounds__(256) void k_transpose_fill(const u64 *skey, const int32_t *row_of, int n, int32_t *col_t, int32_t *perm_t) {
+    const int q = blockIdx.x * blockDim.x + threadIdx.x;
+    if (q >= n) return;
+    const int p = (int)(skey[q] & 0xffffffffull);
+    perm_t[q] = p;
+    col_t[q] = row_of[p];
+}
+// rowptr_t[c] = first sorted position whose column is >= c
+__global__ __launch_bounds__(256) void k_transpose_rowptr(const u64 *skey, int n, int64_t Kc, int32_t *rowptr_t) {
+    const int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (c > Kc) return;
+    int lo = 0, hi = n;
+    while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        if ((int64_t)(skey[mid] >> 32) < c) lo = mid + 1; else hi = mid;
+    }
+    rowptr_t[c] = lo;
+}
+
+struct TLayout { u64 *key_in, *key_out; int32_t *row_of; void *tmp; size_t tmp_bytes, total; };
+TLayout transpose_layout(int64_t nnz, void *base) {
+    TLayout L{};
+    Arena A{(char *)base};
+    const size_t n = (size_t)std::max<int64_t>(nnz, 1);
+    L.key_in = A.take<u64>(n);
+    L.key_out = A.take<u64>(n);
+    L.row_of = A.take<int32_t>(n);
+    size_t sz = 0;
+    (void)rocprim::radix_sort_keys(nullptr, sz, (u64 *)nullptr, (u64 *)nullptr, n, 0, 64);
+    L.tmp_bytes = sz + 4096;
+    L.tmp = A.take<uint8_t>(L.tmp_bytes);
+    L.total = align256(A.off) + 256;
+    return L;
+}
+}  // namespace
+
+extern "C" int libra_csr_transpose_workspace(int64_t nnz, size_t *bytes) {
+    if (!bytes) return LIBRA_ERR_NULL;
+    if (nnz < 0) return LIBRA_ERR_SHAPE;
+    if (nnz >= (1ll << 31) - 64) return LIBRA_ERR_TOO_LARGE;
+    *bytes = transpose_layout(nnz, nullptr).total;
+    return LIBRA_OK;
+}
+
+extern "C" int libra_csr_transpose_device(int64_t M, int64_t Kc, int64_t nnz, const int32_t *d_rowptr, const int32_t *d_col,
+                                          int32_t *d_rowptr_t, int32_t *d_col_t, int32_t *d_perm_t,
+                                          void *workspace, size_t workspace_bytes, void *stream) {
+    if (!d_rowptr || !d_rowptr_t) return LIBRA_ERR_NULL;
+    if (M < 1 || Kc < 1 || nnz < 0) return LIBRA_ERR_SHAPE;
+    if (M >= (1ll << 31) - 64 || Kc >= (1ll << 31) - 64 || nnz >= (1ll << 31) - 64) return LIBRA_ERR_TOO_LARGE;
+    hipStream_t s = (hipStream_t)stream;
+    if (nnz == 0) return hipMemsetAsync(d_rowptr_t, 0, (size_t)(Kc + 1) * sizeof(int32_t), s) == hipSuccess ? LIBRA_OK : LIBRA_ERR_HIP;
+    if (!d_col || !d_col_t || !d_perm_t || !workspace) return LIBRA_ERR_NULL;
+    const TLayout L = transpose_layout(nnz, workspace);
+    if (((uintptr_t)workspace & 255) || workspace_bytes < L.total) return LIBRA_ERR_BUFFER;
+    const int n = (int)nnz;
+    int colbits = 1;
+    while ((1ll << colbits) < Kc) ++colbits;
+    const int64_t nw = (M + W - 1) / W;
+    hipLaunchKernelGGL(k_transpose_keys, dim3((unsigned)nw), dim3(64), 0, s, d_rowptr, d_col, M, L.key_in, L.row_of);
+    size_t sz = L.tmp_bytes;
+    if (rocprim::radix_sort_keys(L.tmp, sz, L.key_in, L.key_out, (size_t)n, 0, (unsigned)(32 + colbits), s) != hipSuccess) return LIBRA_ERR_HIP;
+    hipLaunchKernelGGL(k_transpose_fill, dim3(blocks_for(n, 256)), dim3(256), 0, s, L.key_out, L.row_of, n, d_col_t, d_perm_t);
+    hipLaunchKernelGGL(k_transpose_rowptr, dim3(blocks_for(Kc + 1, 256)), dim3(256), 0, s, L.key_out, n, Kc, d_rowptr_t);
+    if (hipGetLastError() != hipSuccess || hipStreamSynchronize(s) != hipSuccess) return LIBRA_ERR_HIP;     // the workspace may go now
+    return LIBRA_OK;
+}
