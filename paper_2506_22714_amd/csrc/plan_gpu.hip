@@ -80,7 +80,7 @@ struct SubOut {      // one sub-plan in the host planner's format
 };
 
 struct Layout {
-    int32_t *win_ptr, *spos, *hflag, *vid, *einfo, *ewin;
+    int32_t *win_ptr, *spos, *hflag, *vid, *einfo, *ewin, *row_of, *rowbase;
     u64 *key_in, *key_out, *key2_in, *key2_out, *ctr;
     int32_t *vfirst, *vinfo, *vcol, *vwin, *sv, *srank, *scnt, *cum, *tflag, *taud, *win_vptr;
     int32_t *ntau, *nzero, *zbase, *nres, *resptr, *zero_rows;
@@ -116,6 +116,8 @@ Layout make_layout(const Sizes &z, int vsize, void *base) {
     L.vid = A.take<int32_t>(n + 1);
     L.einfo = A.take<int32_t>(n);
     L.ewin = A.take<int32_t>(n);
+    L.row_of = A.take<int32_t>(n);
+    L.rowbase = A.take<int32_t>((size_t)z.M + 1);
     L.vfirst = A.take<int32_t>(n);
     L.vinfo = A.take<int32_t>(n);
     L.vcol = A.take<int32_t>(n);
@@ -173,22 +175,23 @@ __global__ __launch_bounds__(256) void k_win_ptr(const int32_t *rowptr, int64_t 
     if (t <= nw) win_ptr[t] = rowptr[min((int64_t)M, t * W)];
 }
 
-// One wave per window: sort key (column, row in window) of every nonzero, and the checks the host planner makes.
-__global__ __launch_bounds__(64) void k_keys(const int32_t *rowptr, const int32_t *col, int64_t M, int64_t Kc, u64 *key_in, u64 *ctr) {
-    const int64_t w = blockIdx.x;
-    const int lane = threadIdx.x;
-    unsigned bad = 0;
-    for (int r = 0; r < W; ++r) {
-        const int64_t i = w * W + r;
-        if (i >= M) break;
-        const int s = rowptr[i], e = rowptr[i + 1];
-        for (int p = s + lane; p < e; p += 64) {
-            const int c = col[p];
-            if (c < 0 || c >= Kc) bad |= 1u;
-            else if (p > s && col[p - 1] >= c) bad |= 2u;
-            key_in[p] = ((u64)(uint32_t)c << 4) | (u64)r;
-        }
+// Per nonzero (CSR order): its row (bisection over rowptr; rows without nonzeros are skipped over), the sort key
+// (column, row in window), and the checks the host planner makes.
+__global__ __launch_bounds__(256) void k_keys(const int32_t *rowptr, const int32_t *col, int64_t M, int64_t Kc, int n,
+                                              u64 *key_in, int32_t *row_of, u64 *ctr) {
+    const int p = blockIdx.x * blockDim.x + threadIdx.x;
+    if (p >= n) return;
+    int64_t lo = 0, hi = M;                 // rowptr[lo] <= p < rowptr[hi]
+    while (hi - lo > 1) {
+        const int64_t mid = (lo + hi) >> 1;
+        if (rowptr[mid] <= p) lo = mid; else hi = mid;
     }
+    const int c = col[p];
+    unsigned bad = 0;
+    if (c < 0 || c >= Kc) bad = 1u;
+    else if (p > rowptr[lo] && col[p - 1] >= c) bad = 2u;
+    key_in[p] = ((u64)(uint32_t)c << 4) | (u64)(lo & (W - 1));
+    row_of[p] = (int32_t)lo;
     if (bad) atomicOr(&ctr[C_ERR], (u64)bad);
 }
 
@@ -284,7 +287,8 @@ __global__ __launch_bounds__(256) void k_share(const int32_t *win_vptr, const in
     const int w0 = (int)(g * LIBRA_LOCALITY_WINDOWS), w1 = (int)min((int64_t)nw, (g + 1) * LIBRA_LOCALITY_WINDOWS);
     const int v0 = win_vptr[w0], v1 = win_vptr[w1];
     int mine = 0;
-    for (int v = v0 + (int)threadIdx.x; v < v1; v += (int)blockDim.x) {
+    // the group's vectors are dealt to the gridDim.y workgroups of the group
+    for (int v = v0 + (int)(blockIdx.y * blockDim.x + threadIdx.x); v < v1; v += (int)(blockDim.x * gridDim.y)) {
         const int c = vcol[v];
         bool seen = false;
         for (int w = w0; w < w1 && !seen; ++w) {
@@ -302,8 +306,8 @@ __global__ __launch_bounds__(256) void k_share(const int32_t *win_vptr, const in
     if (mine) atomicAdd(&together, mine);
     __syncthreads();
     if (threadIdx.x == 0) {
-        atomicAdd(&ctr[C_TOGETHER], (u64)together);
-        atomicAdd(&ctr[C_APART], (u64)(v1 - v0));
+        if (together) atomicAdd(&ctr[C_TOGETHER], (u64)together);
+        if (blockIdx.y == 0) atomicAdd(&ctr[C_APART], (u64)(v1 - v0));
     }
 }
 
@@ -560,47 +564,45 @@ __global__ __launch_bounds__(128) void k_window_tasks(const int32_t *rowptr, con
     }
 }
 
-// One wave per window: residual nonzeros to their places.  SpMM: window by window, rows that are not decomposed
-// first (row order), then the decomposed rows.  SDDMM: CSR order.
-__global__ __launch_bounds__(64) void k_residual_fill(const int32_t *rowptr, const int32_t *col, const uint8_t *val, int vsize, int64_t M, Rule R,
-                                                      const int32_t *resf_a, const int32_t *rescan_a, const int32_t *resptr,
+// Per window: where each row's residual nonzeros start in the SpMM residual array (rows that are not decomposed
+// first, in row order, then the decomposed rows), minus the row's own prefix so that a nonzero only adds its scan value.
+__global__ __launch_bounds__(128) void k_row_bases(const int32_t *rowptr, const int32_t *rescan_a, const int32_t *resptr, int64_t M, int nw, Rule R,
+                                                   int32_t *rowbase) {
+    const int t = blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= nw) return;
+    int n_short, n_long;
+    const WinRows z = window_rows(rowptr, rescan_a, M, t, R, &n_short, &n_long);
+    int u = 0, sp = z.q_unsplit;
+    const int64_t r0 = (int64_t)t * W;
+    for (int r = 0; r < z.nr; ++r) {
+        int off;
+        if ((z.split >> r) & 1u) { off = sp; sp += z.rlen[r]; } else { off = u; u += z.rlen[r]; }
+        rowbase[r0 + r] = resptr[t] + off - rescan_a[rowptr[r0 + r]];
+    }
+}
+
+// Per nonzero (CSR order): residual nonzeros to their places.  SDDMM: CSR order.
+__global__ __launch_bounds__(256) void k_residual_fill(const int32_t *col, const uint8_t *val, int vsize, int n, Rule R, const int32_t *row_of,
+                                                      const int32_t *resf_a, const int32_t *rescan_a, const int32_t *rowbase,
                                                       int32_t *a_perm, int32_t *a_row, int32_t *a_col, uint8_t *a_val,
                                                       const int32_t *resf_d, const int32_t *rescan_d,
                                                       int32_t *d_perm, int32_t *d_row, int32_t *d_col, uint8_t *d_val) {
-    __shared__ int off[W];
-    const int t = blockIdx.x;
-    const int lane = threadIdx.x;
-    const int64_t r0 = (int64_t)t * W;
-    if (lane == 0) {
-        int n_short, n_long;
-        WinRows z{};
-        if (R.build_a) z = window_rows(rowptr, rescan_a, M, t, R, &n_short, &n_long);
-        int u = 0, s = z.q_unsplit;
-        for (int r = 0; r < W; ++r) {
-            if ((z.split >> r) & 1u) { off[r] = s; s += z.rlen[r]; } else { off[r] = u; u += z.rlen[r]; }
-        }
+    const int p = blockIdx.x * blockDim.x + threadIdx.x;
+    if (p >= n) return;
+    const bool ra = R.build_a && resf_a[p], rd = R.build_d && resf_d[p];
+    if (!ra && !rd) return;
+    const int i = row_of[p], c = col[p];
+    if (ra) {
+        const int d = rowbase[i] + rescan_a[p];
+        a_perm[d] = p; a_row[d] = i; a_col[d] = c;
+        if (vsize == 2) reinterpret_cast<uint16_t *>(a_val)[d] = reinterpret_cast<const uint16_t *>(val)[p];
+        else reinterpret_cast<uint32_t *>(a_val)[d] = reinterpret_cast<const uint32_t *>(val)[p];
     }
-    __syncthreads();
-    const int nr = (int)min((int64_t)W, M - r0);
-    for (int r = 0; r < nr; ++r) {
-        const int64_t i = r0 + r;
-        const int s = rowptr[i], e = rowptr[i + 1];
-        const int base_a = R.build_a ? resptr[t] + off[r] - rescan_a[s] : 0;
-        for (int p = s + lane; p < e; p += 64) {
-            const int c = col[p];
-            if (R.build_a && resf_a[p]) {
-                const int d = base_a + rescan_a[p];
-                a_perm[d] = p; a_row[d] = (int32_t)i; a_col[d] = c;
-                if (vsize == 2) reinterpret_cast<uint16_t *>(a_val)[d] = reinterpret_cast<const uint16_t *>(val)[p];
-                else reinterpret_cast<uint32_t *>(a_val)[d] = reinterpret_cast<const uint32_t *>(val)[p];
-            }
-            if (R.build_d && resf_d[p]) {
-                const int d = rescan_d[p];
-                d_perm[d] = p; d_row[d] = (int32_t)i; d_col[d] = c;
-                if (vsize == 2) reinterpret_cast<uint16_t *>(d_val)[d] = reinterpret_cast<const uint16_t *>(val)[p];
-                else reinterpret_cast<uint32_t *>(d_val)[d] = reinterpret_cast<const uint32_t *>(val)[p];
-            }
-        }
+    if (rd) {
+        const int d = rescan_d[p];
+        d_perm[d] = p; d_row[d] = i; d_col[d] = c;
+        if (vsize == 2) reinterpret_cast<uint16_t *>(d_val)[d] = reinterpret_cast<const uint16_t *>(val)[p];
+        else reinterpret_cast<uint32_t *>(d_val)[d] = reinterpret_cast<const uint32_t *>(val)[p];
     }
 }
 
@@ -733,7 +735,7 @@ extern "C" int libra_plan_device(int64_t M, int64_t Kc, int64_t nnz, const int32
         // ---- 1. census: sort the nonzeros of every window by (column, row) ----
         fill_bytes(L.ctr, 0, C_COUNT * sizeof(u64), s);
         hipLaunchKernelGGL(k_win_ptr, dim3(blocks_for(nw + 1, 256)), dim3(256), 0, s, d_rowptr, M, nw, L.win_ptr);
-        hipLaunchKernelGGL(k_keys, dim3((unsigned)nw), dim3(64), 0, s, d_rowptr, d_col, M, Kc, L.key_in, L.ctr);
+        hipLaunchKernelGGL(k_keys, dim3(blocks_for(n, 256)), dim3(256), 0, s, d_rowptr, d_col, M, Kc, n, L.key_in, L.row_of, L.ctr);
         {
             size_t sz = L.tmp_bytes;
             hip_ok(rocprim::segmented_radix_sort_pairs(L.tmp, sz, L.key_in, L.key_out, rocprim::counting_iterator<int32_t>(0), L.spos,
@@ -823,9 +825,11 @@ extern "C" int libra_plan_device(int64_t M, int64_t Kc, int64_t nnz, const int32
                            L.a.ntasks, L.nzero, L.nres, L.d.ntasks, L.ctr, L.a.tbase, L.zbase, L.resptr, L.d.tbase,
                            L.a.tasks, L.zero_rows, L.d.tasks);
         const int64_t ngroups = (nw + LIBRA_LOCALITY_WINDOWS - 1) / LIBRA_LOCALITY_WINDOWS, nsample = share_samples(ngroups);
-        hipLaunchKernelGGL(k_share, dim3((unsigned)nsample), dim3(256), 0, s, L.win_vptr, L.vcol, nw, ngroups, nsample, L.ctr);
-        hipLaunchKernelGGL(k_residual_fill, dim3((unsigned)nw), dim3(64), 0, s, d_rowptr, d_col, val, vsize, M, R,
-                           L.a.resf, L.a.rescan, L.resptr, L.a.res_perm, L.a.res_row, L.a.res_col, L.a.res_val,
+        hipLaunchKernelGGL(k_share, dim3((unsigned)nsample, 16), dim3(256), 0, s, L.win_vptr, L.vcol, nw, ngroups, nsample, L.ctr);
+        if (o.build_spmm)
+            hipLaunchKernelGGL(k_row_bases, dim3(blocks_for(nw, 128)), dim3(128), 0, s, d_rowptr, L.a.rescan, L.resptr, M, nw, R, L.rowbase);
+        hipLaunchKernelGGL(k_residual_fill, dim3(blocks_for(n, 256)), dim3(256), 0, s, d_col, val, vsize, n, R, L.row_of,
+                           L.a.resf, L.a.rescan, L.rowbase, L.a.res_perm, L.a.res_row, L.a.res_col, L.a.res_val,
                            L.d.resf, L.d.rescan, L.d.res_perm, L.d.res_row, L.d.res_col, L.d.res_val);
         hip_ok(hipMemcpyAsync(ctr, L.ctr, sizeof ctr, hipMemcpyDeviceToHost, s));
         hip_ok(hipStreamSynchronize(s));
