@@ -59,12 +59,14 @@ def main() -> int:
     Y = torch.from_numpy(wl.dense_normal(A.Kc, args.K, seed=3)).cuda()
     C = torch.empty((A.M, args.N), dtype=torch.float32, device="cuda")
     out = torch.empty(A.nnz, dtype=torch.float32, device="cuda")
+    rowptr, col, val = (torch.from_numpy(x).cuda() for x in (A.rowptr.astype(np.int32), A.col.astype(np.int32), A.val))
     print(f"# {args.workload}: M={A.M} nnz={A.nnz} N={args.N} K={args.K}")
     print(f"# {'setting':34s} {'spmm us':>9s} {'dense':>6s} {'tasks':>8s} | {'sddmm us':>9s} {'dense':>6s} {'tasks':>8s}")
     names = list(SWEEPS) if args.what == "all" else [args.what]
     for name in names:
         for kw in SWEEPS[name]:
-            p = lb.Plan.from_csr(A, **kw).upload()
+            # a plan per setting, built on the GPU straight into device memory
+            p = lb.Plan.from_device_csr(A.M, A.Kc, rowptr, col, val, resident=True, keep_host_copy=False, **kw)
             st = p.stats()
             t_spmm = time_us(lambda: p.spmm(B, out=C)) if name not in ("tau_sddmm", "sddmm_cs") else float("nan")
             t_sddmm = time_us(lambda: p.sddmm(X, Y, out=out)) if name not in ("tau_spmm", "cs") else float("nan")
