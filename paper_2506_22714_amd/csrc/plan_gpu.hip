@@ -382,8 +382,8 @@ __global__ __launch_bounds__(256) void k_slots(const int32_t *vwin, const int32_
 // 16 lanes per block: column ids, the bitmap (bit r*16+s) by ballots, NNZ, touched rows, real columns.
 __global__ __launch_bounds__(256) void k_blocks(const int32_t *slotvec, const int32_t *vcol, const int32_t *vinfo, int nb,
                                                 int32_t *blk_cols, u64 *bitmap, int32_t *blknnz, int32_t *blkmask, int32_t *blkncols) {
-    const int gid = blockIdx.x * blockDim.x + threadIdx.x;
-    const int b = gid >> 4, s = gid & 15;
+    const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int b = (int)(gid >> 4), s = (int)(gid & 15);
     const int grp = (threadIdx.x & 63) >> 4;
     const bool live = b < nb;
     const int v = live ? slotvec[(int64_t)b * KB + s] : -1;
@@ -413,8 +413,8 @@ __global__ __launch_bounds__(256) void k_blocks(const int32_t *slotvec, const in
 __global__ __launch_bounds__(256) void k_block_values(const int32_t *slotvec, const int32_t *vfirst, const int32_t *vinfo, const u64 *bitmap,
                                                       const int32_t *blk_valptr, const int32_t *spos, const uint8_t *val, int vsize, int nb,
                                                       int32_t *dense_perm, uint8_t *dense_val) {
-    const int gid = blockIdx.x * blockDim.x + threadIdx.x;
-    const int b = gid >> 4, s = gid & 15;
+    const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int b = (int)(gid >> 4), s = (int)(gid & 15);
     if (b >= nb) return;
     const int v = slotvec[(int64_t)b * KB + s];
     if (v < 0) return;

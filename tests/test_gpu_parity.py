@@ -323,6 +323,34 @@ def test_die_aware_task_order_changes_no_result():
     check_sddmm(A, X, Y, res[1][1], TOL_F16)
 
 
+def test_one_plan_on_two_streams():
+    """A plan is read-only during compute calls and has no hidden workspace: calls on different streams may overlap."""
+    A = wl.make("powerlaw", small=True)
+    p = lb.Plan.from_csr(A, cs=32).upload()
+    assert p.stats()["spmm_zero_rows"] > 0                      # rows with several writers are in play
+    Bs = [dev(wl.dense_normal(A.Kc, 64, seed=40 + i)) for i in range(2)]
+    X, Y = dev(wl.dense_normal(A.M, 32, seed=50)), dev(wl.dense_normal(A.Kc, 32, seed=51))
+    ref = [p.spmm(B) for B in Bs]
+    ref_out = p.sddmm(X, Y)
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream() for _ in range(2)]            # default priority
+    got = [None, None]
+    outs = [None, None]
+    for rep in range(5):
+        for i, st in enumerate(streams):
+            with torch.cuda.stream(st):
+                got[i] = p.spmm(Bs[i])
+                outs[i] = p.sddmm(X, Y)
+        torch.cuda.synchronize()
+        one_writer = torch.ones(A.M, dtype=torch.bool, device="cuda")
+        one_writer[torch.from_numpy(p.export(0)["zero_rows"]).cuda().long()] = False
+        for i in range(2):
+            assert torch.equal(got[i][one_writer], ref[i][one_writer])
+            assert torch.allclose(got[i], ref[i], rtol=1e-4, atol=1e-3)
+            assert torch.equal(outs[i], ref_out)
+    p.close()
+
+
 # ------------------------------------------------------------- bfloat16
 def dev_bf16(bits):
     return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda().view(torch.bfloat16)
