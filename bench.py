@@ -218,7 +218,7 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": f"{args.workload}{'-small' if args.small else ''}: M={A.M} nnz={A.nnz} SpMM N={N} + SDDMM K={K}",
                    "M": A.M, "nnz": A.nnz, "N": N, "K": K, "mode": args.mode,
-                   "tau_spmm": args.tau_spmm or 3, "tau_sddmm": args.tau_sddmm or 32},
+                   "tau_spmm": args.tau_spmm or 3, "tau_sddmm": args.tau_sddmm or 64},
         "roofline": {"bound": "hbm", "kernel": f"spmm_task_kernel<{args.dtype},{min(N, 256)}>", "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
                      "algorithmic_bytes": bytes_spmm, "avg_us": round(spmm_avg_s * 1e6, 2),

@@ -43,7 +43,7 @@ class Opts:
     W: int = 16
     KB: int = 16
     tau_spmm: int = 3
-    tau_sddmm: int = 32
+    tau_sddmm: int = 64
     Ts: int = 8
     Cs: int = 128
     short_len: int = 3
