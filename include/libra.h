@@ -73,6 +73,11 @@ extern "C" {
                                            task table then holds a few empty tasks (no work).  Without this flag and the
                                            next one the planner decides from the sampled neighbour_share statistic */
 #define LIBRA_FLAG_NO_XCD_ORDER    32u  /* never use the die-aware order */
+#define LIBRA_FLAG_SEGMENTS_BY_COLUMN 64u /* SpMM, when the die-aware order is not in use: the segments of decomposed rows
+                                           are sorted by their first column and cut into one run per die, so that a
+                                           die fetches dense-operand rows of one column range only.  Cuts the traffic
+                                           behind the L2 (power-law config: 283 -> 211 MB fetched per call) but not the
+                                           time (73.6 vs 71.8 us), hence off by default */
 
 typedef struct libra_plan_s libra_plan_t;   /* opaque; immutable after libra_plan() except for its values */
 

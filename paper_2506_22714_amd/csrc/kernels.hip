@@ -90,13 +90,15 @@ template <> struct Elem<half_t> {
         __builtin_memcpy(&h, &e.val, 2);
         return (float)h;
     }
-    // one 8-byte LDS read per entry
+    // one 8-byte LDS read per entry (the second word goes through an opaque move so that it is read once, whole)
     __device__ static ent_t lds_ent(const ent_t *lds, int i) {
         const uint2 u = reinterpret_cast<const uint2 *>(lds)[i];
+        uint32_t w = u.y;
+        asm volatile("" : "+v"(w));
         ent_t e;
         e.col = (int32_t)u.x;
-        e.val = (uint16_t)(u.y & 0xffffu);
-        e.row = (uint16_t)(u.y >> 16);
+        e.val = (uint16_t)(w & 0xffffu);
+        e.row = (uint16_t)(w >> 16);
         return e;
     }
     // the lane's 16 bytes of row `col`: one 32x32->64 multiply-add for the address
@@ -337,12 +339,19 @@ __global__ __launch_bounds__(WAVE) void spmm_task_kernel(SpmmArgs a) {
                     const int nb = min(FPI, nbr - bb);
                     // one round trip: the B rows of up to FPI blocks (padding slots become zero rows) ...
                     uint4 raw[H][PASSES];
+                    int cc[H][PASSES];
+                    // all column ids first (LDS reads back to back), then all fetches
+#pragma unroll
+                    for (int h = 0; h < H; ++h)
+#pragma unroll
+                        for (int ps = 0; ps < PASSES; ++ps)
+                            cc[h][ps] = cols_lds[bb * KB + min(h * BPI * KB + ps * RPW + grp, nb * KB - 1)];
 #pragma unroll
                     for (int h = 0; h < H; ++h)
 #pragma unroll
                         for (int ps = 0; ps < PASSES; ++ps) {
                             const int k = h * BPI * KB + ps * RPW + grp;
-                            const int c = cols_lds[bb * KB + min(k, nb * KB - 1)];
+                            const int c = cc[h][ps];
                             // a padding slot fetches row 0 and is cleared by a mask the compiler cannot see through
                             // (so that it keeps the fetch outside any branch)
                             uint32_t keep = (k < nb * KB && c >= 0) ? 0xffffffffu : 0u;
@@ -438,8 +447,11 @@ __global__ __launch_bounds__(WAVE) void spmm_task_kernel(SpmmArgs a) {
 #pragma unroll
             for (int k = 0; k < ECAP / WAVE; ++k) next_ent[k] = E::load_ent(src, min(k * WAVE + lane, nE_next - 1));
         }
-        const int per = (nE + RPW - 1) / RPW;
-        const int q0 = grp * per;
+        // runs are whole batches of U entries (the longest run, which sets the time of the round, needs no more batches
+        // for it), so a batch is U consecutive entries from an aligned base address and never leaves the staged array
+        static_assert(ECAP % U == 0, "a batch must not straddle the end of the staged entries");
+        const int per = ((nE + RPW - 1) / RPW + U - 1) / U * U;
+        const int q0 = min(grp * per, nE);
         const int q1 = min(nE, q0 + per);
         // A row is added into the tile by the group that holds its first entry (plain read-add-write:
         // one owner per row).  A group whose run starts inside a row keeps that row's partial sum in
@@ -473,14 +485,10 @@ __global__ __launch_bounds__(WAVE) void spmm_task_kernel(SpmmArgs a) {
             ent_t en[U];
             typename E::raw_t raw[U];
             const bool full = q + U <= q1;
-            if (full) {
+            // U consecutive entries from one base address; slots past the run hold valid entries whose fetch is
+            // harmless and whose product is never formed
 #pragma unroll
-                for (int u = 0; u < U; ++u) en[u] = E::lds_ent(ent_lds, q + u);
-            } else {
-                // slots past the run repeat its last entry (their fetch is harmless, their product is never formed)
-#pragma unroll
-                for (int u = 0; u < U; ++u) en[u] = E::lds_ent(ent_lds, min(q + u, q1 - 1));
-            }
+            for (int u = 0; u < U; ++u) en[u] = E::lds_ent(ent_lds + q, u);
 #pragma unroll
             for (int u = 0; u < U; ++u) raw[u] = E::load_row(a.B, en[u].col, ldb_bytes, sub);
             bool one_row = full;

@@ -194,13 +194,17 @@ void plan_range(const Ctx &c, int64_t w0, int64_t w1, Part &out) {
                 for (int32_t g0 = b0; g0 < b1; g0 += o.Ts) {
                     int32_t g1 = std::min(b1, g0 + o.Ts);
                     sa.tasks.push_back({LIBRA_TASK_WINDOW, (int32_t)w, g0, g1, q0, q0, 0u, touched(g0, g1), 0u, cols_in(g0, g1)});
+                    sa.task_col.push_back(-1);
                 }
-                if (scalar_mask)
+                if (scalar_mask) {
                     sa.tasks.push_back({LIBRA_TASK_WINDOW, (int32_t)w, b1, b1, q0, q1, scalar_mask, scalar_mask, 0u, (uint32_t)(q1 - q0)});
+                    sa.task_col.push_back(-1);
+                }
                 for (int64_t i = r0; i < r1; ++i) sa.zero_rows.push_back((int32_t)i);
             } else {
                 sa.tasks.push_back({LIBRA_TASK_WINDOW, (int32_t)w, b0, b1, q0, q1, scalar_mask, split_mask & touched(b0, b1),
                                     valid & ~split_mask, cols_in(b0, b1) + (uint32_t)(q1 - q0)});
+                sa.task_col.push_back(-1);
                 for (int r = 0; r < (int)(r1 - r0); ++r)
                     if (split_mask >> r & 1) sa.zero_rows.push_back((int32_t)(r0 + r));
             }
@@ -213,6 +217,7 @@ void plan_range(const Ctx &c, int64_t w0, int64_t w1, Part &out) {
                     for (; q < e; q += o.Cs) {
                         int32_t qe = std::min(e, q + o.Cs);
                         sa.tasks.push_back({LIBRA_TASK_CHUNK, (int32_t)(r0 + r), 0, 0, q, qe, 0u, 0u, 0u, (uint32_t)(qe - q)});
+                        sa.task_col.push_back(sa.res_col[q]);            // first column of the segment
                     }
                     q = e;
                 }
@@ -283,6 +288,7 @@ void concat(SubPlan &dst, SubPlan &src, bool spmm) {
     append(dst.res_row, src.res_row);
     append(dst.res_val, src.res_val);
     append(dst.zero_rows, src.zero_rows);
+    append(dst.task_col, src.task_col);
     if (spmm)
         for (size_t i = 1; i < src.win_resptr.size(); ++i) dst.win_resptr.push_back(src.win_resptr[i] + res_base);
     for (libra_task_t t : src.tasks) {
@@ -296,6 +302,36 @@ void concat(SubPlan &dst, SubPlan &src, bool spmm) {
     dst.long_rows += src.long_rows;
     dst.split_rows += src.split_rows;
     src = SubPlan();
+}
+
+// The task table that interleaves LIBRA_XCDS queues of positions into tasks[begin, end): entry LIBRA_XCDS*j + x is
+// the j-th task of queue x.  Queues of different length are levelled (see below).
+void interleave_queues(std::vector<libra_task_t> &tasks, size_t begin, size_t end, std::vector<size_t> (&queue)[LIBRA_XCDS], int noop_kind) {
+    // level the queue lengths first: the last (lightest) tasks of a long queue move to the end of the shortest one;
+    // what is left to fill with empty tasks is at most one slot per queue
+    for (;;) {
+        int lo = 0, hi = 0;
+        for (int x = 1; x < LIBRA_XCDS; ++x) {
+            if (queue[x].size() < queue[lo].size()) lo = x;
+            if (queue[x].size() > queue[hi].size()) hi = x;
+        }
+        if (queue[hi].size() - queue[lo].size() <= 1) break;
+        const size_t move = (queue[hi].size() - queue[lo].size()) / 2;
+        queue[lo].insert(queue[lo].end(), queue[hi].end() - move, queue[hi].end());
+        queue[hi].resize(queue[hi].size() - move);
+    }
+    size_t maxlen = 0;
+    for (auto &q : queue) maxlen = std::max(maxlen, q.size());
+    const libra_task_t noop{noop_kind, 0, 0, 0, 0, 0, 0u, 0u, 0u, 0u};
+    std::vector<libra_task_t> out;
+    out.reserve(maxlen * LIBRA_XCDS);
+    for (size_t j = 0; j < maxlen; ++j)
+        for (int x = 0; x < LIBRA_XCDS; ++x) out.push_back(j < queue[x].size() ? tasks[begin + queue[x][j]] : noop);
+    while (!out.empty() && out.back().cost == 0 && out.back().blk_begin == out.back().blk_end &&
+           out.back().res_begin == out.back().res_end && out.back().store_mask == 0 && out.back().atomic_mask == 0)
+        out.pop_back();                                             // empty tasks after the last real one
+    tasks.erase(tasks.begin() + begin, tasks.begin() + end);
+    tasks.insert(tasks.begin() + begin, out.begin(), out.end());
 }
 
 // XCD-aware placement.  Workgroup k of a launch runs on XCD k mod LIBRA_XCDS and every XCD has its own L2, so
@@ -326,18 +362,39 @@ void xcd_order(std::vector<libra_task_t> &tasks, size_t begin, size_t end, Group
         std::vector<size_t> &q = queue[round & 1 ? LIBRA_XCDS - 1 - x : x];
         for (size_t k = 0; k < groups[r].count; ++k) q.push_back(key[groups[r].first + k].second);
     }
-    size_t maxlen = 0;
-    for (auto &q : queue) maxlen = std::max(maxlen, q.size());
-    const libra_task_t noop{noop_kind, 0, 0, 0, 0, 0, 0u, 0u, 0u, 0u};
-    std::vector<libra_task_t> out;
-    out.reserve(maxlen * LIBRA_XCDS);
-    for (size_t j = 0; j < maxlen; ++j)
-        for (int x = 0; x < LIBRA_XCDS; ++x) out.push_back(j < queue[x].size() ? tasks[begin + queue[x][j]] : noop);
-    while (!out.empty() && out.back().cost == 0 && out.back().blk_begin == out.back().blk_end &&
-           out.back().res_begin == out.back().res_end && out.back().store_mask == 0 && out.back().atomic_mask == 0)
-        out.pop_back();                                             // empty tasks after the last real one
-    tasks.erase(tasks.begin() + begin, tasks.begin() + end);
-    tasks.insert(tasks.begin() + begin, out.begin(), out.end());
+    interleave_queues(tasks, begin, end, queue, noop_kind);
+}
+
+// Segments of decomposed rows by column.  A long row's segments are runs of consecutive columns, and they add
+// into C with atomics whichever die runs them.  So the segments are sorted by their first column and cut into
+// LIBRA_XCDS runs of equal cost, one per die: a die then fetches rows of the dense operand from one column range
+// only, in ascending order, instead of from all of it, and its L2 can hold them.  The other tasks are dealt to the
+// dies heaviest first as before; each die's queue is merged by cost.
+void place_segments_by_column(std::vector<libra_task_t> &tasks, const std::vector<int32_t> &first_col) {
+    const size_t n = tasks.size();
+    std::vector<size_t> seg, other;
+    for (size_t i = 0; i < n; ++i) (tasks[i].kind == LIBRA_TASK_CHUNK ? seg : other).push_back(i);
+    if (seg.size() < 8 * LIBRA_XCDS) return;
+    std::stable_sort(seg.begin(), seg.end(), [&](size_t a, size_t b) { return first_col[a] < first_col[b]; });
+    uint64_t total = 0;
+    for (size_t i : seg) total += tasks[i].cost;
+    std::vector<size_t> segq[LIBRA_XCDS], othq[LIBRA_XCDS], queue[LIBRA_XCDS];
+    uint64_t run = 0;
+    for (size_t i : seg) {
+        const size_t x = std::min<uint64_t>(LIBRA_XCDS - 1, run * LIBRA_XCDS / std::max<uint64_t>(total, 1));
+        segq[x].push_back(i);
+        run += tasks[i].cost;
+    }
+    for (size_t r = 0; r < other.size(); ++r) {
+        const size_t round = r / LIBRA_XCDS, x = r % LIBRA_XCDS;
+        othq[round & 1 ? LIBRA_XCDS - 1 - x : x].push_back(other[r]);
+    }
+    for (int x = 0; x < LIBRA_XCDS; ++x) {
+        queue[x].resize(segq[x].size() + othq[x].size());
+        std::merge(othq[x].begin(), othq[x].end(), segq[x].begin(), segq[x].end(), queue[x].begin(),
+                   [&](size_t a, size_t b) { return tasks[a].cost > tasks[b].cost; });
+    }
+    interleave_queues(tasks, 0, n, queue, LIBRA_TASK_WINDOW);
 }
 
 // How much neighbouring windows overlap in the columns they reference, on an evenly spaced sample of groups of
@@ -394,7 +451,8 @@ int libra::resolve_options(const libra_plan_opts_t *in, int vdt, Resolved &o) {
     o.heavy_first = !(z.flags & LIBRA_FLAG_NATURAL_ORDER);
     if ((z.flags & LIBRA_FLAG_XCD_ORDER) && (z.flags & LIBRA_FLAG_NO_XCD_ORDER)) return LIBRA_ERR_OPTION;
     o.xcd_order = !o.heavy_first || (z.flags & LIBRA_FLAG_NO_XCD_ORDER) ? 0 : (z.flags & LIBRA_FLAG_XCD_ORDER) ? 1 : -1;
-    if (z.flags & ~63u) return LIBRA_ERR_OPTION;
+    o.segments_by_column = o.heavy_first && (z.flags & LIBRA_FLAG_SEGMENTS_BY_COLUMN);
+    if (z.flags & ~127u) return LIBRA_ERR_OPTION;
     return LIBRA_OK;
 }
 
@@ -431,13 +489,27 @@ void libra::finish_plan(libra_plan_t *P, const ColumnFetch &cols, const int64_t 
     st.neighbour_share = share ? (share[1] ? (double)share[0] / (double)share[1] : 1.0) : neighbour_share(M, rowptr, cols, o.W);
     if (o.heavy_first) {
         auto heavier = [](const libra_task_t &a, const libra_task_t &b) { return a.cost > b.cost; };
-        std::stable_sort(sa.tasks.begin(), sa.tasks.end(), heavier);
+        {
+            // heaviest first, the segments' first columns travelling with their tasks
+            std::vector<size_t> ord(sa.tasks.size());
+            for (size_t i = 0; i < ord.size(); ++i) ord[i] = i;
+            std::stable_sort(ord.begin(), ord.end(), [&](size_t a, size_t b) { return sa.tasks[a].cost > sa.tasks[b].cost; });
+            std::vector<libra_task_t> ts(ord.size());
+            std::vector<int32_t> tc(ord.size(), -1);
+            for (size_t i = 0; i < ord.size(); ++i) {
+                ts[i] = sa.tasks[ord[i]];
+                tc[i] = sa.task_col.at(ord[i]);          // both planners fill one entry per task
+            }
+            sa.tasks.swap(ts);
+            sa.task_col.swap(tc);
+        }
         // SDDMM window tasks first (heaviest first); the flat residual segments stay behind them in order
         auto mid = std::stable_partition(sd.tasks.begin(), sd.tasks.end(),
                                          [](const libra_task_t &t) { return t.kind == LIBRA_TASK_WINDOW; });
         std::stable_sort(sd.tasks.begin(), mid, heavier);
         if (xcd < 0) P->o.xcd_order = xcd = st.neighbour_share <= LIBRA_SHARE_THRESHOLD;
         st.xcd_order = xcd;
+        if (!xcd && o.segments_by_column) place_segments_by_column(sa.tasks, sa.task_col);
         if (xcd) {
             const int W = o.W;
             xcd_order(sa.tasks, 0, sa.tasks.size(), [W](const libra_task_t &t, size_t) {

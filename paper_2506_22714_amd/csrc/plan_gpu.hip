@@ -83,7 +83,7 @@ struct Layout {
     int32_t *win_ptr, *spos, *hflag, *vid, *einfo, *ewin, *row_of, *rowbase;
     u64 *key_in, *key_out, *key2_in, *key2_out, *ctr;
     int32_t *vfirst, *vinfo, *vcol, *vwin, *sv, *srank, *scnt, *cum, *tflag, *taud, *win_vptr;
-    int32_t *ntau, *nzero, *zbase, *nres, *resptr, *zero_rows;
+    int32_t *ntau, *nzero, *zbase, *nres, *resptr, *zero_rows, *task_col;
     SubOut a, d;
     void *tmp;
     size_t tmp_bytes;
@@ -137,6 +137,7 @@ Layout make_layout(const Sizes &z, int vsize, void *base) {
     L.nres = A.take<int32_t>(nw + 1);
     L.resptr = A.take<int32_t>(nw + 1);
     L.zero_rows = A.take<int32_t>((size_t)z.M);
+    L.task_col = A.take<int32_t>((size_t)z.tasks_a_max);
     for (SubOut *s : {&L.a, &L.d}) {
         s->slotvec = A.take<int32_t>(nb * KB);
         s->blk_cols = A.take<int32_t>(nb * KB);
@@ -606,6 +607,13 @@ __global__ __launch_bounds__(256) void k_residual_fill(const int32_t *col, const
     }
 }
 
+// Per SpMM task: first column of a row segment's entries (the host orders the segments by it), -1 for other tasks.
+__global__ __launch_bounds__(256) void k_task_cols(const libra_task_t *tasks, int nt, const int32_t *res_col, int32_t *task_col) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= nt) return;
+    task_col[i] = tasks[i].kind == LIBRA_TASK_CHUNK ? res_col[tasks[i].res_begin] : -1;
+}
+
 // ------------------------------------------------------------------------------------------
 // host driver
 // ------------------------------------------------------------------------------------------
@@ -831,6 +839,8 @@ extern "C" int libra_plan_device(int64_t M, int64_t Kc, int64_t nnz, const int32
         hipLaunchKernelGGL(k_residual_fill, dim3(blocks_for(n, 256)), dim3(256), 0, s, d_col, val, vsize, n, R, L.row_of,
                            L.a.resf, L.a.rescan, L.rowbase, L.a.res_perm, L.a.res_row, L.a.res_col, L.a.res_val,
                            L.d.resf, L.d.rescan, L.d.res_perm, L.d.res_row, L.d.res_col, L.d.res_val);
+        if (o.build_spmm && ntA > 0)
+            hipLaunchKernelGGL(k_task_cols, dim3(blocks_for(ntA, 256)), dim3(256), 0, s, L.a.tasks, ntA, L.a.res_col, L.task_col);
         hip_ok(hipMemcpyAsync(ctr, L.ctr, sizeof ctr, hipMemcpyDeviceToHost, s));
         hip_ok(hipStreamSynchronize(s));
         if (hipGetLastError() != hipSuccess) throw Fail{LIBRA_ERR_HIP};
@@ -849,6 +859,7 @@ extern "C" int libra_plan_device(int64_t M, int64_t Kc, int64_t nnz, const int32
             H.n.blocks = nbs[k]; H.n.col_slots = (int64_t)nbs[k] * KB; H.n.bitmap_words = (int64_t)nbs[k] * 4;
             H.n.dense = dn[k]; H.n.res = nres2[k]; H.n.zero_rows = k == 0 ? nz : 0;
             fetch(H.tasks, S.tasks, (size_t)nts[k], s);
+            if (k == 0) fetch(H.task_col, L.task_col, (size_t)nts[k], s);
             fetch(H.blk_valptr, S.blk_valptr, (size_t)nbs[k] + 1, s);
             if (!keep_host_copy) continue;
             fetch(H.win_blkptr, S.blkptr, (size_t)nw + 1, s);

@@ -92,6 +92,7 @@ struct SubPlan {
     std::vector<uint8_t> dense_val, res_val;        // raw bytes, value dtype
     std::vector<int32_t> win_resptr, res_row, res_col, res_perm, zero_rows;
     std::vector<libra_task_t> tasks;
+    std::vector<int32_t> task_col;      // SpMM, until the tables are ordered: first column of a row segment's entries, -1 for other tasks
     int64_t n_window_tasks = 0, n_chunk_tasks = 0;
     int64_t dense_vectors = 0, pad_slots = 0;
     int64_t short_rows = 0, long_rows = 0, split_rows = 0;
@@ -109,7 +110,7 @@ struct SubPlan {
 
 struct Resolved {
     int mode, W, KB, tau_spmm, tau_sddmm, Ts, Cs, short_len, sddmm_Cs, threads;
-    bool fill, build_spmm, build_sddmm, heavy_first;
+    bool fill, build_spmm, build_sddmm, heavy_first, segments_by_column;
     int xcd_order;       // 1 on, 0 off, -1 decide from the matrix
 };
 

@@ -245,3 +245,23 @@ def test_xcd_order_keeps_the_tasks_and_puts_neighbouring_windows_on_one_die():
         for g, ks in pos.items():
             assert len({k % 8 for k in ks}) == 1, g
             assert max(ks) - min(ks) == 8 * (len(ks) - 1), g
+
+
+def test_segments_by_column_keeps_the_tasks_and_gives_each_die_one_column_range():
+    A = wl.rmat(scale=12, avg_degree=24, seed=6)
+    base = lb.Plan.from_csr(A, cs=16, flags=lb.FLAG_NO_XCD_ORDER)
+    plan = lb.Plan.from_csr(A, cs=16, flags=lb.FLAG_NO_XCD_ORDER | lb.FLAG_SEGMENTS_BY_COLUMN)
+    ex = plan.export(0)
+    t = ex["tasks"]
+    assert canon_tasks(t) == canon_tasks(base.export(0)["tasks"])
+    assert sum(bool(is_empty_task(x)) for x in t) <= 8
+    first_col = np.array([ex["res_col"][x["res_begin"]] if x["kind"] == lb.TASK_CHUNK else -1 for x in t])
+    seg = t["kind"] == lb.TASK_CHUNK
+    assert seg.sum() > 200
+    med = [np.median(first_col[q::8][seg[q::8]]) for q in range(8)]
+    assert all(med[q] < med[q + 1] for q in range(7))              # column ranges ascend from die to die
+    for q in range(7):                              # (light tasks moved to level the queues may stray)
+        assert (first_col[q::8][seg[q::8]] > med[q + 1]).mean() <= 0.2
+    for q in range(8):                              # and a die meets its segments in ascending column order
+        c = first_col[q::8][seg[q::8]]
+        assert (np.diff(c) < 0).sum() <= 0.1 * c.size
