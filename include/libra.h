@@ -78,6 +78,10 @@ extern "C" {
                                            die fetches dense-operand rows of one column range only.  Cuts the traffic
                                            behind the L2 (power-law config: 283 -> 211 MB fetched per call) but not the
                                            time (73.6 vs 71.8 us), hence off by default */
+#define LIBRA_FLAG_TWO_KERNELS    128u  /* libra_spmm runs the task table twice on the stream: first the dense blocks (MFMA), then the
+                                           residual nonzeros (VALU), which add to what the first launch wrote - the paper's
+                                           sequential schedule of its two kernels (Section 4.4.1).  Same results up to the order
+                                           of additions; for debugging and as the baseline the fused task is measured against */
 
 typedef struct libra_plan_s libra_plan_t;   /* opaque; immutable after libra_plan() except for its values */
 

@@ -20,7 +20,7 @@ LIB_PATH = os.environ.get("LIBRA_LIBRARY") or os.path.join(_HERE, "liblibra.so")
 F16, BF16, F32 = 0, 1, 2
 MODE_HYBRID, MODE_DENSE_ONLY, MODE_SCALAR_ONLY = 0, 1, 2
 FLAG_NO_FILL_PADDING, FLAG_NO_SPMM, FLAG_NO_SDDMM, FLAG_NATURAL_ORDER, FLAG_XCD_ORDER, FLAG_NO_XCD_ORDER = 1, 2, 4, 8, 16, 32
-FLAG_SEGMENTS_BY_COLUMN = 64
+FLAG_SEGMENTS_BY_COLUMN, FLAG_TWO_KERNELS = 64, 128
 TASK_WINDOW, TASK_CHUNK = 0, 1
 OK = 0
 ERR = dict(NULL=-1, SHAPE=-2, ROWPTR=-3, COLUMN=-4, UNSORTED=-5, TOO_LARGE=-6, DTYPE=-7, OPTION=-8,

@@ -52,6 +52,7 @@ struct SpmmArgs {
     const void *B;
     float *C;
     int64_t ldb, ldc;
+    int32_t phase;          // 0: a task does all its work; 1: dense blocks only; 2: residual nonzeros only, added to what phase 1 wrote
 };
 
 // Per storage type: how a lane reads its piece of a dense-operand row and a residual entry.
@@ -271,8 +272,15 @@ __global__ __launch_bounds__(WAVE) void spmm_task_kernel(SpmmArgs a) {
     const int grp = lane / LPR;              // which lane group
     const uint32_t atomic_mask = t.masks & 0xffffu, store_mask = t.masks >> 16;
     const uint32_t out_mask = atomic_mask | store_mask;
-    const int nblk = t.blk_end - t.blk_begin;
-    const int L = t.res_end - t.res_begin;
+    // The two-kernel mode (the paper's sequential schedule of Section 4.4.1: matrix-unit part, then scalar part) runs
+    // the table twice.  Phase 1 takes the tasks that have blocks and writes all their rows; phase 2 takes the tasks that
+    // have residual nonzeros or own rows that phase 1 did not write, and adds to rows that phase 1 wrote.
+    const int nblk_all = t.blk_end - t.blk_begin;
+    if (a.phase == 1 && nblk_all == 0) return;
+    const int nblk = a.phase == 2 ? 0 : nblk_all;
+    const int L = a.phase == 1 ? 0 : t.res_end - t.res_begin;
+    if (a.phase == 2 && nblk_all > 0 && L == 0) return;
+    const bool add_to_c = a.phase == 2 && nblk_all > 0;
     const uint32_t ldb_bytes = (uint32_t)a.ldb * (uint32_t)sizeof(T);
 
     // ---- round trip 2: all metadata of the task (first round of each kind) ----
@@ -545,7 +553,12 @@ __global__ __launch_bounds__(WAVE) void spmm_task_kernel(SpmmArgs a) {
             float *dst = cbase + (int64_t)r * a.ldc;
             if (store_mask >> r & 1u) {
                 // streaming store: C is written once and not read again by this call
-                __builtin_nontemporal_store(*reinterpret_cast<const float4_t *>(&tile[r * LDC + cl * 4]), reinterpret_cast<float4_t *>(dst + cl * 4));
+                float4_t x = *reinterpret_cast<const float4_t *>(&tile[r * LDC + cl * 4]);
+                if (add_to_c) {           // stream order: phase 1 has written the row
+                    const float4_t y = *reinterpret_cast<const float4_t *>(dst + cl * 4);
+                    x[0] += y[0]; x[1] += y[1]; x[2] += y[2]; x[3] += y[3];
+                }
+                __builtin_nontemporal_store(x, reinterpret_cast<float4_t *>(dst + cl * 4));
             } else {
                 // each atomic instruction covers LPF consecutive floats of the row
 #pragma unroll
@@ -865,10 +878,12 @@ int launch_spmm(const SpmmArgs &a, int64_t ntasks, hipStream_t s) {
     return hip_rc(hipGetLastError());
 }
 
+int spmm_launch(const libra_plan_t *P, const SpmmArgs &a, int n, int64_t nt, hipStream_t s);
+
 int spmm_piece(const libra_plan_t *P, const void *B, int n, int64_t ldb, float *C, int64_t ldc, hipStream_t s) {
     const SubPlan &sp = P->spmm;
     SpmmArgs a{sp.dev.tasks, sp.dev.blk_cols, sp.dev.blk_bitmap, sp.dev.blk_valptr, sp.dev.dense_val,
-               sp.dev.res_ent, B, C, ldb, ldc};
+               sp.dev.res_ent, B, C, ldb, ldc, 0};
     if (sp.n.zero_rows) {
         const int64_t total = sp.n.zero_rows * (n / 4);
         const unsigned blocks = (unsigned)std::min<int64_t>((total + 255) / 256, 65536);
@@ -876,6 +891,19 @@ int spmm_piece(const libra_plan_t *P, const void *B, int n, int64_t ldb, float *
         if (hipGetLastError() != hipSuccess) return LIBRA_ERR_HIP;
     }
     const int64_t nt = (int64_t)sp.tasks.size();
+    if (P->o.two_kernels && a.phase == 0) {
+        // ablation / debugging schedule: the matrix-unit part and the scalar part as two launches on the stream
+        for (int phase = 1; phase <= 2; ++phase) {
+            SpmmArgs b = a;
+            b.phase = phase;
+            if (int rc = spmm_launch(P, b, n, nt, s)) return rc;
+        }
+        return LIBRA_OK;
+    }
+    return spmm_launch(P, a, n, nt, s);
+}
+
+int spmm_launch(const libra_plan_t *P, const SpmmArgs &a, int n, int64_t nt, hipStream_t s) {
     if (P->vdt == LIBRA_F16) {
         switch (n) {
         case 32: return launch_spmm<half_t, 32>(a, nt, s);

@@ -323,6 +323,24 @@ def test_die_aware_task_order_changes_no_result():
     check_sddmm(A, X, Y, res[1][1], TOL_F16)
 
 
+@pytest.mark.parametrize("N", [64, 128])
+def test_two_kernel_schedule_matches_the_fused_task(N):
+    """Dense blocks and residual nonzeros as two launches (the paper's sequential schedule): same result up to the order
+    of the fp32 additions."""
+    A = mixed_matrix(seed=9)
+    B = wl.dense_normal(A.Kc, N, seed=60 + N)
+    fused, st = gpu_spmm(A, B, ts=2, cs=48)
+    assert 0 < st["spmm_dense_nnz"] < A.nnz and st["spmm_chunk_tasks"] > 0
+    two, _ = gpu_spmm(A, B, ts=2, cs=48, flags=lb.FLAG_TWO_KERNELS)
+    check_spmm(A, B, two, TOL_F16)
+    assert np.allclose(two, fused, rtol=1e-5, atol=1e-4)
+    Bi = wl.dense_small_int(A.Kc, N, seed=61)               # exact arithmetic: any order gives the same bits
+    Ai = wl.Csr(A.M, A.Kc, A.rowptr, A.col, np.sign(A.val).astype(np.float16))
+    f2, _ = gpu_spmm(Ai, Bi, ts=2, cs=48)
+    t2, _ = gpu_spmm(Ai, Bi, ts=2, cs=48, flags=lb.FLAG_TWO_KERNELS)
+    assert np.array_equal(f2, t2)
+
+
 def test_one_plan_on_two_streams():
     """A plan is read-only during compute calls and has no hidden workspace: calls on different streams may overlap."""
     A = wl.make("powerlaw", small=True)
