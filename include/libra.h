@@ -285,6 +285,17 @@ int libra_csr_transpose_device(int64_t M, int64_t Kc, int64_t nnz, const int32_t
                                void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * libra_probe_coissue - the register-only concurrency experiment of Section 3.1 on this GPU: 1024 workgroups of 8 waves
+ * (two per SIMD) run `iters` rounds of (a) 4 independent MFMA 16x16x16 chains on four of the waves, (b) 32 FMAs on
+ * 8 independent chains on the other four, (c) both at once.  times_us[0..2] receive the best of three timed launches of
+ * (a), (b), (c).  (c) close to max(a, b) means the two units work side by side.
+ *   sink_dev  device, at least one float (never written in practice; keeps the loops alive)
+ *   times_us  host out.  The call creates two events, synchronises on them, and destroys them.
+ * Errors: NULL, SHAPE, HIP.
+ */
+int libra_probe_coissue(int iters, float *sink_dev, float times_us[3], void *stream);
+
+/*
  * libra_plan_set_values - replace A's values (same pattern): scatters CSR-ordered device values into the
  * packed dense-block and residual arrays of both sub-plans' device copies.  The host copy keeps the old
  * values.  `dtype` must equal the plan's value type.  Errors: NULL, DTYPE, NOT_UPLOADED, HIP.

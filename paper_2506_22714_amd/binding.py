@@ -105,6 +105,7 @@ def lib() -> C.CDLL:
         L.libra_sddmm_pattern.argtypes = [vp, vp, vp, i32, vp, vp]
         L.libra_edge_softmax.argtypes = [vp, vp, C.c_float, vp, C.c_int, vp]
         L.libra_edge_softmax_backward.argtypes = [vp, vp, C.c_int, vp, C.c_float, vp, vp]
+        L.libra_probe_coissue.argtypes = [C.c_int, vp, C.POINTER(C.c_float * 3), vp]
         L.libra_csr_transpose_workspace.argtypes = [i64, C.POINTER(sz)]
         L.libra_csr_transpose_device.argtypes = [i64, i64, i64, vp, vp, vp, vp, vp, vp, sz, vp]
         L.libra_plan_set_values.argtypes = [vp, vp, C.c_int, vp]
@@ -215,6 +216,13 @@ def libra_edge_softmax_backward(plan, alpha_ptr: int, alpha_dtype: int, dalpha_p
                                 stream: int = 0):
     _check(lib().libra_edge_softmax_backward(plan, C.c_void_p(alpha_ptr), alpha_dtype, C.c_void_p(dalpha_ptr), C.c_float(scale),
                                              C.c_void_p(dscores_ptr), C.c_void_p(stream)), "libra_edge_softmax_backward")
+
+
+def libra_probe_coissue(iters: int, sink_ptr: int, stream: int = 0):
+    """(MFMA only, FMA only, both) in microseconds."""
+    t = (C.c_float * 3)()
+    _check(lib().libra_probe_coissue(iters, C.c_void_p(sink_ptr), C.byref(t), C.c_void_p(stream)), "libra_probe_coissue")
+    return tuple(float(x) for x in t)
 
 
 def libra_csr_transpose_workspace(nnz: int) -> int:

@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "liblibra.so")
-SOURCES = ["plan.cpp", "plan_gpu.hip", "kernels.hip"]
+SOURCES = ["plan.cpp", "plan_gpu.hip", "kernels.hip", "probe.hip"]
 
 
 def hipcc() -> str:

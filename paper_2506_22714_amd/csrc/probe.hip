@@ -1,0 +1,71 @@
+// Register-only probe of matrix-core / vector-ALU concurrency (the experiment of Section 3.1 of the paper, which
+// motivates running both units at once): the same workgroups run (a) MFMA chains on half of their waves, (b) FMA chains
+// on the other half, (c) both.  If the two units run side by side, (c) takes about max(a, b); if they exclude each
+// other, about a + b.  Nothing touches memory inside the loops.
+#include <hip/hip_runtime.h>
+
+#include "libra.h"
+
+namespace {
+
+typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
+typedef float float4_t __attribute__((ext_vector_type(4)));
+
+// 8 waves per workgroup = 2 per SIMD: waves 0..3 are the matrix-core waves, waves 4..7 the vector-ALU waves; each SIMD
+// gets one of each.  mode bit 0: matrix-core waves work; bit 1: vector-ALU waves work.
+__global__ __launch_bounds__(512) void coissue_kernel(int mode, int iters, float *sink) {
+    const int wave = threadIdx.x >> 6;
+    float result = 0.f;
+    if (wave < 4) {
+        if (mode & 1) {
+            const half4_t a = {(_Float16)1.0f, (_Float16)0.5f, (_Float16)0.25f, (_Float16)(threadIdx.x & 3)};
+            const half4_t b = {(_Float16)0.5f, (_Float16)1.0f, (_Float16)2.0f, (_Float16)(blockIdx.x & 1)};
+            float4_t acc[4] = {{0, 0, 0, 0}, {1, 1, 1, 1}, {2, 2, 2, 2}, {3, 3, 3, 3}};
+            for (int i = 0; i < iters; ++i) {
+#pragma unroll
+                for (int k = 0; k < 4; ++k) acc[k] = __builtin_amdgcn_mfma_f32_16x16x16f16(a, b, acc[k], 0, 0, 0);
+            }
+            result = acc[0][0] + acc[1][1] + acc[2][2] + acc[3][3];
+        }
+    } else if (mode & 2) {
+        float x[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) x[k] = (float)(threadIdx.x + k);
+        const float m = 1.0001f, c = 0.5f;
+        for (int i = 0; i < iters; ++i) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+#pragma unroll
+                for (int k = 0; k < 8; ++k) x[k] = fmaf(x[k], m, c);
+        }
+        result = x[0] + x[1] + x[2] + x[3] + x[4] + x[5] + x[6] + x[7];
+    }
+    if (result == 12345.678f) sink[0] = result;         // keeps the loops alive; practically never true
+}
+
+}  // namespace
+
+extern "C" int libra_probe_coissue(int iters, float *sink_dev, float times_us[3], void *stream) {
+    if (!sink_dev || !times_us) return LIBRA_ERR_NULL;
+    if (iters < 1 || iters > (1 << 24)) return LIBRA_ERR_SHAPE;
+    hipStream_t s = (hipStream_t)stream;
+    hipEvent_t e0, e1;
+    if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) return LIBRA_ERR_HIP;
+    int rc = LIBRA_OK;
+    for (int mode = 1; mode <= 3 && rc == LIBRA_OK; ++mode) {
+        float best = 1e30f;
+        for (int rep = 0; rep < 4; ++rep) {          // the first repetition warms up
+            hipEventRecord(e0, s);
+            hipLaunchKernelGGL(coissue_kernel, dim3(1024), dim3(512), 0, s, mode, iters, sink_dev);
+            hipEventRecord(e1, s);
+            if (hipEventSynchronize(e1) != hipSuccess || hipGetLastError() != hipSuccess) { rc = LIBRA_ERR_HIP; break; }
+            float ms = 0.f;
+            hipEventElapsedTime(&ms, e0, e1);
+            if (rep > 0 && ms < best) best = ms;
+        }
+        times_us[mode - 1] = best * 1e3f;
+    }
+    hipEventDestroy(e0);
+    hipEventDestroy(e1);
+    return rc;
+}

@@ -170,3 +170,12 @@ def test_attention_layers_train():
     print("losses", [round(x, 4) for x in losses], flush=True)
     assert losses[-1] < losses[0] - 0.02
     sm.close()
+
+
+def test_matrix_cores_and_vector_alus_run_side_by_side():
+    """Section 3.1 of the paper on this GPU: MFMA waves and FMA waves sharing the SIMDs overlap almost completely."""
+    sink = torch.zeros(4, dtype=torch.float32, device="cuda")
+    a, b, both = lb.libra_probe_coissue(20000, sink.data_ptr(), torch.cuda.current_stream().cuda_stream)
+    print(f"coissue probe: MFMA only {a:.1f} us, FMA only {b:.1f} us, both {both:.1f} us", flush=True)
+    assert a > 50 and b > 50
+    assert both < 0.8 * (a + b)            # far from exclusive
