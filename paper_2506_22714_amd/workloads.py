@@ -232,7 +232,7 @@ def with_long_rows(base: Csr, rows: list[int], length: int, seed: int) -> Csr:
 
 
 # ----------------------------------------------------------------------------
-# Named workloads (BASELINE configs) with a size knob for tests
+# Named workloads (the five benchmark configurations) with a size knob for tests
 # ----------------------------------------------------------------------------
 def make(name: str, small: bool = False) -> Csr:
     """``small`` gives a reduced instance with the same structure, sized so the
