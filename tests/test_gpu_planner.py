@@ -214,7 +214,7 @@ def test_device_planner_rejects_what_the_host_planner_rejects():
     p.close()
 
 
-@pytest.mark.parametrize("name", ["powerlaw", "community", "gat"])
+@pytest.mark.parametrize("name", ["powerlaw", "community", "gat", "irregular"])
 def test_device_planner_full_configs(name):
     A = wl.make(name)
     t0 = time.perf_counter()
