@@ -909,14 +909,12 @@ int spmm_launch(const libra_plan_t *P, const SpmmArgs &a, int n, int64_t nt, hip
         case 32: return launch_spmm<half_t, 32>(a, nt, s);
         case 64: return launch_spmm<half_t, 64>(a, nt, s);
         case 128: return launch_spmm<half_t, 128>(a, nt, s);
-        case 256: return launch_spmm<half_t, 256>(a, nt, s);
         }
     } else if (P->vdt == LIBRA_BF16) {
         switch (n) {
         case 32: return launch_spmm<bf16_t, 32>(a, nt, s);
         case 64: return launch_spmm<bf16_t, 64>(a, nt, s);
         case 128: return launch_spmm<bf16_t, 128>(a, nt, s);
-        case 256: return launch_spmm<bf16_t, 256>(a, nt, s);
         }
     } else {
         switch (n) {
@@ -924,7 +922,6 @@ int spmm_launch(const libra_plan_t *P, const SpmmArgs &a, int n, int64_t nt, hip
         case 32: return launch_spmm<float, 32>(a, nt, s);
         case 64: return launch_spmm<float, 64>(a, nt, s);
         case 128: return launch_spmm<float, 128>(a, nt, s);
-        case 256: return launch_spmm<float, 256>(a, nt, s);
         }
     }
     return LIBRA_ERR_UNSUPPORTED;
@@ -1164,9 +1161,10 @@ extern "C" int libra_spmm(const libra_plan_t *P, const void *B, int32_t N, int64
     if (((uintptr_t)B & 15) || ((uintptr_t)C & 15)) return LIBRA_ERR_BUFFER;
     hipStream_t s = (hipStream_t)stream;
     const int esz = P->vsize;
-    // the feature dimension is cut into pieces the kernels are instantiated for
+    // the feature dimension is cut into pieces the kernels are instantiated for; at most 128 columns, the widest
+    // piece whose tile leaves four waves per SIMD (a 256-column piece ran at two and took 2.5x the time of a 128-column one)
     for (int n0 = 0; n0 < N;) {
-        int n = 256;
+        int n = 128;
         while (n > N - n0) n >>= 1;
         int rc = spmm_piece(P, (const char *)B + (size_t)n0 * esz, n, ldb, C + n0, ldc, s);
         if (rc != LIBRA_OK) return rc;
