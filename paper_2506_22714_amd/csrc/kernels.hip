@@ -102,6 +102,26 @@ template <> struct Elem<half_t> {
         e.row = (uint16_t)(w >> 16);
         return e;
     }
+    // a batch of U consecutive entries from a 16-byte aligned address: U/2 16-byte LDS reads issued back to back, one wait;
+    // the words that hold {value, row} go through an opaque move afterwards so that each is read once, whole
+    template <int U>
+    __device__ static void lds_batch(const ent_t *lds, ent_t (&en)[U]) {
+        static_assert(U % 2 == 0, "two 8-byte entries per 16-byte read");
+        uint4 v[U / 2];
+#pragma unroll
+        for (int k = 0; k < U / 2; ++k) v[k] = reinterpret_cast<const uint4 *>(lds)[k];
+#pragma unroll
+        for (int k = 0; k < U / 2; ++k) {
+            uint32_t w0 = v[k].y, w1 = v[k].w;
+            asm volatile("" : "+v"(w0), "+v"(w1));
+            en[2 * k].col = (int32_t)v[k].x;
+            en[2 * k].val = (uint16_t)(w0 & 0xffffu);
+            en[2 * k].row = (uint16_t)(w0 >> 16);
+            en[2 * k + 1].col = (int32_t)v[k].z;
+            en[2 * k + 1].val = (uint16_t)(w1 & 0xffffu);
+            en[2 * k + 1].row = (uint16_t)(w1 >> 16);
+        }
+    }
     // the lane's 16 bytes of row `col`: one 32x32->64 multiply-add for the address
     __device__ static raw_t load_row(const void *base, int32_t col, uint32_t ld_bytes, int sub) {
         const char *p = reinterpret_cast<const char *>(base) + ((uint64_t)(uint32_t)col * ld_bytes + (uint32_t)sub * 16u);
@@ -171,6 +191,11 @@ template <> struct Elem<float> {
         e.row = __float_as_int(u[2]);
         e.pad = 0;
         return e;
+    }
+    template <int U>
+    __device__ static void lds_batch(const ent_t *lds, ent_t (&en)[U]) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) en[u] = lds_ent(lds, u);
     }
     __device__ static raw_t load_row(const void *base, int32_t col, uint32_t ld_bytes, int sub) {
         const char *p = reinterpret_cast<const char *>(base) + ((uint64_t)(uint32_t)col * ld_bytes + (uint32_t)sub * 16u);
@@ -493,10 +518,9 @@ __global__ __launch_bounds__(WAVE) void spmm_task_kernel(SpmmArgs a) {
             ent_t en[U];
             typename E::raw_t raw[U];
             const bool full = q + U <= q1;
-            // U consecutive entries from one base address; slots past the run hold valid entries whose fetch is
+            // U consecutive entries from one aligned base address; slots past the run hold valid entries whose fetch is
             // harmless and whose product is never formed
-#pragma unroll
-            for (int u = 0; u < U; ++u) en[u] = E::lds_ent(ent_lds + q, u);
+            E::template lds_batch<U>(ent_lds + q, en);
 #pragma unroll
             for (int u = 0; u < U; ++u) raw[u] = E::load_row(a.B, en[u].col, ldb_bytes, sub);
             bool one_row = full;
