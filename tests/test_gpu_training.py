@@ -138,38 +138,52 @@ def test_spmm_and_sddmm_gradients_match_the_formulas():
     sm.close()
 
 
-def test_attention_layers_train():
-    """A few optimiser steps of a two-layer attention network (SDDMM -> softmax -> SpMM per layer) on a synthetic graph:
-    the loss goes down, every gradient is finite.  The dense layers are torch matmuls (not part of the library)."""
+def train_layers(kind, n_layers, steps=12):
+    """Optimiser steps of an n-layer graph network on a synthetic power-law graph; returns the losses.  `gcn`: every layer
+    is SpMM with the fixed symmetric normalisation 1/sqrt(d_i d_j) (Section 5.5's GCN); `agnn`: every layer is SDDMM ->
+    edge softmax -> SpMM with learned attention (its AGNN); layers are residual.  The dense layers are torch matmuls (not part of the library)."""
     from paper_2506_22714_amd import autograd as ag
     torch.manual_seed(0)
     A = wl.make("powerlaw", small=True)
     sm = ag.SparseMatrix(A.M, A.Kc, dev(A.rowptr.astype(np.int32)), dev(A.col.astype(np.int32)))
     F = 32
     feats = dev(wl.dense_normal(A.M, F, seed=5)).float()
-    labels = torch.from_numpy(np.random.default_rng(6).integers(0, 4, size=A.M)).cuda()
-    W1 = (torch.randn(F, F, device="cuda") * 0.2).requires_grad_()
-    W2 = (torch.randn(F, F, device="cuda") * 0.2).requires_grad_()
+    labels = feats[:, :4].argmax(dim=1)           # a target the features determine; residual layers keep it reachable
+    Ws = [(torch.randn(F, F, device="cuda") * (0.2 if kind == "agnn" else 0.35)).requires_grad_() for _ in range(n_layers)]
     Wc = (torch.randn(F, 4, device="cuda") * 0.2).requires_grad_()
     ones = torch.ones(sm.nnz, dtype=torch.float16, device="cuda")
-    opt = torch.optim.Adam([W1, W2, Wc], lr=2e-2)
+    deg = np.maximum(np.diff(A.rowptr), 1).astype(np.float64)
+    rows = np.repeat(np.arange(A.M), np.diff(A.rowptr))
+    norm = dev((1.0 / np.sqrt(deg[rows] * deg[A.col])).astype(np.float16))
+    opt = torch.optim.Adam(Ws + [Wc], lr=2e-2)
     losses = []
-    for step in range(12):
+    for step in range(steps):
         h = feats
-        for Wl in (W1, W2):
+        for Wl in Ws:
             z = (h @ Wl).half()
-            scores = ag.sddmm(sm, ones, z, z)
-            alpha = ag.edge_softmax(sm, scores, 1.0 / np.sqrt(F))
-            h = torch.relu(ag.spmm(sm, alpha, z))
+            if kind == "agnn":
+                scores = ag.sddmm(sm, ones, z, z)
+                alpha = ag.edge_softmax(sm, scores, 1.0 / np.sqrt(F))
+                h = h + torch.relu(ag.spmm(sm, alpha, z))
+            else:
+                h = h + torch.relu(ag.spmm(sm, norm, z))
         loss = torch.nn.functional.cross_entropy(h @ Wc, labels)
         opt.zero_grad()
         loss.backward()
-        assert all(torch.isfinite(w.grad).all() for w in (W1, W2, Wc))
+        assert all(torch.isfinite(w.grad).all() for w in Ws + [Wc])
         opt.step()
         losses.append(float(loss.detach()))
-    print("losses", [round(x, 4) for x in losses], flush=True)
-    assert losses[-1] < losses[0] - 0.02
     sm.close()
+    return losses
+
+
+@pytest.mark.parametrize("kind,n_layers", [("agnn", 2), ("agnn", 5), ("gcn", 5)])
+def test_graph_networks_train(kind, n_layers):
+    """The end-to-end use of Section 5.5 (five-layer GCN and AGNN) on a synthetic graph: the loss goes down and every
+    gradient is finite."""
+    losses = train_layers(kind, n_layers)
+    print(kind, n_layers, "losses", [round(x, 4) for x in losses], flush=True)
+    assert losses[-1] < losses[0] - 0.02
 
 
 def test_matrix_cores_and_vector_alus_run_side_by_side():
