@@ -302,6 +302,17 @@ int libra_probe_coissue(int iters, float *sink_dev, float times_us[3], void *str
  */
 int libra_plan_set_values(libra_plan_t *plan, const void *vals_csr_dev, int dtype, void *stream);
 
+/*
+ * libra_plan_set_values_for - the same for the arrays of one operator only (`ops` = LIBRA_OP_SPMM, LIBRA_OP_SDDMM or
+ * both or-ed together).  An attention layer (SDDMM with A's pattern -> softmax -> SpMM with the new coefficients,
+ * Section 5.5) only needs the SpMM arrays refreshed; the other sub-plan then keeps its previous values, and what
+ * libra_sddmm computes with them is the caller's business.  Errors as above, plus OPTION for an `ops` without a known bit
+ * or with an unknown one.
+ */
+#define LIBRA_OP_SPMM  1
+#define LIBRA_OP_SDDMM 2
+int libra_plan_set_values_for(libra_plan_t *plan, const void *vals_csr_dev, int dtype, int ops, void *stream);
+
 /* Host views for checkers; pointers stay valid until libra_plan_destroy.  which: 0 = SpMM, 1 = SDDMM. */
 int libra_plan_export(const libra_plan_t *plan, int which, libra_subplan_view_t *view);
 int libra_plan_stats(const libra_plan_t *plan, libra_stats_t *stats);

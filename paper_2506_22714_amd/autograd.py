@@ -41,7 +41,7 @@ def _feature_ok(n: int) -> bool:
 class _SpMM(torch.autograd.Function):
     @staticmethod
     def forward(ctx, sm: SparseMatrix, vals: torch.Tensor, B: torch.Tensor):
-        sm.plan.set_values(vals.detach().contiguous())
+        sm.plan.set_values(vals.detach().contiguous(), lb.OP_SPMM)
         ctx.sm = sm
         ctx.save_for_backward(vals, B)
         return sm.plan.spmm(B.detach().contiguous())
@@ -53,7 +53,7 @@ class _SpMM(torch.autograd.Function):
         dC16 = dC.to(sm.dtype).contiguous()
         dvals = dB = None
         if ctx.needs_input_grad[2]:
-            sm.plan_t.set_values(vals.detach()[sm.perm_t].contiguous())
+            sm.plan_t.set_values(vals.detach()[sm.perm_t].contiguous(), lb.OP_SPMM)
             dB = sm.plan_t.spmm(dC16).to(B.dtype)
         if ctx.needs_input_grad[1]:
             if not _feature_ok(B.shape[1]):
@@ -65,7 +65,7 @@ class _SpMM(torch.autograd.Function):
 class _SDDMM(torch.autograd.Function):
     @staticmethod
     def forward(ctx, sm: SparseMatrix, vals: torch.Tensor, X: torch.Tensor, Y: torch.Tensor):
-        sm.plan.set_values(vals.detach().contiguous())
+        sm.plan.set_values(vals.detach().contiguous(), lb.OP_SDDMM)
         ctx.sm = sm
         ctx.save_for_backward(vals, X, Y)
         return sm.plan.sddmm(X.detach().contiguous(), Y.detach().contiguous())
@@ -78,10 +78,10 @@ class _SDDMM(torch.autograd.Function):
         g = (dout * vals.detach().float()).to(sm.dtype).contiguous()
         dvals = dX = dY = None
         if ctx.needs_input_grad[2]:
-            sm.plan.set_values(g)
+            sm.plan.set_values(g, lb.OP_SPMM)
             dX = sm.plan.spmm(Yc).to(X.dtype)
         if ctx.needs_input_grad[3]:
-            sm.plan_t.set_values(g[sm.perm_t].contiguous())
+            sm.plan_t.set_values(g[sm.perm_t].contiguous(), lb.OP_SPMM)
             dY = sm.plan_t.spmm(Xc).to(Y.dtype)
         if ctx.needs_input_grad[1]:
             dvals = (dout * sm.plan.sddmm(Xc, Yc, pattern_only=True)).to(vals.dtype)

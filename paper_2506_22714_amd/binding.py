@@ -22,6 +22,7 @@ MODE_HYBRID, MODE_DENSE_ONLY, MODE_SCALAR_ONLY = 0, 1, 2
 FLAG_NO_FILL_PADDING, FLAG_NO_SPMM, FLAG_NO_SDDMM, FLAG_NATURAL_ORDER, FLAG_XCD_ORDER, FLAG_NO_XCD_ORDER = 1, 2, 4, 8, 16, 32
 FLAG_SEGMENTS_BY_COLUMN, FLAG_TWO_KERNELS = 64, 128
 TASK_WINDOW, TASK_CHUNK = 0, 1
+OP_SPMM, OP_SDDMM = 1, 2
 OK = 0
 ERR = dict(NULL=-1, SHAPE=-2, ROWPTR=-3, COLUMN=-4, UNSORTED=-5, TOO_LARGE=-6, DTYPE=-7, OPTION=-8,
            UNSUPPORTED=-9, NOT_UPLOADED=-10, BUFFER=-11, NOT_BUILT=-12, HIP=-13, NOMEM=-14)
@@ -109,6 +110,7 @@ def lib() -> C.CDLL:
         L.libra_csr_transpose_workspace.argtypes = [i64, C.POINTER(sz)]
         L.libra_csr_transpose_device.argtypes = [i64, i64, i64, vp, vp, vp, vp, vp, vp, sz, vp]
         L.libra_plan_set_values.argtypes = [vp, vp, C.c_int, vp]
+        L.libra_plan_set_values_for.argtypes = [vp, vp, C.c_int, C.c_int, vp]
         L.libra_plan_export.argtypes = [vp, C.c_int, C.POINTER(SubplanView)]
         L.libra_plan_stats.argtypes = [vp, C.POINTER(Stats)]
         L.libra_plan_destroy.argtypes = [vp]
@@ -261,6 +263,11 @@ def libra_edge_softmax(plan, scores_ptr: int, scale: float, out_ptr: int, out_dt
 
 def libra_plan_set_values(plan, vals_ptr: int, dtype: int, stream: int = 0):
     _check(lib().libra_plan_set_values(plan, C.c_void_p(vals_ptr), dtype, C.c_void_p(stream)), "libra_plan_set_values")
+
+
+def libra_plan_set_values_for(plan, vals_ptr: int, dtype: int, ops: int, stream: int = 0):
+    _check(lib().libra_plan_set_values_for(plan, C.c_void_p(vals_ptr), dtype, ops, C.c_void_p(stream)),
+           "libra_plan_set_values_for")
 
 
 def libra_plan_destroy(plan):
@@ -420,7 +427,7 @@ class Plan:
                                     torch.cuda.current_stream().cuda_stream)
         return out
 
-    def set_values(self, vals):
+    def set_values(self, vals, ops: int = OP_SPMM | OP_SDDMM):
         import torch
         assert vals.is_cuda and vals.dtype == self._torch_dtype() and vals.is_contiguous() and vals.numel() == self.nnz
-        libra_plan_set_values(self.handle, vals.data_ptr(), self.val_dtype, torch.cuda.current_stream().cuda_stream)
+        libra_plan_set_values_for(self.handle, vals.data_ptr(), self.val_dtype, ops, torch.cuda.current_stream().cuda_stream)

@@ -1297,7 +1297,12 @@ extern "C" int libra_edge_softmax_backward(const libra_plan_t *P, const void *al
 }
 
 extern "C" int libra_plan_set_values(libra_plan_t *P, const void *vals, int dtype, void *stream) {
+    return libra_plan_set_values_for(P, vals, dtype, LIBRA_OP_SPMM | LIBRA_OP_SDDMM, stream);
+}
+
+extern "C" int libra_plan_set_values_for(libra_plan_t *P, const void *vals, int dtype, int ops, void *stream) {
     if (!P) return LIBRA_ERR_NULL;
+    if (!(ops & (LIBRA_OP_SPMM | LIBRA_OP_SDDMM)) || (ops & ~(LIBRA_OP_SPMM | LIBRA_OP_SDDMM))) return LIBRA_ERR_OPTION;
     if (!vals && P->nnz > 0) return LIBRA_ERR_NULL;
     if (dtype != P->vdt) return LIBRA_ERR_DTYPE;
     if (!P->dev_base) return LIBRA_ERR_NOT_UPLOADED;
@@ -1311,8 +1316,9 @@ extern "C" int libra_plan_set_values(libra_plan_t *P, const void *vals, int dtyp
         {sa.dev.res_perm, sa.dev.res_ent, sa.n.res, f16 ? (int)sizeof(ResEnt16) : (int)sizeof(ResEnt32), 4},
         {sd.dev.dense_perm, sd.dev.dense_pv, sd.n.dense, (int)sizeof(SdPv), 4},
         {sd.dev.res_perm, sd.dev.res_ent, sd.n.res, (int)sizeof(SdEnt), 12}};
-    for (const Seg &g : segs) {
-        if (g.n == 0) continue;
+    for (int k = 0; k < 4; ++k) {
+        const Seg &g = segs[k];
+        if (g.n == 0 || !(ops & (k < 2 ? LIBRA_OP_SPMM : LIBRA_OP_SDDMM))) continue;
         const unsigned blocks = (unsigned)std::min<int64_t>((g.n + 255) / 256, 1 << 16);
         if (f16)
             hipLaunchKernelGGL((scatter_values_kernel<uint16_t>), dim3(blocks), dim3(256), 0, s, (const uint16_t *)vals, g.perm, g.n, g.dst, g.stride, g.offset);

@@ -265,6 +265,28 @@ def test_unsupported_requests_return_codes():
 
 
 # ---------------------------------------------- softmax glue and new values
+def test_new_values_for_one_operator_leave_the_other_alone():
+    """Refreshing only the SpMM arrays (what an attention layer needs) changes libra_spmm and not libra_sddmm, and the
+    other way round; both against the oracle with the values each operator should see."""
+    A = wl.make("powerlaw", small=True)
+    N = K = 32
+    B, X, Y = wl.dense_normal(A.Kc, N, seed=31), wl.dense_normal(A.M, K, seed=32), wl.dense_normal(A.Kc, K, seed=33)
+    rng = np.random.default_rng(34)
+    v1, v2 = wl.uniform_values(rng, A.nnz), wl.uniform_values(rng, A.nnz)
+    p = lb.Plan.from_csr(A).upload()                     # both operators start from A.val
+    p.set_values(dev(v1), lb.OP_SPMM)
+    check_spmm(A, B, p.spmm(dev(B)).cpu().numpy(), TOL_F16, val=v1)
+    check_sddmm(A, X, Y, p.sddmm(dev(X), dev(Y)).cpu().numpy(), TOL_F16)
+    p.set_values(dev(v2), lb.OP_SDDMM)
+    check_spmm(A, B, p.spmm(dev(B)).cpu().numpy(), TOL_F16, val=v1)
+    check_sddmm(A, X, Y, p.sddmm(dev(X), dev(Y)).cpu().numpy(), TOL_F16, val=v2)
+    for bad in (0, 4, 7):
+        with pytest.raises(lb.LibraError) as e:
+            p.set_values(dev(v1), bad)
+        assert e.value.code == lb.ERR["OPTION"]
+    p.close()
+
+
 def test_edge_softmax_and_set_values_attention_head():
     A = wl.make("gat", small=True)
     K = 64
