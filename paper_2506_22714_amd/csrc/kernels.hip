@@ -793,49 +793,82 @@ __global__ __launch_bounds__(256) void edge_softmax_rows_kernel(const int32_t *r
     }
 }
 
-// Rows of 65 .. LIBRA_SOFTMAX_LONG_ROW nonzeros (listed at plan time): one wave per row.
-template <class TO>
-__global__ __launch_bounds__(256) void edge_softmax_medium_kernel(const int32_t *rowptr, const int32_t *rows, int nrows, const float *score, float scale, TO *out) {
-    const int lane = threadIdx.x & 63;
-    const int w = (blockIdx.x * blockDim.x + threadIdx.x) >> 6;
-    if (w >= nrows) return;
-    const int64_t i = rows[w];
-    const int s = rowptr[i], n = rowptr[i + 1] - s;
-    float mx = -INFINITY;
-    for (int q = lane; q < n; q += WAVE) mx = fmaxf(mx, scale * score[s + q]);
+// Rows listed at plan time: 65 .. LIBRA_SOFTMAX_LONG_ROW nonzeros, one wave per row (THREADS = 64, four rows per
+// workgroup), and longer ones, one 256-thread workgroup per row.  A thread takes UNR scores per round, all loads in flight
+// together; the row's maximum and denominator come from one pass (running maximum, sum rescaled when it grows); the second
+// pass writes, from the registers if the whole row fitted one round and from a second read (cache) otherwise.
+template <int THREADS>
+__device__ inline float list_sum(float x, float *red) {
 #pragma unroll
-    for (int m = 1; m < WAVE; m <<= 1) mx = fmaxf(mx, __shfl_xor(mx, m, WAVE));
-    float den = 0.f;
-    for (int q = lane; q < n; q += WAVE) den += __expf(scale * score[s + q] - mx);
+    for (int m = 1; m < WAVE; m <<= 1) x += __shfl_xor(x, m, WAVE);
+    if constexpr (THREADS > WAVE) {
+        __syncthreads();                // earlier readers of `red` are done
+        if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = x;
+        __syncthreads();
+        x = 0.f;
 #pragma unroll
-    for (int m = 1; m < WAVE; m <<= 1) den += __shfl_xor(den, m, WAVE);
-    const float inv = 1.f / den;
-    for (int q = lane; q < n; q += WAVE) out[s + q] = to_storage<TO>(__expf(scale * score[s + q] - mx) * inv);
+        for (int w = 0; w < THREADS / WAVE; ++w) x += red[w];
+    }
+    return x;
+}
+template <int THREADS>
+__device__ inline float list_max(float x, float *red) {
+#pragma unroll
+    for (int m = 1; m < WAVE; m <<= 1) x = fmaxf(x, __shfl_xor(x, m, WAVE));
+    if constexpr (THREADS > WAVE) {
+        __syncthreads();
+        if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = x;
+        __syncthreads();
+        x = red[0];
+#pragma unroll
+        for (int w = 1; w < THREADS / WAVE; ++w) x = fmaxf(x, red[w]);
+    }
+    return x;
 }
 
-// Long rows (listed at plan time): one 256-thread workgroup per row.
-template <class TO>
-__global__ __launch_bounds__(256) void edge_softmax_long_kernel(const int32_t *rowptr, const int32_t *rows, const float *score, float scale, TO *out) {
+template <class TO, int THREADS, int UNR>
+__global__ __launch_bounds__(256) void edge_softmax_list_kernel(const int32_t *rowptr, const int32_t *rows, int nrows, const float *score, float scale, TO *out) {
     __shared__ float red[4];
-    const int64_t i = rows[blockIdx.x];
+    const int tid = THREADS == WAVE ? (int)(threadIdx.x & 63) : (int)threadIdx.x;
+    const int w = THREADS == WAVE ? (int)((blockIdx.x * blockDim.x + threadIdx.x) >> 6) : (int)blockIdx.x;
+    if (w >= nrows) return;             // whole waves (THREADS == WAVE) or whole workgroups leave together
+    const int64_t i = rows[w];
     const int s = rowptr[i], n = rowptr[i + 1] - s;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    float mx = -INFINITY;
-    for (int q = tid; q < n; q += 256) mx = fmaxf(mx, scale * score[s + q]);
+    const float *sc = score + s;
+    float v[UNR];
+    auto fetch = [&](int q0) {          // clamped addresses, padding becomes -inf afterwards
 #pragma unroll
-    for (int m = 1; m < WAVE; m <<= 1) mx = fmaxf(mx, __shfl_xor(mx, m, WAVE));
-    if (lane == 0) red[wave] = mx;
-    __syncthreads();
-    mx = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
-    __syncthreads();
-    float den = 0.f;
-    for (int q = tid; q < n; q += 256) den += __expf(scale * score[s + q] - mx);
+        for (int u = 0; u < UNR; ++u) v[u] = sc[min(q0 + u * THREADS + tid, n - 1)];
 #pragma unroll
-    for (int m = 1; m < WAVE; m <<= 1) den += __shfl_xor(den, m, WAVE);
-    if (lane == 0) red[wave] = den;
-    __syncthreads();
-    const float inv = 1.f / (red[0] + red[1] + red[2] + red[3]);
-    for (int q = tid; q < n; q += 256) out[s + q] = to_storage<TO>(__expf(scale * score[s + q] - mx) * inv);
+        for (int u = 0; u < UNR; ++u) v[u] = q0 + u * THREADS + tid < n ? scale * v[u] : -INFINITY;
+    };
+    float m = -INFINITY, d = 0.f;
+    for (int q0 = 0; q0 < n; q0 += THREADS * UNR) {
+        fetch(q0);
+        float bm = v[0];
+#pragma unroll
+        for (int u = 1; u < UNR; ++u) bm = fmaxf(bm, v[u]);
+        const float nm = fmaxf(m, bm);
+        if (nm > -INFINITY) {           // this thread has seen a score
+            float acc = 0.f;
+#pragma unroll
+            for (int u = 0; u < UNR; ++u) acc += __expf(v[u] - nm);
+            d = d * __expf(m - nm) + acc;       // m = -inf: d is 0 and exp(-inf) = 0
+            m = nm;
+        }
+    }
+    const float mx = list_max<THREADS>(m, red);
+    const float den = list_sum<THREADS>(m > -INFINITY ? d * __expf(m - mx) : 0.f, red);
+    const float inv = 1.f / den;
+    const bool in_registers = n <= THREADS * UNR;
+    for (int q0 = 0; q0 < n; q0 += THREADS * UNR) {
+        if (!in_registers) fetch(q0);
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) {
+            const int q = q0 + u * THREADS + tid;
+            if (q < n) out[s + q] = to_storage<TO>(__expf(v[u] - mx) * inv);
+        }
+    }
 }
 
 // Backward of the edge softmax: dscore_p = scale * alpha_p * (dalpha_p - sum_row alpha_q dalpha_q).  Same three row
@@ -866,26 +899,44 @@ __global__ __launch_bounds__(256) void edge_softmax_bwd_rows_kernel(const int32_
     }
 }
 
-// one wave per listed row (65 .. LIBRA_SOFTMAX_LONG_ROW nonzeros), or one 256-thread workgroup per listed long row
-template <class TA, int THREADS>
+// one wave per listed row (65 .. LIBRA_SOFTMAX_LONG_ROW nonzeros), or one 256-thread workgroup per listed long row;
+// UNR pairs per thread and round, as in the forward kernel
+template <class TA, int THREADS, int UNR>
 __global__ __launch_bounds__(256) void edge_softmax_bwd_list_kernel(const int32_t *rowptr, const int32_t *rows, int nrows, const TA *alpha, const float *dalpha, float scale, float *dscore) {
     __shared__ float red[4];
-    const int lane = threadIdx.x & 63;
-    const int tid = THREADS == WAVE ? lane : (int)threadIdx.x;
+    const int tid = THREADS == WAVE ? (int)(threadIdx.x & 63) : (int)threadIdx.x;
     const int w = THREADS == WAVE ? (int)((blockIdx.x * blockDim.x + threadIdx.x) >> 6) : (int)blockIdx.x;
     if (w >= nrows) return;             // whole waves (THREADS == WAVE) or whole workgroups leave together
     const int64_t i = rows[w];
     const int s = rowptr[i], n = rowptr[i + 1] - s;
-    float dot = 0.f;
-    for (int q = tid; q < n; q += THREADS) dot += from_storage<TA>(alpha[s + q]) * dalpha[s + q];
+    float a[UNR], g[UNR];
+    auto fetch = [&](int q0) {          // clamped addresses; padding contributes zero
+        TA ar[UNR];
 #pragma unroll
-    for (int m = 1; m < WAVE; m <<= 1) dot += __shfl_xor(dot, m, WAVE);
-    if (THREADS > WAVE) {
-        if (lane == 0) red[threadIdx.x >> 6] = dot;
-        __syncthreads();
-        dot = red[0] + red[1] + red[2] + red[3];
+        for (int u = 0; u < UNR; ++u) {
+            const int q = min(q0 + u * THREADS + tid, n - 1);
+            ar[u] = alpha[s + q];
+            g[u] = dalpha[s + q];
+        }
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) a[u] = q0 + u * THREADS + tid < n ? from_storage<TA>(ar[u]) : 0.f;
+    };
+    float dot = 0.f;
+    for (int q0 = 0; q0 < n; q0 += THREADS * UNR) {
+        fetch(q0);
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) dot += a[u] * g[u];
     }
-    for (int q = tid; q < n; q += THREADS) dscore[s + q] = scale * from_storage<TA>(alpha[s + q]) * (dalpha[s + q] - dot);
+    dot = list_sum<THREADS>(dot, red);
+    const bool in_registers = n <= THREADS * UNR;
+    for (int q0 = 0; q0 < n; q0 += THREADS * UNR) {
+        if (!in_registers) fetch(q0);
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) {
+            const int q = q0 + u * THREADS + tid;
+            if (q < n) dscore[s + q] = scale * a[u] * (g[u] - dot);
+        }
+    }
 }
 
 // dst[i * stride + offset] (as T) = src[perm[i]]: new values into a packed array or into entry records
@@ -1264,8 +1315,8 @@ extern "C" int libra_edge_softmax(const libra_plan_t *P, const float *scores, fl
         typedef decltype(tag) TO;
         TO *o = reinterpret_cast<TO *>(vals_out);
         hipLaunchKernelGGL((edge_softmax_rows_kernel<TO>), dim3(blocks), dim3(256), 0, s, P->d_rowptr, P->M, scores, scale, o);
-        if (nmed) hipLaunchKernelGGL((edge_softmax_medium_kernel<TO>), dim3((nmed + 3) / 4), dim3(256), 0, s, P->d_rowptr, P->d_medium_rows, (int)nmed, scores, scale, o);
-        if (nlong) hipLaunchKernelGGL((edge_softmax_long_kernel<TO>), dim3(nlong), dim3(256), 0, s, P->d_rowptr, P->d_long_rows, scores, scale, o);
+        if (nmed) hipLaunchKernelGGL((edge_softmax_list_kernel<TO, WAVE, 8>), dim3((nmed + 3) / 4), dim3(256), 0, s, P->d_rowptr, P->d_medium_rows, (int)nmed, scores, scale, o);
+        if (nlong) hipLaunchKernelGGL((edge_softmax_list_kernel<TO, 256, 16>), dim3(nlong), dim3(256), 0, s, P->d_rowptr, P->d_long_rows, (int)nlong, scores, scale, o);
     };
     if (out_dtype == LIBRA_F16) run(half_t{});
     else if (out_dtype == LIBRA_BF16) run(bf16_t{});
@@ -1287,8 +1338,8 @@ extern "C" int libra_edge_softmax_backward(const libra_plan_t *P, const void *al
         typedef decltype(tag) TA;
         const TA *a = reinterpret_cast<const TA *>(alpha);
         hipLaunchKernelGGL((edge_softmax_bwd_rows_kernel<TA>), dim3(blocks), dim3(256), 0, s, P->d_rowptr, P->M, a, dalpha, scale, dscores);
-        if (nmed) hipLaunchKernelGGL((edge_softmax_bwd_list_kernel<TA, WAVE>), dim3((nmed + 3) / 4), dim3(256), 0, s, P->d_rowptr, P->d_medium_rows, (int)nmed, a, dalpha, scale, dscores);
-        if (nlong) hipLaunchKernelGGL((edge_softmax_bwd_list_kernel<TA, 256>), dim3(nlong), dim3(256), 0, s, P->d_rowptr, P->d_long_rows, (int)nlong, a, dalpha, scale, dscores);
+        if (nmed) hipLaunchKernelGGL((edge_softmax_bwd_list_kernel<TA, WAVE, 8>), dim3((nmed + 3) / 4), dim3(256), 0, s, P->d_rowptr, P->d_medium_rows, (int)nmed, a, dalpha, scale, dscores);
+        if (nlong) hipLaunchKernelGGL((edge_softmax_bwd_list_kernel<TA, 256, 8>), dim3(nlong), dim3(256), 0, s, P->d_rowptr, P->d_long_rows, (int)nlong, a, dalpha, scale, dscores);
     };
     if (alpha_dtype == LIBRA_F16) run(half_t{});
     else if (alpha_dtype == LIBRA_BF16) run(bf16_t{});
