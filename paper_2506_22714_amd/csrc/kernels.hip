@@ -712,14 +712,26 @@ __device__ inline void sddmm_segment_task(const SddmmArgs &a, const DevTask &t) 
     constexpr int LPN = K / PL;              // lanes per nonzero
     constexpr int NPW = WAVE / LPN;          // nonzeros per wave pass
     constexpr int U = LPN <= 8 ? 8 : 4;      // passes in flight
-    static_assert(LPN >= 1 && LPN <= WAVE, "unsupported K");
+    static_assert(LPN >= 4 && LPN % 4 == 0 && LPN <= WAVE, "unsupported K (whole quads per nonzero)");
     const int lane = threadIdx.x;
     const int sub = lane % LPN, grp = lane / LPN;
     for (int q0 = t.res_begin; q0 < t.res_end; q0 += NPW * U) {
-        uint4 ent[U];                        // row, col, position, value bits
+        // An entry is 4 words (row, col, position, value bits).  Each lane of a quad fetches one of them (a quad then
+        // costs the texture path 16 bytes instead of 64) and the quad shares them with DPP moves.
+        uint32_t word[U];
+        uint4 ent[U];
         typename E::raw_t x[U], y[U];
 #pragma unroll
-        for (int u = 0; u < U; ++u) ent[u] = reinterpret_cast<const uint4 *>(a.res_ent)[min(q0 + u * NPW + grp, t.res_end - 1)];
+        for (int u = 0; u < U; ++u)
+            word[u] = reinterpret_cast<const uint32_t *>(a.res_ent)[(int64_t)min(q0 + u * NPW + grp, t.res_end - 1) * 4 + (sub & 3)];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int w = (int)word[u];
+            ent[u].x = (uint32_t)__builtin_amdgcn_update_dpp(0, w, 0x00, 0xf, 0xf, true);      // quad_perm [0,0,0,0]
+            ent[u].y = (uint32_t)__builtin_amdgcn_update_dpp(0, w, 0x55, 0xf, 0xf, true);      // quad_perm [1,1,1,1]
+            ent[u].z = (uint32_t)__builtin_amdgcn_update_dpp(0, w, 0xAA, 0xf, 0xf, true);      // quad_perm [2,2,2,2]
+            ent[u].w = (uint32_t)__builtin_amdgcn_update_dpp(0, w, 0xFF, 0xf, 0xf, true);      // quad_perm [3,3,3,3]
+        }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             x[u] = E::load(a.X, (int64_t)(int32_t)ent[u].x * K + sub * PL);
