@@ -287,6 +287,41 @@ def test_new_values_for_one_operator_leave_the_other_alone():
     p.close()
 
 
+def test_edge_softmax_at_every_row_length_class_boundary():
+    """Rows of exactly the lengths at which the softmax kernels change shape (16 lanes per row up to 64 nonzeros; one wave,
+    512 scores per round, up to 2048; one workgroup, 4096 per round, beyond), with scores that grow along the row so that
+    the running maximum is replaced in every round.  Forward against the oracle, backward against the textbook formula."""
+    lengths = [0, 1, 2, 15, 16, 17, 63, 64, 65, 127, 511, 512, 513, 1023, 1025, 2047, 2048, 2049, 4095, 4096, 4097, 8191, 8193, 12001]
+    Kc = 16384
+    rng = np.random.default_rng(77)
+    cols = [np.sort(rng.choice(Kc, size=n, replace=False)).astype(np.int32) for n in lengths]
+    rowptr = np.zeros(len(lengths) + 1, dtype=np.int32)
+    np.cumsum(lengths, out=rowptr[1:])
+    A = wl.Csr(len(lengths), Kc, rowptr, np.concatenate(cols).astype(np.int32), np.ones(int(rowptr[-1]), dtype=np.float16))
+    rows = np.repeat(np.arange(A.M), lengths)
+    pos = np.arange(A.nnz) - rowptr[rows]
+    scores = (20.0 * pos / np.maximum(np.asarray(lengths)[rows] - 1, 1) - 10.0 + rng.standard_normal(A.nnz)).astype(np.float32)
+    dalpha = rng.standard_normal(A.nnz).astype(np.float32)
+    scale = 1.3
+    p = lb.Plan.from_csr(A).upload()
+    ref = oracle.edge_softmax(A.rowptr, scores.astype(np.float64), scale)
+    a32 = p.edge_softmax(dev(scores), scale, out=torch.empty(A.nnz, dtype=torch.float32, device="cuda"))
+    got = a32.cpu().numpy().astype(np.float64)
+    # fp32 exponentials of arguments down to -26 against a double reference: relative error of exp and of the sum
+    assert np.max(np.abs(got - ref) / ref) < 2e-5
+    sums = np.bincount(rows, weights=got, minlength=A.M)
+    assert np.all(np.abs(sums[np.asarray(lengths) > 0] - 1.0) < 1e-5)
+    a16 = p.edge_softmax(dev(scores), scale).cpu().numpy().astype(np.float64)
+    assert np.max(np.abs(a16 - ref) / np.maximum(ref, 2.0 ** -14)) < 1e-3
+    ds = p.edge_softmax_backward(a32, dev(dalpha), scale).cpu().numpy().astype(np.float64)
+    dot = np.bincount(rows, weights=got * dalpha, minlength=A.M)
+    sabs = np.bincount(rows, weights=np.abs(got * dalpha), minlength=A.M)
+    want = scale * got * (dalpha - dot[rows])
+    tol = 32 * np.sqrt(max(lengths)) * 2.0 ** -24
+    assert np.max(np.abs(ds - want) / (scale * got * (np.abs(dalpha) + sabs[rows]) + 1e-30)) <= tol
+    p.close()
+
+
 def test_edge_softmax_and_set_values_attention_head():
     A = wl.make("gat", small=True)
     K = 64
