@@ -60,7 +60,7 @@ def main() -> int:
     ap.add_argument("--natural-order", action="store_true")
     ap.add_argument("--xcd-order", action="store_true", help="group tasks of neighbouring windows on one accelerator die")
     ap.add_argument("--no-xcd-order", action="store_true", help="never do that (default: the planner decides from the matrix)")
-    ap.add_argument("--segments-by-column", action="store_true", help="row segments placed on the dies by column range")
+    ap.add_argument("--segments-by-cost", action="store_true", help="row segments in heaviest-first order instead of one column range per die")
     ap.add_argument("--two-kernels", action="store_true", help="SpMM as two launches (dense blocks, then residual nonzeros)")
     ap.add_argument("--host-plan", action="store_true",
                     help="run the compute calls on the host-built, uploaded plan (default: on the plan the device planner "
@@ -106,7 +106,7 @@ def main() -> int:
     val = wl.to_bf16_bits(A.val.astype(np.float32)) if bf16 else None
     opts = dict(mode=args.mode, spmm_min_vec_nnz=args.tau_spmm, sddmm_min_blk_nnz=args.tau_sddmm, ts=args.ts, cs=args.cs,
                 flags=(lb.FLAG_NATURAL_ORDER if args.natural_order else 0) | (lb.FLAG_XCD_ORDER if args.xcd_order else 0)
-                | (lb.FLAG_NO_XCD_ORDER if args.no_xcd_order else 0) | (lb.FLAG_SEGMENTS_BY_COLUMN if args.segments_by_column else 0)
+                | (lb.FLAG_NO_XCD_ORDER if args.no_xcd_order else 0) | (lb.FLAG_SEGMENTS_BY_COST if args.segments_by_cost else 0)
                 | (lb.FLAG_TWO_KERNELS if args.two_kernels else 0))
     # the plan is built once per matrix, outside the timed region, by both planners: on the host (+ upload) and on the
     # device (the plan's device copy written directly, no host copy kept)
@@ -212,7 +212,7 @@ def main() -> int:
     achieved = bytes_spmm / spmm_avg_s / 1e9
     default_cfg = (not args.small and not bf16 and args.mode == 0 and not (args.tau_spmm or args.tau_sddmm or args.ts or args.cs)
                    and not args.natural_order and not args.xcd_order and not args.no_xcd_order
-                   and not args.segments_by_column and not args.two_kernels)
+                   and not args.segments_by_cost and not args.two_kernels)
     traffic = MEASURED_TRAFFIC_BYTES.get((args.workload, N)) if default_cfg else None
 
     out = {

@@ -73,15 +73,18 @@ extern "C" {
                                            task table then holds a few empty tasks (no work).  Without this flag and the
                                            next one the planner decides from the sampled neighbour_share statistic */
 #define LIBRA_FLAG_NO_XCD_ORDER    32u  /* never use the die-aware order */
-#define LIBRA_FLAG_SEGMENTS_BY_COLUMN 64u /* SpMM, when the die-aware order is not in use: the segments of decomposed rows
-                                           are sorted by their first column and cut into one run per die, so that a
-                                           die fetches dense-operand rows of one column range only.  Cuts the traffic
-                                           behind the L2 (power-law config: 283 -> 211 MB fetched per call) but not the
-                                           time (73.6 vs 71.8 us), hence off by default */
+#define LIBRA_FLAG_SEGMENTS_BY_COLUMN 64u /* accepted, and what the planner does anyway (kept so that callers that ask for it
+                                           still work): when the die-aware order is not in use, the segments of decomposed
+                                           rows are sorted by their first column and cut into one run per die, so that a
+                                           die fetches dense-operand rows of one column range only and its L2 holds eight
+                                           times as many distinct hot rows.  SpMM on this machine: GAT graph 868 -> 644 us,
+                                           irregular graph 2.29 -> 1.95 ms, power-law config 72.6 -> 71.5 us */
 #define LIBRA_FLAG_TWO_KERNELS    128u  /* libra_spmm runs the task table twice on the stream: first the dense blocks (MFMA), then the
                                            residual nonzeros (VALU), which add to what the first launch wrote - the paper's
                                            sequential schedule of its two kernels (Section 4.4.1).  Same results up to the order
                                            of additions; for debugging and as the baseline the fused task is measured against */
+
+#define LIBRA_FLAG_SEGMENTS_BY_COST 256u /* leave the segments of decomposed rows where the heaviest-first order puts them */
 
 typedef struct libra_plan_s libra_plan_t;   /* opaque; immutable after libra_plan() except for its values */
 

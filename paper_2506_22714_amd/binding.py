@@ -20,7 +20,7 @@ LIB_PATH = os.environ.get("LIBRA_LIBRARY") or os.path.join(_HERE, "liblibra.so")
 F16, BF16, F32 = 0, 1, 2
 MODE_HYBRID, MODE_DENSE_ONLY, MODE_SCALAR_ONLY = 0, 1, 2
 FLAG_NO_FILL_PADDING, FLAG_NO_SPMM, FLAG_NO_SDDMM, FLAG_NATURAL_ORDER, FLAG_XCD_ORDER, FLAG_NO_XCD_ORDER = 1, 2, 4, 8, 16, 32
-FLAG_SEGMENTS_BY_COLUMN, FLAG_TWO_KERNELS = 64, 128
+FLAG_SEGMENTS_BY_COLUMN, FLAG_TWO_KERNELS, FLAG_SEGMENTS_BY_COST = 64, 128, 256
 TASK_WINDOW, TASK_CHUNK = 0, 1
 OP_SPMM, OP_SDDMM = 1, 2
 OK = 0

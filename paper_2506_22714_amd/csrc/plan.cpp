@@ -451,9 +451,10 @@ int libra::resolve_options(const libra_plan_opts_t *in, int vdt, Resolved &o) {
     o.heavy_first = !(z.flags & LIBRA_FLAG_NATURAL_ORDER);
     if ((z.flags & LIBRA_FLAG_XCD_ORDER) && (z.flags & LIBRA_FLAG_NO_XCD_ORDER)) return LIBRA_ERR_OPTION;
     o.xcd_order = !o.heavy_first || (z.flags & LIBRA_FLAG_NO_XCD_ORDER) ? 0 : (z.flags & LIBRA_FLAG_XCD_ORDER) ? 1 : -1;
-    o.segments_by_column = o.heavy_first && (z.flags & LIBRA_FLAG_SEGMENTS_BY_COLUMN);
+    if ((z.flags & LIBRA_FLAG_SEGMENTS_BY_COLUMN) && (z.flags & LIBRA_FLAG_SEGMENTS_BY_COST)) return LIBRA_ERR_OPTION;
+    o.segments_by_column = o.heavy_first && !(z.flags & LIBRA_FLAG_SEGMENTS_BY_COST);
     o.two_kernels = (z.flags & LIBRA_FLAG_TWO_KERNELS) != 0;
-    if (z.flags & ~255u) return LIBRA_ERR_OPTION;
+    if (z.flags & ~511u) return LIBRA_ERR_OPTION;
     return LIBRA_OK;
 }
 

@@ -98,7 +98,7 @@ def test_device_planner_random_options():
             A = wl.with_long_rows(A, [M // 2], min(Kc, 200), seed=it)
         kw = dict(mode=int(rng.integers(0, 3)), spmm_min_vec_nnz=int(rng.integers(1, 8)), sddmm_min_blk_nnz=int(rng.integers(1, 80)),
                   ts=int(rng.integers(1, 6)), cs=int(rng.integers(1, 40)), short_len=int(rng.integers(1, 5)),
-                  sddmm_cs=int(rng.integers(1, 60)), flags=int(rng.choice([0, 1, 8, 9, 16, 32])))
+                  sddmm_cs=int(rng.integers(1, 60)), flags=int(rng.choice([0, 1, 8, 9, 16, 32, 256, 288])))
         print("random case", it, M, Kc, A.nnz, kw, flush=True)
         ph = lb.Plan.from_csr(A, **kw)
         pd = device_plan(A, **kw)

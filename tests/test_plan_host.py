@@ -186,8 +186,9 @@ def test_planner_matches_reference_bit_for_bit(case):
 
 def test_plan_does_not_depend_on_thread_count_and_orders_heaviest_first():
     A = wl.rmat(scale=11, avg_degree=8, seed=4)
-    e1 = lb.Plan.from_csr(A, threads=1, cs=16, ts=2, flags=lb.FLAG_NO_XCD_ORDER).export(0)
-    e7 = lb.Plan.from_csr(A, threads=7, cs=16, ts=2, flags=lb.FLAG_NO_XCD_ORDER).export(0)
+    plain = lb.FLAG_NO_XCD_ORDER | lb.FLAG_SEGMENTS_BY_COST
+    e1 = lb.Plan.from_csr(A, threads=1, cs=16, ts=2, flags=plain).export(0)
+    e7 = lb.Plan.from_csr(A, threads=7, cs=16, ts=2, flags=plain).export(0)
     for k in e1:
         assert np.array_equal(e1[k], e7[k]), k
     a1, a7 = (lb.Plan.from_csr(A, threads=t, cs=16, ts=2).export(0) for t in (1, 7))       # order decided from the matrix
@@ -249,8 +250,10 @@ def test_xcd_order_keeps_the_tasks_and_puts_neighbouring_windows_on_one_die():
 
 def test_segments_by_column_keeps_the_tasks_and_gives_each_die_one_column_range():
     A = wl.rmat(scale=12, avg_degree=24, seed=6)
-    base = lb.Plan.from_csr(A, cs=16, flags=lb.FLAG_NO_XCD_ORDER)
-    plan = lb.Plan.from_csr(A, cs=16, flags=lb.FLAG_NO_XCD_ORDER | lb.FLAG_SEGMENTS_BY_COLUMN)
+    base = lb.Plan.from_csr(A, cs=16, flags=lb.FLAG_NO_XCD_ORDER | lb.FLAG_SEGMENTS_BY_COST)
+    plan = lb.Plan.from_csr(A, cs=16, flags=lb.FLAG_NO_XCD_ORDER)
+    asked = lb.Plan.from_csr(A, cs=16, flags=lb.FLAG_NO_XCD_ORDER | lb.FLAG_SEGMENTS_BY_COLUMN)
+    assert np.array_equal(asked.export(0)["tasks"], plan.export(0)["tasks"])          # the flag names the default
     ex = plan.export(0)
     t = ex["tasks"]
     assert canon_tasks(t) == canon_tasks(base.export(0)["tasks"])
