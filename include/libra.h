@@ -77,8 +77,10 @@ extern "C" {
                                            still work): when the die-aware order is not in use, the segments of decomposed
                                            rows are sorted by their first column and cut into one run per die, so that a
                                            die fetches dense-operand rows of one column range only and its L2 holds eight
-                                           times as many distinct hot rows.  SpMM on this machine: GAT graph 868 -> 644 us,
-                                           irregular graph 2.29 -> 1.95 ms, power-law config 72.6 -> 71.5 us */
+                                           times as many distinct hot rows; the flat SDDMM segments that lie inside one row are
+                                           placed the same way.  On this box: GAT graph SpMM 868 -> 644 us, SDDMM 1.02 -> 0.80 ms;
+                                           irregular graph 2.29 -> 1.95 ms and 2.37 -> 1.95 ms; power-law config 72.6 -> 71.4 us
+                                           and 32.1 -> 30.7 us */
 #define LIBRA_FLAG_TWO_KERNELS    128u  /* libra_spmm runs the task table twice on the stream: first the dense blocks (MFMA), then the
                                            residual nonzeros (VALU), which add to what the first launch wrote - the paper's
                                            sequential schedule of its two kernels (Section 4.4.1).  Same results up to the order

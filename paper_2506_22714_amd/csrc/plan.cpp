@@ -397,6 +397,22 @@ void place_segments_by_column(std::vector<libra_task_t> &tasks, const std::vecto
     interleave_queues(tasks, 0, n, queue, LIBRA_TASK_WINDOW);
 }
 
+// The same for the flat residual segments of the SDDMM table (tasks[begin, end), in CSR order): a segment that lies inside
+// one row is a run of ascending columns, i.e. it gathers rows of the second dense operand from a narrow column range.
+// Those segments are sorted by first column and cut into LIBRA_XCDS equal runs, one per die; the others (several short
+// rows each, columns from everywhere) are dealt round-robin as before and follow them in each die's queue.
+void place_sddmm_segments_by_column(std::vector<libra_task_t> &tasks, size_t begin, size_t end, const std::vector<int32_t> &seg_col) {
+    const size_t n = end - begin;
+    std::vector<size_t> placed, other;
+    for (size_t i = 0; i < n; ++i) (seg_col.at(i) >= 0 ? placed : other).push_back(i);
+    if (placed.size() < 8 * LIBRA_XCDS) return;
+    std::stable_sort(placed.begin(), placed.end(), [&](size_t a, size_t b) { return seg_col[a] < seg_col[b]; });
+    std::vector<size_t> queue[LIBRA_XCDS];
+    for (size_t r = 0; r < placed.size(); ++r) queue[r * LIBRA_XCDS / placed.size()].push_back(placed[r]);
+    for (size_t r = 0; r < other.size(); ++r) queue[r % LIBRA_XCDS].push_back(other[r]);
+    interleave_queues(tasks, begin, end, queue, LIBRA_TASK_CHUNK);
+}
+
 // How much neighbouring windows overlap in the columns they reference, on an evenly spaced sample of groups of
 // LIBRA_LOCALITY_WINDOWS windows: distinct columns of the group / sum of the distinct columns of its windows.
 double neighbour_share(int64_t M, const int32_t *rowptr, const ColumnFetch &cols, int W) {
@@ -482,9 +498,13 @@ void libra::finish_plan(libra_plan_t *P, const ColumnFetch &cols, const int64_t 
     if (o.build_sddmm) {
         // scalar segments over the flat residual list (no atomics needed: each output has one writer)
         const int32_t nres = (int32_t)sd.n.res;
+        const size_t nseg = ((size_t)nres + o.sddmm_Cs - 1) / o.sddmm_Cs;
+        const bool derive = sd.seg_col.size() != nseg && P->host_arrays;
+        if (sd.seg_col.size() != nseg) sd.seg_col.assign(nseg, -1);
         for (int32_t q = 0; q < nres; q += o.sddmm_Cs) {
             int32_t q1 = std::min(nres, q + o.sddmm_Cs);
             sd.tasks.push_back({LIBRA_TASK_CHUNK, 0, 0, 0, q, q1, 0u, 0u, 0u, (uint32_t)(2 * (q1 - q))});
+            if (derive && sd.res_row[q] == sd.res_row[q1 - 1]) sd.seg_col[q / o.sddmm_Cs] = sd.res_col[q];
         }
     }
     // ---- ordering: heaviest first, so that the tail of the launch is made of light tasks ----
@@ -511,7 +531,10 @@ void libra::finish_plan(libra_plan_t *P, const ColumnFetch &cols, const int64_t 
         std::stable_sort(sd.tasks.begin(), mid, heavier);
         if (xcd < 0) P->o.xcd_order = xcd = st.neighbour_share <= LIBRA_SHARE_THRESHOLD;
         st.xcd_order = xcd;
-        if (!xcd && o.segments_by_column) place_segments_by_column(sa.tasks, sa.task_col);
+        if (!xcd && o.segments_by_column) {
+            place_segments_by_column(sa.tasks, sa.task_col);
+            place_sddmm_segments_by_column(sd.tasks, (size_t)(mid - sd.tasks.begin()), sd.tasks.size(), sd.seg_col);
+        }
         if (xcd) {
             const int W = o.W;
             xcd_order(sa.tasks, 0, sa.tasks.size(), [W](const libra_task_t &t, size_t) {

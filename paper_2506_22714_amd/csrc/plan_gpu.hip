@@ -57,7 +57,7 @@ struct Arena {
 
 struct Sizes {
     int64_t M, n;
-    int64_t nw, nbmax, tasks_a_max, tasks_d_max;
+    int64_t nw, nbmax, tasks_a_max, tasks_d_max, segs_d_max;
 };
 
 Sizes make_sizes(int64_t M, int64_t n, const Resolved &o) {
@@ -67,6 +67,7 @@ Sizes make_sizes(int64_t M, int64_t n, const Resolved &o) {
     z.nbmax = n / KB + z.nw + 1;
     z.tasks_a_max = z.nbmax / o.Ts + 2 * z.nw + 2 * (n / o.Cs) + 8;
     z.tasks_d_max = z.nbmax / o.Ts + z.nw + 8;
+    z.segs_d_max = n / o.sddmm_Cs + 2;
     return z;
 }
 
@@ -83,7 +84,7 @@ struct Layout {
     int32_t *win_ptr, *spos, *hflag, *vid, *einfo, *ewin, *row_of, *rowbase;
     u64 *key_in, *key_out, *key2_in, *key2_out, *ctr;
     int32_t *vfirst, *vinfo, *vcol, *vwin, *sv, *srank, *scnt, *cum, *tflag, *taud, *win_vptr;
-    int32_t *ntau, *nzero, *zbase, *nres, *resptr, *zero_rows, *task_col;
+    int32_t *ntau, *nzero, *zbase, *nres, *resptr, *zero_rows, *task_col, *seg_col;
     SubOut a, d;
     void *tmp;
     size_t tmp_bytes;
@@ -138,6 +139,7 @@ Layout make_layout(const Sizes &z, int vsize, void *base) {
     L.resptr = A.take<int32_t>(nw + 1);
     L.zero_rows = A.take<int32_t>((size_t)z.M);
     L.task_col = A.take<int32_t>((size_t)z.tasks_a_max);
+    L.seg_col = A.take<int32_t>((size_t)z.segs_d_max);
     for (SubOut *s : {&L.a, &L.d}) {
         s->slotvec = A.take<int32_t>(nb * KB);
         s->blk_cols = A.take<int32_t>(nb * KB);
@@ -608,6 +610,14 @@ __global__ __launch_bounds__(256) void k_residual_fill(const int32_t *col, const
 }
 
 // Per SpMM task: first column of a row segment's entries (the host orders the segments by it), -1 for other tasks.
+// Per flat SDDMM residual segment (cs entries of the residual list): its first column if the segment lies in one row, else -1.
+__global__ __launch_bounds__(256) void k_segment_cols(const int32_t *res_row, const int32_t *res_col, int nres, int cs, int nseg, int32_t *seg_col) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= nseg) return;
+    const int64_t q = (int64_t)i * cs, q1 = q + cs < nres ? q + cs : nres;
+    seg_col[i] = res_row[q] == res_row[q1 - 1] ? res_col[q] : -1;
+}
+
 __global__ __launch_bounds__(256) void k_task_cols(const libra_task_t *tasks, int nt, const int32_t *res_col, int32_t *task_col) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= nt) return;
@@ -841,6 +851,9 @@ extern "C" int libra_plan_device(int64_t M, int64_t Kc, int64_t nnz, const int32
                            L.d.resf, L.d.rescan, L.d.res_perm, L.d.res_row, L.d.res_col, L.d.res_val);
         if (o.build_spmm && ntA > 0)
             hipLaunchKernelGGL(k_task_cols, dim3(blocks_for(ntA, 256)), dim3(256), 0, s, L.a.tasks, ntA, L.a.res_col, L.task_col);
+        const int nsegD = o.build_sddmm ? (nresD + o.sddmm_Cs - 1) / o.sddmm_Cs : 0;
+        if (nsegD > 0)
+            hipLaunchKernelGGL(k_segment_cols, dim3(blocks_for(nsegD, 256)), dim3(256), 0, s, L.d.res_row, L.d.res_col, nresD, o.sddmm_Cs, nsegD, L.seg_col);
         hip_ok(hipMemcpyAsync(ctr, L.ctr, sizeof ctr, hipMemcpyDeviceToHost, s));
         hip_ok(hipStreamSynchronize(s));
         if (hipGetLastError() != hipSuccess) throw Fail{LIBRA_ERR_HIP};
@@ -860,6 +873,7 @@ extern "C" int libra_plan_device(int64_t M, int64_t Kc, int64_t nnz, const int32
             H.n.dense = dn[k]; H.n.res = nres2[k]; H.n.zero_rows = k == 0 ? nz : 0;
             fetch(H.tasks, S.tasks, (size_t)nts[k], s);
             if (k == 0) fetch(H.task_col, L.task_col, (size_t)nts[k], s);
+            if (k == 1) fetch(H.seg_col, L.seg_col, (size_t)nsegD, s);
             fetch(H.blk_valptr, S.blk_valptr, (size_t)nbs[k] + 1, s);
             if (!keep_host_copy) continue;
             fetch(H.win_blkptr, S.blkptr, (size_t)nw + 1, s);

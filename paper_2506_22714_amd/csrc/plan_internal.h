@@ -93,6 +93,8 @@ struct SubPlan {
     std::vector<int32_t> win_resptr, res_row, res_col, res_perm, zero_rows;
     std::vector<libra_task_t> tasks;
     std::vector<int32_t> task_col;      // SpMM, until the tables are ordered: first column of a row segment's entries, -1 for other tasks
+    std::vector<int32_t> seg_col;       // SDDMM, until the tables are ordered: per flat residual segment, its first column if all its
+                                        // nonzeros lie in one row, else -1 (the device planner fills it; the host planner derives it)
     int64_t n_window_tasks = 0, n_chunk_tasks = 0;
     int64_t dense_vectors = 0, pad_slots = 0;
     int64_t short_rows = 0, long_rows = 0, split_rows = 0;
