@@ -5,6 +5,8 @@
 // window order, so the result does not depend on the thread count.
 #include <algorithm>
 #include <chrono>
+#include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <thread>
@@ -304,6 +306,20 @@ void concat(SubPlan &dst, SubPlan &src, bool spmm) {
     src = SubPlan();
 }
 
+// Sorts packed keys (sort value in the high word, position in the low word) by the high word; keys that come in position
+// order leave in (value, position) order, i.e. this is the stable sort of the positions by value.  LSD radix, 11 bits a pass.
+void sort_by_high_word(std::vector<uint64_t> &a, uint32_t max_value) {
+    std::vector<uint64_t> b(a.size());
+    const int bits = 32 - __builtin_clz(max_value | 1u);
+    for (int shift = 0; shift < bits; shift += 11) {
+        std::vector<size_t> cnt(2049, 0);
+        for (uint64_t k : a) cnt[((k >> 32) >> shift & 2047u) + 1]++;
+        for (int i = 0; i < 2048; ++i) cnt[i + 1] += cnt[i];
+        for (uint64_t k : a) b[cnt[(k >> 32) >> shift & 2047u]++] = k;
+        a.swap(b);
+    }
+}
+
 // The task table that interleaves LIBRA_XCDS queues of positions into tasks[begin, end): entry LIBRA_XCDS*j + x is
 // the j-th task of queue x.  Queues of different length are levelled (see below).
 void interleave_queues(std::vector<libra_task_t> &tasks, size_t begin, size_t end, std::vector<size_t> (&queue)[LIBRA_XCDS], int noop_kind) {
@@ -330,8 +346,12 @@ void interleave_queues(std::vector<libra_task_t> &tasks, size_t begin, size_t en
     while (!out.empty() && out.back().cost == 0 && out.back().blk_begin == out.back().blk_end &&
            out.back().res_begin == out.back().res_end && out.back().store_mask == 0 && out.back().atomic_mask == 0)
         out.pop_back();                                             // empty tasks after the last real one
-    tasks.erase(tasks.begin() + begin, tasks.begin() + end);
-    tasks.insert(tasks.begin() + begin, out.begin(), out.end());
+    if (begin == 0 && end == tasks.size()) {
+        tasks.swap(out);
+    } else {
+        tasks.erase(tasks.begin() + begin, tasks.begin() + end);
+        tasks.insert(tasks.begin() + begin, out.begin(), out.end());
+    }
 }
 
 // XCD-aware placement.  Workgroup k of a launch runs on XCD k mod LIBRA_XCDS and every XCD has its own L2, so
@@ -375,7 +395,16 @@ void place_segments_by_column(std::vector<libra_task_t> &tasks, const std::vecto
     std::vector<size_t> seg, other;
     for (size_t i = 0; i < n; ++i) (tasks[i].kind == LIBRA_TASK_CHUNK ? seg : other).push_back(i);
     if (seg.size() < 8 * LIBRA_XCDS) return;
-    std::stable_sort(seg.begin(), seg.end(), [&](size_t a, size_t b) { return first_col[a] < first_col[b]; });
+    {   // by first column, ties in table order (packed keys)
+        std::vector<uint64_t> key(seg.size());
+        uint32_t top = 0;
+        for (size_t k = 0; k < seg.size(); ++k) {
+            key[k] = ((uint64_t)(uint32_t)first_col[seg[k]] << 32) | (uint32_t)seg[k];
+            top = std::max(top, (uint32_t)first_col[seg[k]]);
+        }
+        sort_by_high_word(key, top);
+        for (size_t k = 0; k < seg.size(); ++k) seg[k] = (size_t)(key[k] & 0xffffffffu);
+    }
     uint64_t total = 0;
     for (size_t i : seg) total += tasks[i].cost;
     std::vector<size_t> segq[LIBRA_XCDS], othq[LIBRA_XCDS], queue[LIBRA_XCDS];
@@ -406,7 +435,16 @@ void place_sddmm_segments_by_column(std::vector<libra_task_t> &tasks, size_t beg
     std::vector<size_t> placed, other;
     for (size_t i = 0; i < n; ++i) (seg_col.at(i) >= 0 ? placed : other).push_back(i);
     if (placed.size() < 8 * LIBRA_XCDS) return;
-    std::stable_sort(placed.begin(), placed.end(), [&](size_t a, size_t b) { return seg_col[a] < seg_col[b]; });
+    {
+        std::vector<uint64_t> key(placed.size());
+        uint32_t top = 0;
+        for (size_t k = 0; k < placed.size(); ++k) {
+            key[k] = ((uint64_t)(uint32_t)seg_col[placed[k]] << 32) | (uint32_t)placed[k];
+            top = std::max(top, (uint32_t)seg_col[placed[k]]);
+        }
+        sort_by_high_word(key, top);
+        for (size_t k = 0; k < placed.size(); ++k) placed[k] = (size_t)(key[k] & 0xffffffffu);
+    }
     std::vector<size_t> queue[LIBRA_XCDS];
     for (size_t r = 0; r < placed.size(); ++r) queue[r * LIBRA_XCDS / placed.size()].push_back(placed[r]);
     for (size_t r = 0; r < other.size(); ++r) queue[r % LIBRA_XCDS].push_back(other[r]);
@@ -484,6 +522,12 @@ void libra::finish_plan(libra_plan_t *P, const ColumnFetch &cols, const int64_t 
     libra_stats_t &st = P->stats;
     const int64_t nwin = (M + o.W - 1) / o.W;
     int xcd = o.xcd_order;
+    const bool trace = std::getenv("LIBRA_TRACE") != nullptr;
+    const auto t0 = std::chrono::steady_clock::now();
+    auto mark = [&](const char *what) {
+        if (trace) std::fprintf(stderr, "[finish_plan] %-34s %8.3f ms\n", what,
+                                1e3 * std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count());
+    };
     for (int64_t i = 0; i < M; ++i) {       // row lists of the edge softmax
         const int32_t n = rowptr[i + 1] - rowptr[i];
         if (n > LIBRA_SOFTMAX_LONG_ROW) P->long_rows.push_back((int32_t)i);
@@ -507,33 +551,50 @@ void libra::finish_plan(libra_plan_t *P, const ColumnFetch &cols, const int64_t 
             if (derive && sd.res_row[q] == sd.res_row[q1 - 1]) sd.seg_col[q / o.sddmm_Cs] = sd.res_col[q];
         }
     }
+    mark("row lists, sddmm segments");
     // ---- ordering: heaviest first, so that the tail of the launch is made of light tasks ----
     st.neighbour_share = share ? (share[1] ? (double)share[0] / (double)share[1] : 1.0) : neighbour_share(M, rowptr, cols, o.W);
+    mark("neighbour share");
     if (o.heavy_first) {
         auto heavier = [](const libra_task_t &a, const libra_task_t &b) { return a.cost > b.cost; };
         {
             // heaviest first, the segments' first columns travelling with their tasks
-            std::vector<size_t> ord(sa.tasks.size());
-            for (size_t i = 0; i < ord.size(); ++i) ord[i] = i;
-            std::stable_sort(ord.begin(), ord.end(), [&](size_t a, size_t b) { return sa.tasks[a].cost > sa.tasks[b].cost; });
+            // (sorted as packed keys: descending cost, then position - i.e. a stable sort - without indirect compares)
+            uint32_t top = 0;
+            for (const libra_task_t &t : sa.tasks) top = std::max(top, t.cost);
+            std::vector<uint64_t> ord(sa.tasks.size());
+            for (size_t i = 0; i < ord.size(); ++i) ord[i] = ((uint64_t)(top - sa.tasks[i].cost) << 32) | (uint32_t)i;
+            sort_by_high_word(ord, top);
             std::vector<libra_task_t> ts(ord.size());
             std::vector<int32_t> tc(ord.size(), -1);
             for (size_t i = 0; i < ord.size(); ++i) {
-                ts[i] = sa.tasks[ord[i]];
-                tc[i] = sa.task_col.at(ord[i]);          // both planners fill one entry per task
+                const size_t from = (size_t)(ord[i] & 0xffffffffu);
+                ts[i] = sa.tasks[from];
+                tc[i] = sa.task_col.at(from);            // both planners fill one entry per task
             }
             sa.tasks.swap(ts);
             sa.task_col.swap(tc);
         }
+        mark("spmm heaviest first");
         // SDDMM window tasks first (heaviest first); the flat residual segments stay behind them in order
         auto mid = std::stable_partition(sd.tasks.begin(), sd.tasks.end(),
                                          [](const libra_task_t &t) { return t.kind == LIBRA_TASK_WINDOW; });
         std::stable_sort(sd.tasks.begin(), mid, heavier);
         if (xcd < 0) P->o.xcd_order = xcd = st.neighbour_share <= LIBRA_SHARE_THRESHOLD;
         st.xcd_order = xcd;
+        mark("sddmm window tasks first");
         if (!xcd && o.segments_by_column) {
-            place_segments_by_column(sa.tasks, sa.task_col);
-            place_sddmm_segments_by_column(sd.tasks, (size_t)(mid - sd.tasks.begin()), sd.tasks.size(), sd.seg_col);
+            // the two tables are independent: the SDDMM one is placed on a second thread unless the caller asked for one
+            const size_t nwt = (size_t)(mid - sd.tasks.begin());
+            auto place_sd = [&]() { place_sddmm_segments_by_column(sd.tasks, nwt, sd.tasks.size(), sd.seg_col); };
+            if (o.threads == 1) {
+                place_segments_by_column(sa.tasks, sa.task_col);
+                place_sd();
+            } else {
+                std::thread other(place_sd);
+                place_segments_by_column(sa.tasks, sa.task_col);
+                other.join();
+            }
         }
         if (xcd) {
             const int W = o.W;
@@ -548,6 +609,7 @@ void libra::finish_plan(libra_plan_t *P, const ColumnFetch &cols, const int64_t 
                 return (int64_t)t.id / LIBRA_LOCALITY_WINDOWS; }, LIBRA_TASK_CHUNK);
         }
     }
+    mark("placement done");
     for (SubPlan *sp : {&sa, &sd}) {
         for (auto &t : sp->tasks) (t.kind == LIBRA_TASK_WINDOW ? sp->n_window_tasks : sp->n_chunk_tasks)++;
         sp->n.tasks = (int64_t)sp->tasks.size();
