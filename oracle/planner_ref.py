@@ -44,7 +44,7 @@ class Opts:
     KB: int = 16
     tau_spmm: int = 3
     tau_sddmm: int = 64
-    Ts: int = 8
+    Ts: int = 16
     Cs: int = 128
     short_len: int = 3
     fill_padding: bool = True

@@ -491,7 +491,7 @@ int libra::resolve_options(const libra_plan_opts_t *in, int vdt, Resolved &o) {
     o.KB = z.block_cols ? z.block_cols : 16;
     o.tau_spmm = z.spmm_min_vec_nnz ? z.spmm_min_vec_nnz : 3;
     o.tau_sddmm = z.sddmm_min_blk_nnz ? z.sddmm_min_blk_nnz : 64;
-    o.Ts = z.ts ? z.ts : 8;
+    o.Ts = z.ts ? z.ts : 16;
     o.Cs = z.cs ? z.cs : 128;
     o.short_len = z.short_len ? z.short_len : 3;
     o.sddmm_Cs = z.sddmm_cs ? z.sddmm_cs : 128;

@@ -152,7 +152,7 @@ def ref_opts(kw: dict) -> pr.Opts:
     fl = kw.get("flags", 0)
     return pr.Opts(mode=kw.get("mode", 0), W=kw.get("window_rows", 16), KB=kw.get("block_cols", 16),
                    tau_spmm=kw.get("spmm_min_vec_nnz", 3), tau_sddmm=kw.get("sddmm_min_blk_nnz", 64),
-                   Ts=kw.get("ts", 8), Cs=kw.get("cs", 128), short_len=kw.get("short_len", 3),
+                   Ts=kw.get("ts", 16), Cs=kw.get("cs", 128), short_len=kw.get("short_len", 3),
                    fill_padding=not (fl & lb.FLAG_NO_FILL_PADDING), sddmm_Cs=kw.get("sddmm_cs", 128))
 
 
