@@ -52,6 +52,7 @@ struct SpmmArgs {
     const void *B;
     float *C;
     int64_t ldb, ldc;
+    int32_t tasks_per_die;  // the table holds die k's tasks (dispatch positions k, k + 8, ...) contiguously from k * tasks_per_die on
     int32_t phase;          // 0: a task does all its work; 1: dense blocks only; 2: residual nonzeros only, added to what phase 1 wrote
 };
 
@@ -246,6 +247,10 @@ template <> __device__ inline bf16_t to_storage<bf16_t>(float x) {
     return bf16_t{(uint16_t)(u >> 16)};
 }
 
+// Workgroup b of a launch runs on die b mod 8, so the records of the tasks that one die runs are stored next to each
+// other: a 128-byte line of the table then serves four consecutive workgroups of one die instead of four dies.
+__device__ inline int64_t task_slot(unsigned b, int per_die) { return (int64_t)(b & (LIBRA_XCDS - 1)) * per_die + (b >> 3); }
+
 // ---------------------------------------------------------------------------------------
 // SpMM.  N = feature columns handled by this launch, T = storage type of values and B.
 //
@@ -293,7 +298,7 @@ __global__ __launch_bounds__(WAVE) __attribute__((amdgpu_waves_per_eu(N >= 128 ?
     __shared__ __attribute__((aligned(16))) uint64_t bm_lds[DENSE ? BCAP * 4 : 2];
     float *tile = reinterpret_cast<float *>(smem);
 
-    const DevTask t = a.tasks[blockIdx.x];
+    const DevTask t = a.tasks[task_slot(blockIdx.x, a.tasks_per_die)];
     const int lane = threadIdx.x;
     const int sub = lane % LPR;              // which PL-wide piece of a row
     const int grp = lane / LPR;              // which lane group
@@ -619,6 +624,7 @@ struct SddmmArgs {
     const void *Y;
     float *out;
     int64_t M;
+    int32_t tasks_per_die;      // as in SpmmArgs
     int32_t pattern_only;       // nonzero: out_p = <X_i, Y_j>, A's values are not applied
 };
 
@@ -750,7 +756,7 @@ __device__ inline void sddmm_segment_task(const SddmmArgs &a, const DevTask &t) 
 // residual segments.  fp32 plans have no window tasks.
 template <class T, int K>
 __global__ __launch_bounds__(WAVE) void sddmm_task_kernel(SddmmArgs a) {
-    const DevTask t = a.tasks[blockIdx.x];
+    const DevTask t = a.tasks[task_slot(blockIdx.x, a.tasks_per_die)];
     if constexpr (!std::is_same<T, float>::value) {
         if (t.kind == LIBRA_TASK_WINDOW) {
             sddmm_window_task<T, K>(a, t);
@@ -971,15 +977,16 @@ int spmm_launch(const libra_plan_t *P, const SpmmArgs &a, int n, int64_t nt, hip
 
 int spmm_piece(const libra_plan_t *P, const void *B, int n, int64_t ldb, float *C, int64_t ldc, hipStream_t s) {
     const SubPlan &sp = P->spmm;
+    const int64_t per_die = ((int64_t)sp.tasks.size() + LIBRA_XCDS - 1) / LIBRA_XCDS;
     SpmmArgs a{sp.dev.tasks, sp.dev.blk_cols, sp.dev.blk_bitmap, sp.dev.blk_valptr, sp.dev.dense_val,
-               sp.dev.res_ent, B, C, ldb, ldc, 0};
+               sp.dev.res_ent, B, C, ldb, ldc, (int32_t)per_die, 0};
     if (sp.n.zero_rows) {
         const int64_t total = sp.n.zero_rows * (n / 4);
         const unsigned blocks = (unsigned)std::min<int64_t>((total + 255) / 256, 65536);
         hipLaunchKernelGGL(zero_rows_kernel, dim3(blocks), dim3(256), 0, s, sp.dev.zero_rows, sp.n.zero_rows, C, ldc, n / 4);
         if (hipGetLastError() != hipSuccess) return LIBRA_ERR_HIP;
     }
-    const int64_t nt = (int64_t)sp.tasks.size();
+    const int64_t nt = per_die * LIBRA_XCDS;         // every slot of the table (the last few may hold empty tasks)
     if (P->o.two_kernels && a.phase == 0) {
         // ablation / debugging schedule: the matrix-unit part and the scalar part as two launches on the stream
         for (int phase = 1; phase <= 2; ++phase) {
@@ -1044,8 +1051,14 @@ struct Uploader {
     void putv(const V &v, P *&dst) { put(v.data(), nullptr, v.size() * sizeof(v[0]), dst); }
 };
 
+// Slots of the device task table: the table's length rounded up to whole rounds of the dies.
+size_t task_slots(int64_t ntasks) { return (size_t)((ntasks + LIBRA_XCDS - 1) / LIBRA_XCDS) * LIBRA_XCDS; }
+
+// Device task records, die by die (see task_slot); the slots past the last task hold empty tasks.
 std::vector<DevTask> pack_tasks(const libra_plan_t *P, const SubPlan &sp, bool spmm) {
-    std::vector<DevTask> out(sp.tasks.size());
+    const size_t per_die = task_slots((int64_t)sp.tasks.size()) / LIBRA_XCDS;
+    const DevTask empty{0, 0, 0, 0, 0, 0u, (uint32_t)(spmm ? LIBRA_TASK_WINDOW : LIBRA_TASK_CHUNK), 0};
+    std::vector<DevTask> out(per_die * LIBRA_XCDS, empty);
     for (size_t i = 0; i < sp.tasks.size(); ++i) {
         const libra_task_t &t = sp.tasks[i];
         DevTask d{t.id, t.blk_begin, t.blk_end, t.res_begin, t.res_end, (t.atomic_mask & 0xffffu) | (t.store_mask << 16),
@@ -1056,7 +1069,7 @@ std::vector<DevTask> pack_tasks(const libra_plan_t *P, const SubPlan &sp, bool s
             d.blk_begin = d.blk_end = 0;
             d.masks = 1u << (t.id % P->o.W);
         }
-        out[i] = d;
+        out[(i % LIBRA_XCDS) * per_die + i / LIBRA_XCDS] = d;
     }
     return out;
 }
@@ -1105,7 +1118,7 @@ void layout(libra_plan_t *P, Uploader &u, Staging *st, const DeviceSource *da, c
     auto H = [&](const void *p) { return from_host ? p : nullptr; };
     // ---- SpMM ----
     if (st) st->tasks_a = pack_tasks(P, sa, true);
-    u.put(st ? (const void *)st->tasks_a.data() : nullptr, nullptr, (size_t)sa.n.tasks * sizeof(DevTask), sa.dev.tasks);
+    u.put(st ? (const void *)st->tasks_a.data() : nullptr, nullptr, task_slots(sa.n.tasks) * sizeof(DevTask), sa.dev.tasks);
     u.put(H(sa.blk_cols.data()), da ? da->blk_cols : nullptr, (size_t)sa.n.col_slots * 4, sa.dev.blk_cols);
     u.put(H(sa.blk_bitmap.data()), da ? da->blk_bitmap : nullptr, (size_t)sa.n.bitmap_words * 8, sa.dev.blk_bitmap);
     u.put(H(sa.blk_valptr.data()), da ? da->blk_valptr : nullptr, P->o.build_spmm ? (size_t)(sa.n.blocks + 1) * 4 : 0, sa.dev.blk_valptr);
@@ -1130,7 +1143,7 @@ void layout(libra_plan_t *P, Uploader &u, Staging *st, const DeviceSource *da, c
     u.put(H(sa.zero_rows.data()), da ? da->zero_rows : nullptr, (size_t)sa.n.zero_rows * 4, sa.dev.zero_rows);
     // ---- SDDMM ----
     if (st) st->tasks_d = pack_tasks(P, sd, false);
-    u.put(st ? (const void *)st->tasks_d.data() : nullptr, nullptr, (size_t)sd.n.tasks * sizeof(DevTask), sd.dev.tasks);
+    u.put(st ? (const void *)st->tasks_d.data() : nullptr, nullptr, task_slots(sd.n.tasks) * sizeof(DevTask), sd.dev.tasks);
     u.put(H(sd.blk_cols.data()), dd ? dd->blk_cols : nullptr, (size_t)sd.n.col_slots * 4, sd.dev.blk_cols);
     u.put(H(sd.blk_bitmap.data()), dd ? dd->blk_bitmap : nullptr, (size_t)sd.n.bitmap_words * 8, sd.dev.blk_bitmap);
     u.put(H(sd.blk_valptr.data()), dd ? dd->blk_valptr : nullptr, P->o.build_sddmm ? (size_t)(sd.n.blocks + 1) * 4 : 0, sd.dev.blk_valptr);
@@ -1285,9 +1298,10 @@ int sddmm_call(const libra_plan_t *P, const void *X, const void *Y, int32_t K, f
     const SubPlan &sp = P->sddmm;
     SddmmArgs a{sp.dev.tasks, sp.dev.blk_cols, sp.dev.blk_bitmap, sp.dev.blk_valptr,
                 reinterpret_cast<const uint2 *>(sp.dev.dense_pv), (int32_t)sp.n.dense,
-                reinterpret_cast<const SdEnt *>(sp.dev.res_ent), X, Y, out, P->M, pattern_only};
-    const int64_t nt = (int64_t)sp.tasks.size();
-    if (nt == 0) return LIBRA_OK;
+                reinterpret_cast<const SdEnt *>(sp.dev.res_ent), X, Y, out, P->M, 0, pattern_only};
+    if (sp.tasks.empty()) return LIBRA_OK;
+    a.tasks_per_die = (int32_t)(((int64_t)sp.tasks.size() + LIBRA_XCDS - 1) / LIBRA_XCDS);
+    const int64_t nt = (int64_t)a.tasks_per_die * LIBRA_XCDS;     // every slot of the table
     if (sp.n_window_tasks > 0 && P->vdt == LIBRA_F32) return LIBRA_ERR_UNSUPPORTED;
     const dim3 grid((unsigned)nt), block(WAVE);
     if (P->vdt == LIBRA_F16) {
