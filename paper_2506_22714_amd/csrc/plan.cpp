@@ -8,6 +8,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <exception>
 #include <new>
 #include <thread>
 
@@ -591,9 +592,18 @@ void libra::finish_plan(libra_plan_t *P, const ColumnFetch &cols, const int64_t 
                 place_segments_by_column(sa.tasks, sa.task_col);
                 place_sd();
             } else {
-                std::thread other(place_sd);
-                place_segments_by_column(sa.tasks, sa.task_col);
+                std::exception_ptr failed;          // an exception must not leave the thread's function
+                std::thread other([&]() {
+                    try { place_sd(); } catch (...) { failed = std::current_exception(); }
+                });
+                try {
+                    place_segments_by_column(sa.tasks, sa.task_col);
+                } catch (...) {
+                    other.join();
+                    throw;
+                }
                 other.join();
+                if (failed) std::rethrow_exception(failed);
             }
         }
         if (xcd) {
