@@ -454,27 +454,48 @@ void place_sddmm_segments_by_column(std::vector<libra_task_t> &tasks, size_t beg
 
 // How much neighbouring windows overlap in the columns they reference, on an evenly spaced sample of groups of
 // LIBRA_LOCALITY_WINDOWS windows: distinct columns of the group / sum of the distinct columns of its windows.
-double neighbour_share(int64_t M, const int32_t *rowptr, const ColumnFetch &cols, int W) {
+double neighbour_share(int64_t M, const int32_t *rowptr, const ColumnFetch &cols, int W, int threads) {
     const int64_t rows_per_group = (int64_t)W * LIBRA_LOCALITY_WINDOWS;
     const int64_t ngroups = (M + rows_per_group - 1) / rows_per_group;
     const int64_t nsample = share_samples(ngroups);
-    std::vector<uint64_t> keys;
-    int64_t together = 0, apart = 0;
-    for (int64_t k = 0; k < nsample; ++k) {
-        const int64_t g = sampled_group(k, ngroups, nsample);
-        const int64_t r0 = g * rows_per_group, r1 = std::min(M, r0 + rows_per_group);
-        keys.clear();
-        const int32_t *col = cols(rowptr[r0], rowptr[r1]) - rowptr[r0];      // indexable by CSR position
-        for (int64_t i = r0; i < r1; ++i)
-            for (int32_t p = rowptr[i]; p < rowptr[i + 1]; ++p)
-                keys.push_back(((uint64_t)((i - r0) / W) << 32) | (uint32_t)col[p]);
-        std::sort(keys.begin(), keys.end());
-        apart += std::unique(keys.begin(), keys.end()) - keys.begin();
-        for (auto &x : keys) x &= 0xffffffffull;
-        std::sort(keys.begin(), keys.end());
-        together += std::unique(keys.begin(), keys.end()) - keys.begin();
+    int nthr = threads ? threads : (int)std::thread::hardware_concurrency();
+    nthr = (int)std::max<int64_t>(1, std::min<int64_t>(nthr, nsample));
+    std::vector<int64_t> together(nthr, 0), apart(nthr, 0);
+    // the sampled groups are independent; a hub window's group alone can hold a large share of the nonzeros, so the
+    // samples are dealt to the threads one by one rather than in ranges
+    auto work = [&](int t) {
+        std::vector<uint64_t> keys;
+        for (int64_t k = t; k < nsample; k += nthr) {
+            const int64_t g = sampled_group(k, ngroups, nsample);
+            const int64_t r0 = g * rows_per_group, r1 = std::min(M, r0 + rows_per_group);
+            keys.clear();
+            const int32_t *col = cols(rowptr[r0], rowptr[r1]) - rowptr[r0];      // indexable by CSR position
+            for (int64_t i = r0; i < r1; ++i)
+                for (int32_t p = rowptr[i]; p < rowptr[i + 1]; ++p)
+                    keys.push_back(((uint64_t)((i - r0) / W) << 32) | (uint32_t)col[p]);
+            std::sort(keys.begin(), keys.end());
+            apart[t] += std::unique(keys.begin(), keys.end()) - keys.begin();
+            for (auto &x : keys) x &= 0xffffffffull;
+            std::sort(keys.begin(), keys.end());
+            together[t] += std::unique(keys.begin(), keys.end()) - keys.begin();
+        }
+    };
+    if (nthr == 1) {
+        work(0);
+    } else {
+        std::vector<std::exception_ptr> failed(nthr);
+        std::vector<std::thread> pool;
+        for (int t = 0; t < nthr; ++t)
+            pool.emplace_back([&, t]() {
+                try { work(t); } catch (...) { failed[t] = std::current_exception(); }
+            });
+        for (auto &th : pool) th.join();
+        for (auto &f : failed)
+            if (f) std::rethrow_exception(f);
     }
-    return apart ? (double)together / (double)apart : 1.0;
+    int64_t tg = 0, ap = 0;
+    for (int t = 0; t < nthr; ++t) { tg += together[t]; ap += apart[t]; }
+    return ap ? (double)tg / (double)ap : 1.0;
 }
 
 }  // namespace
@@ -554,7 +575,7 @@ void libra::finish_plan(libra_plan_t *P, const ColumnFetch &cols, const int64_t 
     }
     mark("row lists, sddmm segments");
     // ---- ordering: heaviest first, so that the tail of the launch is made of light tasks ----
-    st.neighbour_share = share ? (share[1] ? (double)share[0] / (double)share[1] : 1.0) : neighbour_share(M, rowptr, cols, o.W);
+    st.neighbour_share = share ? (share[1] ? (double)share[0] / (double)share[1] : 1.0) : neighbour_share(M, rowptr, cols, o.W, o.threads);
     mark("neighbour share");
     if (o.heavy_first) {
         auto heavier = [](const libra_task_t &a, const libra_task_t &b) { return a.cost > b.cost; };
