@@ -7,6 +7,7 @@ library through the binding only.
 
     python -m paper_2506_22714_amd.tune --workload powerlaw --N 128 --K 32
     python -m paper_2506_22714_amd.tune --workload community --what tau_sddmm
+    python -m paper_2506_22714_amd.tune --workload gat --N 64 --K 64 --what ablation
 """
 from __future__ import annotations
 
@@ -39,6 +40,22 @@ SWEEPS = {
     "sddmm_cs": [dict(sddmm_cs=c) for c in (64, 128, 256, 512, 1024)],
 }
 
+# The parts of the method switched off one at a time (the paper's ablations, Section 5.4): not part of "all".
+# Flag values as in libra.h: 1 no filling of padding slots, 8 window order, 32 | 256 heaviest first without any
+# die-aware order or placement.
+UNBOUNDED = 1 << 20
+ABLATION = [
+    ("as shipped", dict()),
+    ("no load balancing (Ts, Cs unbounded)", dict(ts=UNBOUNDED, cs=UNBOUNDED)),
+    ("dense part not decomposed (Ts unbounded)", dict(ts=UNBOUNDED)),
+    ("long rows not decomposed (Cs unbounded)", dict(cs=UNBOUNDED)),
+    ("window order instead of heaviest first", dict(flags=8)),
+    ("heaviest first, nothing die-aware", dict(flags=32 | 256)),
+    ("padding slots not filled", dict(flags=1)),
+    ("matrix cores only", dict(mode=1)),
+    ("vector ALUs only", dict(mode=2)),
+]
+
 
 def main() -> int:
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
@@ -46,7 +63,7 @@ def main() -> int:
     ap.add_argument("--small", action="store_true")
     ap.add_argument("--N", type=int, default=128)
     ap.add_argument("--K", type=int, default=32)
-    ap.add_argument("--what", default="all", help="one of: all, " + ", ".join(SWEEPS))
+    ap.add_argument("--what", default="all", help="one of: all, ablation, " + ", ".join(SWEEPS))
     args = ap.parse_args()
 
     import torch
@@ -62,6 +79,15 @@ def main() -> int:
     rowptr, col, val = (torch.from_numpy(x).cuda() for x in (A.rowptr.astype(np.int32), A.col.astype(np.int32), A.val))
     print(f"# {args.workload}: M={A.M} nnz={A.nnz} N={args.N} K={args.K}")
     print(f"# {'setting':34s} {'spmm us':>9s} {'dense':>6s} {'tasks':>8s} | {'sddmm us':>9s} {'dense':>6s} {'tasks':>8s}")
+    if args.what == "ablation":
+        for label, kw in ABLATION:
+            p = lb.Plan.from_device_csr(A.M, A.Kc, rowptr, col, val, resident=True, keep_host_copy=False, **kw)
+            st = p.stats()
+            t_spmm, t_sddmm = time_us(lambda: p.spmm(B, out=C)), time_us(lambda: p.sddmm(X, Y, out=out))
+            print(f"  {label:42s} {t_spmm:9.1f} {st['spmm_dense_nnz'] / max(A.nnz, 1):6.3f} {st['spmm_tasks']:8d} | "
+                  f"{t_sddmm:9.1f} {st['sddmm_dense_nnz'] / max(A.nnz, 1):6.3f} {st['sddmm_tasks']:8d}", flush=True)
+            p.close()
+        return 0
     names = list(SWEEPS) if args.what == "all" else [args.what]
     for name in names:
         for kw in SWEEPS[name]:
