@@ -56,7 +56,7 @@ extern "C" {
 /* ---- value types (storage type of A's values and of the dense operands) ---- */
 #define LIBRA_F16   0    /* IEEE binary16 in, fp32 accumulate (MFMA + VALU) */
 #define LIBRA_BF16  1    /* bfloat16 in, fp32 accumulate (MFMA + VALU); beside the paper's FP16 / TF32 inputs (Section 4.4) */
-#define LIBRA_F32   2    /* binary32 in, fp32 accumulate; scalar (VALU) path only */
+#define LIBRA_F32   2    /* binary32 in, fp32 accumulate (MFMA 16x16x4 f32 + VALU): the paper's TF32 & FP32 mode with unrounded inputs */
 
 /* ---- distribution modes (Section 5.3.2: matrix-unit-only, scalar-only, hybrid) ---- */
 #define LIBRA_MODE_HYBRID       0
@@ -171,8 +171,8 @@ typedef struct {
  *   M, Kc        in   matrix shape, 1 <= M, Kc < 2^31
  *   rowptr       in   host, int32[M+1], rowptr[0] = 0, non-decreasing, rowptr[M] = nnz < 2^31
  *   col          in   host, int32[nnz], strictly increasing inside each row, 0 <= col < Kc
- *   val          in   host, nnz values of type val_dtype (LIBRA_F16, LIBRA_BF16 or LIBRA_F32).  LIBRA_F32 forces
- *                     LIBRA_MODE_SCALAR_ONLY (CDNA4 has no reduced-precision-free fp32 matrix path worth using).
+ *   val          in   host, nnz values of type val_dtype (LIBRA_F16, LIBRA_BF16 or LIBRA_F32).  The split does not depend
+ *                     on the type; fp32 dense tiles run on v_mfma_f32_16x16x4_f32 (CDNA4 has no TF32: nothing is rounded).
  *   opts         in   host, may be NULL (all defaults)
  *   out          out  receives a new plan; release with libra_plan_destroy.  The inputs are copied,
  *                     the caller may free them after the call.
@@ -227,7 +227,7 @@ int libra_plan_upload(libra_plan_t *plan, void *dev_buf, size_t bytes, void *str
  *   C    device, M x N row-major fp32 with row stride ldc (ldc >= N, ldc % 4 == 0); fully overwritten
  *        (rows of A without nonzeros become zeros); must not alias B.
  *   N    multiple of 32 (fp16) or of 16 (fp32), 32 <= N <= 512
- * Dense blocks run on MFMA (fp16 operands, fp32 accumulate), residual nonzeros on the VALU (fp32 FMA);
+ * Dense blocks run on MFMA (operands of the plan's value type, fp32 accumulate), residual nonzeros on the VALU (fp32 FMA);
  * rows with one writer are stored once, rows with several writers are cleared and accumulated with
  * fp32 atomics (their summation order is not deterministic).
  * Errors: NULL, SHAPE, UNSUPPORTED, NOT_UPLOADED, NOT_BUILT, HIP.

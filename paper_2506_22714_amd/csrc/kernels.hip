@@ -103,6 +103,7 @@ template <> struct Elem<half_t> {
         e.row = (uint16_t)(w >> 16);
         return e;
     }
+    __device__ static void mask(raw_t &r, uint32_t keep) { r.x &= keep; r.y &= keep; r.z &= keep; r.w &= keep; }
     // a batch of U consecutive entries from a 16-byte aligned address: U/2 16-byte LDS reads issued back to back, one wait;
     // the words that hold {value, row} go through an opaque move afterwards so that each is read once, whole
     template <int U>
@@ -193,6 +194,10 @@ template <> struct Elem<float> {
         e.pad = 0;
         return e;
     }
+    __device__ static void mask(raw_t &r, uint32_t keep) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) r[e] = __uint_as_float(__float_as_uint(r[e]) & keep);
+    }
     template <int U>
     __device__ static void lds_batch(const ent_t *lds, ent_t (&en)[U]) {
 #pragma unroll
@@ -277,16 +282,17 @@ template <class T, int N>
 __global__ __launch_bounds__(WAVE) __attribute__((amdgpu_waves_per_eu(N >= 128 ? 4 : 6))) void spmm_task_kernel(SpmmArgs a) {
     using E = Elem<T>;
     typedef typename E::ent_t ent_t;
-    constexpr bool DENSE = !std::is_same<T, float>::value;     // 16-bit storage: the matrix-core path exists
+    constexpr bool F32 = std::is_same<T, float>::value;        // fp32 storage: v_mfma_f32_16x16x4_f32, operands straight from the stage
+    constexpr bool DENSE = true;
     constexpr int PL = E::PER_LANE;          // elements of a row per lane
     constexpr int LPR = N / PL;              // lanes per row
     constexpr int RPW = WAVE / LPR;          // lane groups per wave
     static_assert(LPR >= 1 && LPR <= WAVE && WAVE % LPR == 0, "unsupported N");
     constexpr int LDC = N + 4;               // fp32 tile row stride (floats)
     constexpr int BPI = 1;                   // dense blocks staged in LDS at a time (the stage then fits inside the tile's bytes)
-    constexpr int LDBS = N + 16;             // fp16 stage row stride (halves): 4 consecutive rows cover all 32 banks
+    constexpr int LDBS = N + 16;             // stage row stride in elements: 4 consecutive 16-bit rows / 2 consecutive fp32 rows cover all 32 banks
     constexpr int TILE_BYTES = W * LDC * 4;
-    constexpr int STAGE_BYTES = DENSE ? BPI * KB * LDBS * 2 : 0;
+    constexpr int STAGE_BYTES = DENSE ? BPI * KB * LDBS * (int)sizeof(T) : 0;
     constexpr int SMEM = TILE_BYTES > STAGE_BYTES ? TILE_BYTES : STAGE_BYTES;
     constexpr int ECAP = 128;                // residual entries staged per round
     constexpr int BCAP = 8;                  // dense blocks whose metadata is staged per round
@@ -359,10 +365,11 @@ __global__ __launch_bounds__(WAVE) __attribute__((amdgpu_waves_per_eu(N >= 128 ?
             tile_ready = true;
             constexpr int NT = N / 16;
             constexpr int PASSES = BPI * KB / RPW;               // wave loads per staged group of BPI blocks
-            constexpr int H = N <= 128 ? 2 : 1;                  // staged groups per round trip (more costs registers, i.e. waves)
+            constexpr int H = (N <= 128 && !F32) ? 2 : 1;        // staged groups per round trip (more costs registers, i.e. waves)
             constexpr int FPI = BPI * H;                         // blocks fetched per round trip
             static_assert(BPI * KB % RPW == 0 && PASSES >= 1, "stage shape");
-            uint16_t *stage = reinterpret_cast<uint16_t *>(smem);
+            typedef typename std::conditional<F32, float, uint16_t>::type stage_t;
+            stage_t *stage = reinterpret_cast<stage_t *>(smem);
             const int g = lane >> 4, j = lane & 15;
             float4_t acc[NT];
 #pragma unroll
@@ -378,7 +385,7 @@ __global__ __launch_bounds__(WAVE) __attribute__((amdgpu_waves_per_eu(N >= 128 ?
                 for (int bb = 0; bb < nbr; bb += FPI) {
                     const int nb = min(FPI, nbr - bb);
                     // one round trip: the B rows of up to FPI blocks (padding slots become zero rows) ...
-                    uint4 raw[H][PASSES];
+                    typename E::raw_t raw[H][PASSES];
                     int cc[H][PASSES];
                     // all column ids first (LDS reads back to back), then all fetches
 #pragma unroll
@@ -397,13 +404,15 @@ __global__ __launch_bounds__(WAVE) __attribute__((amdgpu_waves_per_eu(N >= 128 ?
                             uint32_t keep = (k < nb * KB && c >= 0) ? 0xffffffffu : 0u;
                             asm volatile("" : "+v"(keep));
                             raw[h][ps] = E::load_row(a.B, keep ? c : 0, ldb_bytes, sub);
-                            raw[h][ps].x &= keep; raw[h][ps].y &= keep; raw[h][ps].z &= keep; raw[h][ps].w &= keep;
+                            E::mask(raw[h][ps], keep);
                         }
                     // ... and this lane's 4 A elements (row j, slots 4g..4g+3) of each block, decoded from its bitmap
-                    short4_t af[FPI];
+                    typedef typename std::conditional<F32, float, short>::type aval_t;
+                    typedef typename std::conditional<F32, float4_t, short4_t>::type afrag_t;
+                    afrag_t af[FPI];
 #pragma unroll
                     for (int x = 0; x < FPI; ++x) {
-                        af[x] = short4_t{0, 0, 0, 0};
+                        af[x] = afrag_t{0, 0, 0, 0};
                         if (x < nb) {
                             const uint64_t *bm = &bm_lds[(bb + x) * 4];
                             const uint64_t w0 = bm[0], w1 = bm[1], w2 = bm[2], w3 = bm[3];
@@ -414,14 +423,14 @@ __global__ __launch_bounds__(WAVE) __attribute__((amdgpu_waves_per_eu(N >= 128 ?
                             const int bitpos = (j & 3) * 16 + 4 * g;
                             prefix += __popcll(word & ((1ull << bitpos) - 1ull));
                             const unsigned nib = (unsigned)(word >> bitpos) & 0xFu;
-                            const short *vals = reinterpret_cast<const short *>(a.dense_val) + vbase + prefix;
-                            // unconditional loads (an unset slot reads a neighbouring value, at most 3 halves past the
+                            const aval_t *vals = reinterpret_cast<const aval_t *>(a.dense_val) + vbase + prefix;
+                            // unconditional loads (an unset slot reads a neighbouring value, at most 3 values past the
                             // array's end, inside its 16 spare bytes) and a select afterwards
-                            short av[4];
+                            aval_t av[4];
 #pragma unroll
                             for (int e = 0; e < 4; ++e) av[e] = vals[__popc(nib & ((1u << e) - 1u))];
 #pragma unroll
-                            for (int e = 0; e < 4; ++e) af[x][e] = (nib >> e & 1u) ? av[e] : (short)0;
+                            for (int e = 0; e < 4; ++e) af[x][e] = (nib >> e & 1u) ? av[e] : (aval_t)0;
                             vbase += c0 + c1 + c2 + c3;
                         }
                     }
@@ -433,20 +442,31 @@ __global__ __launch_bounds__(WAVE) __attribute__((amdgpu_waves_per_eu(N >= 128 ?
 #pragma unroll
                             for (int ps = 0; ps < PASSES; ++ps) {
                                 const int k = ps * RPW + grp;
-                                *reinterpret_cast<uint4 *>(&stage[k * LDBS + sub * 8]) = raw[h][ps];
+                                *reinterpret_cast<typename E::raw_t *>(&stage[k * LDBS + sub * PL]) = raw[h][ps];
                             }
                             wave_sync();
 #pragma unroll
                             for (int x = 0; x < BPI; ++x) {
                                 if (h * BPI + x < nb) {
-                                    // lane i of a 16-lane block points at row i/4, halves 4(i%4)..+3 of the 32-byte row piece;
-                                    // the transposing read hands lane j the four rows' element j: B[4g+e][16n+j], e = 0..3
-                                    const uint16_t *src = &stage[(x * KB + 4 * g + (j >> 2)) * LDBS + 4 * (j & 3)];
+                                    if constexpr (F32) {
+                                        // k-step e of the 16x16x4 product takes column slot 4g + e from lane group g (the same
+                                        // slots as this lane's 4 A elements): B[4g+e][16n+j] is a plain 4-byte read
+                                        const float *src = &stage[(x * KB + 4 * g) * LDBS + j];
 #pragma unroll
-                                    for (int n = 0; n < NT; ++n) {
-                                        const short4_t r = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                                            (short4_t __attribute__((address_space(3))) *)(src + 16 * n));
-                                        acc[n] = mfma_k16<T>(af[h * BPI + x], r, acc[n]);
+                                        for (int n = 0; n < NT; ++n)
+#pragma unroll
+                                            for (int e = 0; e < 4; ++e)
+                                                acc[n] = __builtin_amdgcn_mfma_f32_16x16x4f32(af[h * BPI + x][e], src[e * LDBS + 16 * n], acc[n], 0, 0, 0);
+                                    } else {
+                                        // lane i of a 16-lane block points at row i/4, halves 4(i%4)..+3 of the 32-byte row piece;
+                                        // the transposing read hands lane j the four rows' element j: B[4g+e][16n+j], e = 0..3
+                                        const uint16_t *src = &stage[(x * KB + 4 * g + (j >> 2)) * LDBS + 4 * (j & 3)];
+#pragma unroll
+                                        for (int n = 0; n < NT; ++n) {
+                                            const short4_t r = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                                                (short4_t __attribute__((address_space(3))) *)(src + 16 * n));
+                                            acc[n] = mfma_k16<T>(af[h * BPI + x], r, acc[n]);
+                                        }
                                     }
                                 }
                             }
@@ -711,6 +731,70 @@ __device__ inline void sddmm_window_task(const SddmmArgs &a, const DevTask &t) {
 }
 
 // Residual nonzeros: LPN lanes per nonzero, NPW nonzeros per wave pass, U passes in one batch of loads.
+// The same for fp32 storage: v_mfma_f32_16x16x4_f32.  A lane (g, j) fetches X[row j][16t + 4g .. +3] and Y[col j][16t + 4g .. +3] as
+// 16-byte loads; k-step 4t + e of the product takes element e of both, i.e. lane group g contributes k = 16t + 4g + e to
+// that step - any assignment of the k's to steps and lane groups gives the same sum as long as both operands use it.
+template <int K>
+__device__ inline void sddmm_window_task_f32(const SddmmArgs &a, const DevTask &t) {
+    constexpr int KT = K / 16;               // 16-byte pieces per lane and operand row
+    constexpr int BB = K <= 32 ? 4 : K <= 64 ? 2 : 1;      // blocks per batch (register budget)
+    const int lane = threadIdx.x;
+    const int g = lane >> 4, j = lane & 15;
+    const float *X = reinterpret_cast<const float *>(a.X);
+    const float *Y = reinterpret_cast<const float *>(a.Y);
+    const int64_t xr = min((int64_t)t.id * W + j, a.M - 1);
+    float4_t xa[KT];
+#pragma unroll
+    for (int s = 0; s < KT; ++s) xa[s] = *reinterpret_cast<const float4_t *>(X + xr * K + 16 * s + 4 * g);
+    for (int b0 = t.blk_begin; b0 < t.blk_end; b0 += BB) {
+        int col[BB], vptr[BB];
+        uint64_t word[BB];
+#pragma unroll
+        for (int x = 0; x < BB; ++x) {
+            const int b = min(b0 + x, t.blk_end - 1);
+            col[x] = a.blk_cols[(int64_t)b * KB + j];
+            word[x] = a.blk_bitmap[(int64_t)b * 4 + g];          // rows 4g..4g+3 of the block, bit e*16 + j
+            vptr[x] = a.blk_valptr[b];
+        }
+        float4_t yb[BB][KT];
+#pragma unroll
+        for (int x = 0; x < BB; ++x) {
+            const int c = max(col[x], 0);                        // padding slot: no bit is set in its column
+#pragma unroll
+            for (int s = 0; s < KT; ++s) yb[x][s] = *reinterpret_cast<const float4_t *>(Y + (int64_t)c * K + 16 * s + 4 * g);
+        }
+        int slot[BB][4];
+#pragma unroll
+        for (int x = 0; x < BB; ++x) {
+            const int cnt = __popcll(word[x]);
+            const int c0 = __builtin_amdgcn_readlane(cnt, 0), c1 = __builtin_amdgcn_readlane(cnt, 16), c2 = __builtin_amdgcn_readlane(cnt, 32);
+            const int prefix = vptr[x] + (g > 0 ? c0 : 0) + (g > 1 ? c1 : 0) + (g > 2 ? c2 : 0);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) slot[x][e] = prefix + __popcll(word[x] & ((1ull << (e * 16 + j)) - 1ull));
+        }
+        uint2 pv[BB][4];
+#pragma unroll
+        for (int x = 0; x < BB; ++x)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) pv[x][e] = a.dense_pv[min(slot[x][e], a.n_dense - 1)];
+        float4_t d[BB];
+#pragma unroll
+        for (int x = 0; x < BB; ++x) {
+            d[x] = float4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int s = 0; s < KT; ++s)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) d[x] = __builtin_amdgcn_mfma_f32_16x16x4f32(xa[s][e], yb[x][s][e], d[x], 0, 0, 0);
+        }
+#pragma unroll
+        for (int x = 0; x < BB; ++x)
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (b0 + x < t.blk_end && (word[x] >> (e * 16 + j) & 1ull))
+                    a.out[(int32_t)pv[x][e].x] = (a.pattern_only ? 1.f : __uint_as_float(pv[x][e].y)) * d[x][e];
+    }
+}
+
 template <class T, int K>
 __device__ inline void sddmm_segment_task(const SddmmArgs &a, const DevTask &t) {
     using E = Elem<T>;
@@ -757,11 +841,10 @@ __device__ inline void sddmm_segment_task(const SddmmArgs &a, const DevTask &t) 
 template <class T, int K>
 __global__ __launch_bounds__(WAVE) void sddmm_task_kernel(SddmmArgs a) {
     const DevTask t = a.tasks[task_slot(blockIdx.x, a.tasks_per_die)];
-    if constexpr (!std::is_same<T, float>::value) {
-        if (t.kind == LIBRA_TASK_WINDOW) {
-            sddmm_window_task<T, K>(a, t);
-            return;
-        }
+    if (t.kind == LIBRA_TASK_WINDOW) {
+        if constexpr (std::is_same<T, float>::value) sddmm_window_task_f32<K>(a, t);
+        else sddmm_window_task<T, K>(a, t);
+        return;
     }
     sddmm_segment_task<T, K>(a, t);
 }
@@ -1302,7 +1385,6 @@ int sddmm_call(const libra_plan_t *P, const void *X, const void *Y, int32_t K, f
     if (sp.tasks.empty()) return LIBRA_OK;
     a.tasks_per_die = (int32_t)(((int64_t)sp.tasks.size() + LIBRA_XCDS - 1) / LIBRA_XCDS);
     const int64_t nt = (int64_t)a.tasks_per_die * LIBRA_XCDS;     // every slot of the table
-    if (sp.n_window_tasks > 0 && P->vdt == LIBRA_F32) return LIBRA_ERR_UNSUPPORTED;
     const dim3 grid((unsigned)nt), block(WAVE);
     if (P->vdt == LIBRA_F16) {
         switch (K) {

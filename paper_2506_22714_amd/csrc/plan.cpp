@@ -508,7 +508,6 @@ int libra::resolve_options(const libra_plan_opts_t *in, int vdt, Resolved &o) {
     }
     o.mode = z.mode;
     if (o.mode < 0 || o.mode > 2) return LIBRA_ERR_OPTION;
-    if (vdt == LIBRA_F32) o.mode = LIBRA_MODE_SCALAR_ONLY;
     o.W = z.window_rows ? z.window_rows : 16;
     o.KB = z.block_cols ? z.block_cols : 16;
     o.tau_spmm = z.spmm_min_vec_nnz ? z.spmm_min_vec_nnz : 3;

@@ -135,16 +135,19 @@ def test_tiny_config_spmm_and_sddmm(mode):
     check_sddmm(A, X, Y, out, TOL_F16)
 
 
-def test_tiny_config_fp32_mode():
+@pytest.mark.parametrize("mode", [lb.MODE_HYBRID, lb.MODE_DENSE_ONLY, lb.MODE_SCALAR_ONLY])
+def test_tiny_config_fp32_mode(mode):
     A = wl.tiny()
     v32 = A.val.astype(np.float32)
     B = wl.dense_normal(A.Kc, 32, seed=wl.BASE_SEED + 101, dtype=np.float32)
-    C, st = gpu_spmm(A, B, val=v32)
-    assert st["spmm_dense_nnz"] == 0
+    kw = dict(mode=mode, spmm_min_vec_nnz=2, sddmm_min_blk_nnz=17)          # both paths in use in the hybrid mode
+    C, st = gpu_spmm(A, B, val=v32, **kw)
+    assert (st["spmm_dense_nnz"] > 0) == (mode != lb.MODE_SCALAR_ONLY) and (st["spmm_res_nnz"] > 0) == (mode != lb.MODE_DENSE_ONLY)
     check_spmm(A, B, C, TOL_F32, val=v32)
     X = wl.dense_normal(A.M, 32, seed=wl.BASE_SEED + 102, dtype=np.float32)
     Y = wl.dense_normal(A.Kc, 32, seed=wl.BASE_SEED + 103, dtype=np.float32)
-    out, _ = gpu_sddmm(A, X, Y, val=v32)
+    out, st = gpu_sddmm(A, X, Y, val=v32, **kw)
+    assert (st["sddmm_dense_nnz"] > 0) == (mode != lb.MODE_SCALAR_ONLY)
     check_sddmm(A, X, Y, out, TOL_F32, val=v32)
 
 
@@ -164,8 +167,10 @@ def test_spmm_fp32_mode_widths(N):
     A = mixed_matrix(M=500, Kc=450, seed=4)
     v32 = A.val.astype(np.float32)
     B = wl.dense_normal(A.Kc, N, seed=N, dtype=np.float32)
-    C, _ = gpu_spmm(A, B, val=v32, cs=64)
-    check_spmm(A, B, C, TOL_F32, val=v32)
+    for mode in (lb.MODE_HYBRID, lb.MODE_DENSE_ONLY, lb.MODE_SCALAR_ONLY):
+        C, st = gpu_spmm(A, B, val=v32, cs=64, ts=2, mode=mode)
+        assert (st["spmm_dense_nnz"] > 0) == (mode != lb.MODE_SCALAR_ONLY)
+        check_spmm(A, B, C, TOL_F32, val=v32)
 
 
 @pytest.mark.parametrize("K", [32, 64, 128])
@@ -177,8 +182,10 @@ def test_sddmm_feature_widths_on_mixed_matrix(K):
     assert st["sddmm_dense_nnz"] > 0 and st["sddmm_res_nnz"] > 0
     check_sddmm(A, X, Y, out, TOL_F16)
     v32 = A.val.astype(np.float32)
-    out32, _ = gpu_sddmm(A, X.astype(np.float32), Y.astype(np.float32), val=v32)
-    check_sddmm(A, X.astype(np.float32), Y.astype(np.float32), out32, TOL_F32, val=v32)
+    for mode in (lb.MODE_HYBRID, lb.MODE_DENSE_ONLY, lb.MODE_SCALAR_ONLY):
+        out32, st32 = gpu_sddmm(A, X.astype(np.float32), Y.astype(np.float32), val=v32, ts=2, sddmm_min_blk_nnz=24, mode=mode)
+        assert (st32["sddmm_dense_nnz"] > 0) == (mode != lb.MODE_SCALAR_ONLY)
+        check_sddmm(A, X.astype(np.float32), Y.astype(np.float32), out32, TOL_F32, val=v32)
 
 
 def test_mode_equivalence_over_thresholds():

@@ -201,13 +201,22 @@ def test_plan_does_not_depend_on_thread_count_and_orders_heaviest_first():
     assert np.all(np.diff(win) >= 0)
 
 
-def test_fp32_values_force_the_scalar_path():
-    A = wl.random_pattern(64, 64, 0.2, seed=3)
-    p = lb.Plan.from_csr(A, val=A.val.astype(np.float32))
-    st = p.stats()
-    assert st["spmm_dense_nnz"] == 0 and st["sddmm_dense_nnz"] == 0 and st["spmm_res_nnz"] == A.nnz
-    ex = p.export(0)
-    assert ex["res_val"].dtype == np.float32 and np.array_equal(ex["res_val"], A.val.astype(np.float32))
+def test_fp32_values_plan_like_16_bit_values_and_are_carried_whole():
+    """The split rule looks at the pattern only: fp32 values give the same blocks, bitmaps and tasks as fp16 ones (the dense
+    tiles then run on the fp32 matrix instruction), and every value arrives unrounded on its path."""
+    A = wl.make("community", small=True)
+    v32 = (A.val.astype(np.float32) * np.float32(1.0009765625) + np.float32(1e-4)).astype(np.float32)   # not fp16 numbers
+    p16, p32 = lb.Plan.from_csr(A), lb.Plan.from_csr(A, val=v32)
+    st = p32.stats()
+    assert st["spmm_dense_nnz"] > 0 and st["sddmm_dense_nnz"] > 0 and st["spmm_res_nnz"] > 0
+    for which in (0, 1):
+        a, b = p16.export(which), p32.export(which)
+        for k in ("tasks", "blk_cols", "blk_bitmap", "blk_valptr", "dense_perm", "res_perm", "res_row", "res_col"):
+            assert np.array_equal(a[k], b[k]), (which, k)
+        assert b["dense_val"].dtype == np.float32 and b["res_val"].dtype == np.float32
+        assert np.array_equal(b["dense_val"], v32[b["dense_perm"]]) and np.array_equal(b["res_val"], v32[b["res_perm"]])
+    sc = lb.Plan.from_csr(A, val=v32, mode=lb.MODE_SCALAR_ONLY).stats()
+    assert sc["spmm_dense_nnz"] == 0 and sc["sddmm_dense_nnz"] == 0 and sc["spmm_res_nnz"] == A.nnz
 
 
 def test_bfloat16_plan_has_the_same_structure_and_carries_the_bits():
