@@ -33,13 +33,13 @@ HBM_PEAK_GBS = 8000.0
 MEASURED_TRAFFIC_BYTES = {("powerlaw", 128): int((2.0 * 104_040 + 1.0 * 75_444) * 1024)}
 
 
-def spmm_algorithmic_bytes(A, N: int, kref: int) -> int:
-    """Every array of the method once: col + val, rowptr, referenced rows of B, C."""
-    return A.nnz * (4 + 2) + 4 * (A.M + 1) + kref * N * 2 + A.M * N * 4
+def spmm_algorithmic_bytes(A, N: int, kref: int, es: int = 2) -> int:
+    """Every array of the method once: col + val, rowptr, referenced rows of B, C (es = bytes per stored value)."""
+    return A.nnz * (4 + es) + 4 * (A.M + 1) + kref * N * es + A.M * N * 4
 
 
-def sddmm_algorithmic_bytes(A, K: int, mref: int, kref: int) -> int:
-    return A.nnz * (4 + 2 + 4) + 4 * (A.M + 1) + (mref + kref) * K * 2
+def sddmm_algorithmic_bytes(A, K: int, mref: int, kref: int, es: int = 2) -> int:
+    return A.nnz * (4 + es + 4) + 4 * (A.M + 1) + (mref + kref) * K * es
 
 
 def main() -> int:
@@ -65,7 +65,7 @@ def main() -> int:
     ap.add_argument("--host-plan", action="store_true",
                     help="run the compute calls on the host-built, uploaded plan (default: on the plan the device planner "
                          "wrote; the two plans are identical and both planners are timed either way)")
-    ap.add_argument("--dtype", default="f16", choices=["f16", "bf16"], help="storage type of A's values and the dense operands")
+    ap.add_argument("--dtype", default="f16", choices=["f16", "bf16", "f32"], help="storage type of A's values and the dense operands")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run only a 1 GiB device copy (5 times): the known-size kernel that scales the rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE readings")
@@ -102,8 +102,11 @@ def main() -> int:
     X = wl.dense_normal(A.M, K, seed=wl.BASE_SEED + 202)
     Y = wl.dense_normal(A.Kc, K, seed=wl.BASE_SEED + 203)
 
-    bf16 = args.dtype == "bf16"
-    val = wl.to_bf16_bits(A.val.astype(np.float32)) if bf16 else None
+    bf16, f32 = args.dtype == "bf16", args.dtype == "f32"
+    es = 4 if f32 else 2
+    if f32:
+        B, X, Y = (a.astype(np.float32) for a in (B, X, Y))
+    val = wl.to_bf16_bits(A.val.astype(np.float32)) if bf16 else A.val.astype(np.float32) if f32 else None
     opts = dict(mode=args.mode, spmm_min_vec_nnz=args.tau_spmm, sddmm_min_blk_nnz=args.tau_sddmm, ts=args.ts, cs=args.cs,
                 flags=(lb.FLAG_NATURAL_ORDER if args.natural_order else 0) | (lb.FLAG_XCD_ORDER if args.xcd_order else 0)
                 | (lb.FLAG_NO_XCD_ORDER if args.no_xcd_order else 0) | (lb.FLAG_SEGMENTS_BY_COST if args.segments_by_cost else 0)
@@ -118,7 +121,7 @@ def main() -> int:
     torch.cuda.synchronize()
     upload_s = time.perf_counter() - t0
     rp_d, col_d = torch.from_numpy(A.rowptr.astype(np.int32)).cuda(), torch.from_numpy(A.col.astype(np.int32)).cuda()
-    val_d = (torch.from_numpy(val.view(np.int16)).cuda().view(torch.bfloat16) if bf16 else torch.from_numpy(A.val).cuda())
+    val_d = (torch.from_numpy(val.view(np.int16)).cuda().view(torch.bfloat16) if bf16 else torch.from_numpy(A.val if val is None else val).cuda())
     dev_s = []
     dev_plan = None
     for _ in range(3):                      # the first call pays for module loading and the allocator
@@ -206,11 +209,11 @@ def main() -> int:
 
     kref = int(np.unique(A.col).size)
     mref = int((np.diff(A.rowptr) > 0).sum())
-    bytes_spmm = spmm_algorithmic_bytes(A, N, kref)
-    bytes_sddmm = sddmm_algorithmic_bytes(A, K, mref, kref)
+    bytes_spmm = spmm_algorithmic_bytes(A, N, kref, es)
+    bytes_sddmm = sddmm_algorithmic_bytes(A, K, mref, kref, es)
     spmm_avg_s = float(spmm_ms.mean()) * 1e-3
     achieved = bytes_spmm / spmm_avg_s / 1e9
-    default_cfg = (not args.small and not bf16 and args.mode == 0 and not (args.tau_spmm or args.tau_sddmm or args.ts or args.cs)
+    default_cfg = (not args.small and args.dtype == "f16" and args.mode == 0 and not (args.tau_spmm or args.tau_sddmm or args.ts or args.cs)
                    and not args.natural_order and not args.xcd_order and not args.no_xcd_order
                    and not args.segments_by_cost and not args.two_kernels)
     traffic = MEASURED_TRAFFIC_BYTES.get((args.workload, N)) if default_cfg else None
@@ -255,7 +258,7 @@ def main() -> int:
                  "xcd_order": st["xcd_order"]},
     }
 
-    if args.workload == "gat" and N == K and not bf16:
+    if args.workload == "gat" and N == K and args.dtype == "f16":
         # the attention head of this configuration as a whole: scores (SDDMM) -> row softmax -> new values into the SpMM
         # arrays -> aggregation (SpMM with B = Y); outside the timed region, the plan's values are restored afterwards
         alpha = torch.empty(A.nnz, dtype=torch.float16, device="cuda")
