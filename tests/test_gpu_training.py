@@ -138,6 +138,35 @@ def test_spmm_and_sddmm_gradients_match_the_formulas():
     sm.close()
 
 
+def test_fp32_gradients_run_on_both_paths():
+    """The same chain rule with fp32 storage (dense tiles on the fp32 matrix instruction): nothing is rounded on the way,
+    so every gradient meets the derived bound directly."""
+    from paper_2506_22714_amd import autograd as ag
+    A = graft(None)
+    At, order = transpose_host(A)
+    N = 64
+    sm = ag.SparseMatrix(A.M, A.Kc, dev(A.rowptr.astype(np.int32)), dev(A.col.astype(np.int32)), dtype=torch.float32, cs=50)
+    st = sm.plan.stats()
+    assert st["spmm_dense_nnz"] > 0 and st["spmm_res_nnz"] > 0
+    v32 = A.val.astype(np.float32)
+    vals = dev(v32).requires_grad_()
+    Bn = wl.dense_normal(A.Kc, N, seed=11, dtype=np.float32)
+    B = dev(Bn).requires_grad_()
+    C = ag.spmm(sm, vals, B)
+    deg = np.diff(A.rowptr).astype(np.float64)
+    degt = np.diff(At.rowptr).astype(np.float64)
+    tol = lambda d: 16 * np.sqrt(d) * 2.0 ** -24
+    ref, S = oracle.spmm(A.rowptr, A.col, v32, Bn)
+    assert oracle.graded_error(C.detach().cpu().numpy(), ref, S, deg[:, None]) <= tol(deg.max())
+    dCn = wl.dense_normal(A.M, N, seed=12, dtype=np.float32)
+    C.backward(dev(dCn))
+    ref, S = oracle.spmm(At.rowptr, At.col, v32[order], dCn)                       # dB = A^T dC
+    assert oracle.graded_error(B.grad.cpu().numpy(), ref, S, degt[:, None]) <= tol(degt.max())
+    ref, S = oracle.sddmm(A.rowptr, A.col, np.ones(A.nnz, dtype=np.float32), dCn, Bn)    # dA_p = <dC_i, B_j>
+    assert oracle.graded_error(vals.grad.cpu().numpy(), ref, S, N) <= tol(N)
+    sm.close()
+
+
 def train_layers(kind, n_layers, steps=12):
     """Optimiser steps of an n-layer graph network on a synthetic power-law graph; returns the losses.  `gcn`: every layer
     is SpMM with the fixed symmetric normalisation 1/sqrt(d_i d_j) (Section 5.5's GCN); `agnn`: every layer is SDDMM ->
