@@ -254,6 +254,7 @@ template <> __device__ inline bf16_t to_storage<bf16_t>(float x) {
 
 // Workgroup b of a launch runs on die b mod 8, so the records of the tasks that one die runs are stored next to each
 // other: a 128-byte line of the table then serves four consecutive workgroups of one die instead of four dies.
+static_assert(LIBRA_XCDS == 8, "task_slot divides by the number of dies with a shift");
 __device__ inline int64_t task_slot(unsigned b, int per_die) { return (int64_t)(b & (LIBRA_XCDS - 1)) * per_die + (b >> 3); }
 
 // ---------------------------------------------------------------------------------------
