@@ -53,6 +53,7 @@ struct SpmmArgs {
     float *C;
     int64_t ldb, ldc;
     int32_t tasks_per_die;  // the table holds die k's tasks (dispatch positions k, k + 8, ...) contiguously from k * tasks_per_die on
+    int32_t pieces;         // the launch covers `pieces` adjacent column pieces of N features each: every task runs once per piece
     int32_t phase;          // 0: a task does all its work; 1: dense blocks only; 2: residual nonzeros only, added to what phase 1 wrote
 };
 
@@ -305,7 +306,12 @@ __global__ __launch_bounds__(WAVE) __attribute__((amdgpu_waves_per_eu(N >= 128 ?
     __shared__ __attribute__((aligned(16))) uint64_t bm_lds[DENSE ? BCAP * 4 : 2];
     float *tile = reinterpret_cast<float *>(smem);
 
-    const DevTask t = a.tasks[task_slot(blockIdx.x, a.tasks_per_die)];
+    // workgroup b: die b mod 8, then the pieces of one task next to each other (they read the same plan data through
+    // the same L2), then the die's next task
+    const unsigned round = blockIdx.x >> 3, piece = round % (unsigned)a.pieces;
+    const DevTask t = a.tasks[(int64_t)(blockIdx.x & (LIBRA_XCDS - 1)) * a.tasks_per_die + round / (unsigned)a.pieces];
+    const char *Bp = reinterpret_cast<const char *>(a.B) + (size_t)piece * N * sizeof(T);
+    float *Cp = a.C + (size_t)piece * N;
     const int lane = threadIdx.x;
     const int sub = lane % LPR;              // which PL-wide piece of a row
     const int grp = lane / LPR;              // which lane group
@@ -404,7 +410,7 @@ __global__ __launch_bounds__(WAVE) __attribute__((amdgpu_waves_per_eu(N >= 128 ?
                             // (so that it keeps the fetch outside any branch)
                             uint32_t keep = (k < nb * KB && c >= 0) ? 0xffffffffu : 0u;
                             asm volatile("" : "+v"(keep));
-                            raw[h][ps] = E::load_row(a.B, keep ? c : 0, ldb_bytes, sub);
+                            raw[h][ps] = E::load_row(Bp, keep ? c : 0, ldb_bytes, sub);
                             E::mask(raw[h][ps], keep);
                         }
                     // ... and this lane's 4 A elements (row j, slots 4g..4g+3) of each block, decoded from its bitmap
@@ -550,7 +556,7 @@ __global__ __launch_bounds__(WAVE) __attribute__((amdgpu_waves_per_eu(N >= 128 ?
             // harmless and whose product is never formed
             E::template lds_batch<U>(ent_lds + q, en);
 #pragma unroll
-            for (int u = 0; u < U; ++u) raw[u] = E::load_row(a.B, en[u].col, ldb_bytes, sub);
+            for (int u = 0; u < U; ++u) raw[u] = E::load_row(Bp, en[u].col, ldb_bytes, sub);
             bool one_row = full;
 #pragma unroll
             for (int u = 1; u < U; ++u) one_row = one_row && en[u].row == en[0].row;
@@ -597,7 +603,7 @@ __global__ __launch_bounds__(WAVE) __attribute__((amdgpu_waves_per_eu(N >= 128 ?
 
     // ---- write the tile once: a wave pass covers RPP rows, LPF lanes per row ----
     {
-        float *cbase = a.C + (int64_t)t.id * W * a.ldc;
+        float *cbase = Cp + (int64_t)t.id * W * a.ldc;
 #pragma unroll
         for (int r0 = 0; r0 < W; r0 += RPP) {
             const int r = r0 + rr;
@@ -1053,21 +1059,23 @@ inline int hip_rc(hipError_t e) { return e == hipSuccess ? LIBRA_OK : LIBRA_ERR_
 template <class T, int N>
 int launch_spmm(const SpmmArgs &a, int64_t ntasks, hipStream_t s) {
     if (ntasks == 0) return LIBRA_OK;
-    hipLaunchKernelGGL((spmm_task_kernel<T, N>), dim3((unsigned)ntasks), dim3(WAVE), 0, s, a);
+    hipLaunchKernelGGL((spmm_task_kernel<T, N>), dim3((unsigned)(ntasks * a.pieces)), dim3(WAVE), 0, s, a);
     return hip_rc(hipGetLastError());
 }
 
 int spmm_launch(const libra_plan_t *P, const SpmmArgs &a, int n, int64_t nt, hipStream_t s);
 
-int spmm_piece(const libra_plan_t *P, const void *B, int n, int64_t ldb, float *C, int64_t ldc, hipStream_t s) {
+// `pieces` adjacent pieces of n columns each, one launch
+int spmm_piece(const libra_plan_t *P, const void *B, int n, int pieces, int64_t ldb, float *C, int64_t ldc, hipStream_t s) {
     const SubPlan &sp = P->spmm;
     const int64_t per_die = ((int64_t)sp.tasks.size() + LIBRA_XCDS - 1) / LIBRA_XCDS;
     SpmmArgs a{sp.dev.tasks, sp.dev.blk_cols, sp.dev.blk_bitmap, sp.dev.blk_valptr, sp.dev.dense_val,
-               sp.dev.res_ent, B, C, ldb, ldc, (int32_t)per_die, 0};
+               sp.dev.res_ent, B, C, ldb, ldc, (int32_t)per_die, pieces, 0};
     if (sp.n.zero_rows) {
-        const int64_t total = sp.n.zero_rows * (n / 4);
+        const int n4 = n * pieces / 4;
+        const int64_t total = sp.n.zero_rows * n4;
         const unsigned blocks = (unsigned)std::min<int64_t>((total + 255) / 256, 65536);
-        hipLaunchKernelGGL(zero_rows_kernel, dim3(blocks), dim3(256), 0, s, sp.dev.zero_rows, sp.n.zero_rows, C, ldc, n / 4);
+        hipLaunchKernelGGL(zero_rows_kernel, dim3(blocks), dim3(256), 0, s, sp.dev.zero_rows, sp.n.zero_rows, C, ldc, n4);
         if (hipGetLastError() != hipSuccess) return LIBRA_ERR_HIP;
     }
     const int64_t nt = per_die * LIBRA_XCDS;         // every slot of the table (the last few may hold empty tasks)
@@ -1352,9 +1360,14 @@ extern "C" int libra_spmm(const libra_plan_t *P, const void *B, int32_t N, int64
     for (int n0 = 0; n0 < N;) {
         int n = 128;
         while (n > N - n0) n >>= 1;
-        int rc = spmm_piece(P, (const char *)B + (size_t)n0 * esz, n, ldb, C + n0, ldc, s);
+        // The 128-column pieces of a wide operand go into one launch when the plan keeps neighbouring windows on one die
+        // (matrices whose windows share columns: the pieces of a task then share the plan's data and the launch has one
+        // tail; community N=256: 535 -> 508 us).  Elsewhere they run one after the other: together they would compete for
+        // the L2 with twice the rows of B (power-law N=512: 267 us apart, 354 us together).
+        const int pieces = (n == 128 && P->o.xcd_order == 1) ? (N - n0) / 128 : 1;
+        int rc = spmm_piece(P, (const char *)B + (size_t)n0 * esz, n, pieces, ldb, C + n0, ldc, s);
         if (rc != LIBRA_OK) return rc;
-        n0 += n;
+        n0 += n * pieces;
     }
     return LIBRA_OK;
 }

@@ -156,10 +156,13 @@ def test_tiny_config_fp32_mode(mode):
 def test_spmm_feature_widths_on_mixed_matrix(N):
     A = mixed_matrix()
     B = wl.dense_normal(A.Kc, N, seed=N)
-    C, st = gpu_spmm(A, B, ts=2, cs=48)
-    assert st["spmm_split_rows"] >= 4 and st["spmm_chunk_tasks"] > 8 and st["spmm_zero_rows"] > 0
-    assert st["spmm_dense_nnz"] > 0 and st["spmm_res_nnz"] > 0
-    check_spmm(A, B, C, TOL_F16)
+    # with the die-aware window order the 128-column pieces of a wide operand share one launch, without it they run in turn
+    for flags in (lb.FLAG_XCD_ORDER, lb.FLAG_NO_XCD_ORDER):
+        C, st = gpu_spmm(A, B, ts=2, cs=48, flags=flags)
+        assert st["xcd_order"] == (flags == lb.FLAG_XCD_ORDER)
+        assert st["spmm_split_rows"] >= 4 and st["spmm_chunk_tasks"] > 8 and st["spmm_zero_rows"] > 0
+        assert st["spmm_dense_nnz"] > 0 and st["spmm_res_nnz"] > 0
+        check_spmm(A, B, C, TOL_F16)
 
 
 @pytest.mark.parametrize("N", [16, 48, 128])
