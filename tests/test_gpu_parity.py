@@ -152,7 +152,7 @@ def test_tiny_config_fp32_mode(mode):
 
 
 # ------------------------------------------------------- shapes and splitting
-@pytest.mark.parametrize("N", [32, 64, 96, 128, 256, 512])
+@pytest.mark.parametrize("N", [32, 64, 96, 128, 160, 256, 384, 512])
 def test_spmm_feature_widths_on_mixed_matrix(N):
     A = mixed_matrix()
     B = wl.dense_normal(A.Kc, N, seed=N)
