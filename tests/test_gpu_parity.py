@@ -436,6 +436,42 @@ def test_one_plan_on_two_streams():
     p.close()
 
 
+def test_compute_calls_can_be_captured_in_a_graph():
+    """The compute calls only launch kernels on the caller's stream (rows with several writers are cleared by a kernel, not
+    by a memset; nothing is allocated), so a step can be captured once and replayed: every replay, with eager work between
+    the replays, gives the eager result."""
+    A = wl.make("powerlaw", small=True)
+    p = lb.Plan.from_csr(A, cs=32).upload()
+    assert p.stats()["spmm_zero_rows"] > 0
+    B = dev(wl.dense_small_int(A.Kc, 64, seed=60))              # integer-valued inputs: every order of additions is exact
+    X, Y = dev(wl.dense_small_int(A.M, 32, seed=61)), dev(wl.dense_small_int(A.Kc, 32, seed=62))
+    p.set_values(dev(np.ones(A.nnz, dtype=np.float16)))
+    C_ref, out_ref = p.spmm(B), p.sddmm(X, Y)
+    C, out = torch.empty_like(C_ref), torch.empty_like(out_ref)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()                                   # default priority
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        p.spmm(B, out=C)                                         # warm-up on the capture stream
+        p.sddmm(X, Y, out=out)
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            p.spmm(B, out=C)
+            p.sddmm(X, Y, out=out)
+    torch.cuda.current_stream().wait_stream(side)
+    for rep in range(4):
+        C.fill_(float("nan"))
+        out.fill_(float("nan"))
+        scratch = p.spmm(B)                                      # eager work of the same library between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(C, C_ref) and torch.equal(out, out_ref), rep
+        assert torch.equal(scratch, C_ref)
+    p.close()
+
+
 # ------------------------------------------------------------- bfloat16
 def dev_bf16(bits):
     return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda().view(torch.bfloat16)
