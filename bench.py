@@ -154,9 +154,9 @@ def main() -> int:
         step()
     torch.cuda.synchronize()
     # Per-operator durations come from events on the launch stream inside the timed region, on every `stride`-th step
-    # only: an event record keeps the next kernel from starting until the previous one has retired (about 5 us of idle
+    # (every 16th of the default 200) only: an event record keeps the next kernel from starting until the previous one has retired (about 5 us of idle
     # GPU each on this machine), which would otherwise be a tenth of every step of the headline workload.
-    stride = 8 if args.steps >= 64 else 4 if args.steps >= 8 else 1
+    stride = 16 if args.steps >= 128 else 8 if args.steps >= 64 else 4 if args.steps >= 8 else 1
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range((args.steps + stride - 1) // stride)]
     torch.cuda.synchronize()
     t_start = time.perf_counter()
