@@ -62,7 +62,8 @@ template <class T> struct Elem;
 template <> struct Elem<half_t> {
     static constexpr int PER_LANE = 8;                   // 16 bytes
     typedef uint4 raw_t;
-    typedef ResEnt16 ent_t;
+    typedef ResEnt16 ent_t;                              // a residual entry in registers ...
+    typedef ResEnt16 stored_t;                           // ... and in memory
     __device__ static raw_t load(const void *base, int64_t elem_off) {
         return *reinterpret_cast<const uint4 *>(reinterpret_cast<const half_t *>(base) + elem_off);
     }
@@ -163,7 +164,8 @@ template <> struct Elem<bf16_t> : Elem<half_t> {
 template <> struct Elem<float> {
     static constexpr int PER_LANE = 4;                   // 16 bytes
     typedef float4_t raw_t;
-    typedef ResEnt32 ent_t;
+    struct ent_t { int32_t col; float val; int32_t row; };
+    typedef ResEnt32 stored_t;
     __device__ static raw_t load(const void *base, int64_t elem_off) {
         return *reinterpret_cast<const float4_t *>(reinterpret_cast<const float *>(base) + elem_off);
     }
@@ -176,33 +178,34 @@ template <> struct Elem<float> {
         for (int e = 0; e < 4; ++e) s = fmaf(x[e], y[e], s);
         return s;
     }
-    __device__ static ent_t load_ent(const void *base, int64_t i) {
-        const float4_t u = reinterpret_cast<const float4_t *>(base)[i];
-        ent_t e;
-        e.col = __float_as_int(u[0]);
-        e.val = u[1];
-        e.row = __float_as_int(u[2]);
-        e.pad = 0;
-        return e;
+    __device__ static stored_t load_ent(const void *base, int64_t i) {
+        const uint2 u = reinterpret_cast<const uint2 *>(base)[i];
+        return stored_t{u.x, __uint_as_float(u.y)};
     }
     __device__ static float ent_val(const ent_t &e) { return e.val; }
-    __device__ static ent_t lds_ent(const ent_t *lds, int i) {
-        const float4_t u = reinterpret_cast<const float4_t *>(lds)[i];
-        ent_t e;
-        e.col = __float_as_int(u[0]);
-        e.val = u[1];
-        e.row = __float_as_int(u[2]);
-        e.pad = 0;
-        return e;
+    __device__ static ent_t unpack(uint32_t col_row, uint32_t val_bits) {
+        return ent_t{(int32_t)(col_row & RES32_COL_MASK), __uint_as_float(val_bits), (int32_t)(col_row >> RES32_ROW_SHIFT)};
+    }
+    __device__ static ent_t lds_ent(const stored_t *lds, int i) {
+        const uint2 u = reinterpret_cast<const uint2 *>(lds)[i];
+        return unpack(u.x, u.y);
     }
     __device__ static void mask(raw_t &r, uint32_t keep) {
 #pragma unroll
         for (int e = 0; e < 4; ++e) r[e] = __uint_as_float(__float_as_uint(r[e]) & keep);
     }
+    // U consecutive entries from a 16-byte aligned address, two per 16-byte read
     template <int U>
-    __device__ static void lds_batch(const ent_t *lds, ent_t (&en)[U]) {
+    __device__ static void lds_batch(const stored_t *lds, ent_t (&en)[U]) {
+        static_assert(U % 2 == 0, "two 8-byte entries per 16-byte read");
+        uint4 v[U / 2];
 #pragma unroll
-        for (int u = 0; u < U; ++u) en[u] = lds_ent(lds, u);
+        for (int k = 0; k < U / 2; ++k) v[k] = reinterpret_cast<const uint4 *>(lds)[k];
+#pragma unroll
+        for (int k = 0; k < U / 2; ++k) {
+            en[2 * k] = unpack(v[k].x, v[k].y);
+            en[2 * k + 1] = unpack(v[k].z, v[k].w);
+        }
     }
     __device__ static raw_t load_row(const void *base, int32_t col, uint32_t ld_bytes, int sub) {
         const char *p = reinterpret_cast<const char *>(base) + ((uint64_t)(uint32_t)col * ld_bytes + (uint32_t)sub * 16u);
@@ -284,6 +287,7 @@ template <class T, int N>
 __global__ __launch_bounds__(WAVE) __attribute__((amdgpu_waves_per_eu(N >= 128 ? 4 : 6))) void spmm_task_kernel(SpmmArgs a) {
     using E = Elem<T>;
     typedef typename E::ent_t ent_t;
+    typedef typename E::stored_t stored_t;
     constexpr bool F32 = std::is_same<T, float>::value;        // fp32 storage: v_mfma_f32_16x16x4_f32, operands straight from the stage
     constexpr bool DENSE = true;
     constexpr int PL = E::PER_LANE;          // elements of a row per lane
@@ -301,7 +305,7 @@ __global__ __launch_bounds__(WAVE) __attribute__((amdgpu_waves_per_eu(N >= 128 ?
     constexpr int U = N >= 128 ? SPMM_U : SPMM_U / 2;   // B-row fetches in flight per lane group (narrow rows: fewer, for more waves)
     // the B stage (dense phase) and the C tile (afterwards) share the same LDS bytes
     __shared__ __attribute__((aligned(16))) unsigned char smem[SMEM];
-    __shared__ __attribute__((aligned(16))) ent_t ent_lds[ECAP];
+    __shared__ __attribute__((aligned(16))) stored_t ent_lds[ECAP];
     __shared__ __attribute__((aligned(16))) int32_t cols_lds[DENSE ? BCAP * KB : 4];
     __shared__ __attribute__((aligned(16))) uint64_t bm_lds[DENSE ? BCAP * 4 : 2];
     float *tile = reinterpret_cast<float *>(smem);
@@ -334,8 +338,8 @@ __global__ __launch_bounds__(WAVE) __attribute__((amdgpu_waves_per_eu(N >= 128 ?
     // First round of each kind of metadata, all loads in flight together, then the LDS writes.
     {
         const int nE = min(L, ECAP), nb = min(nblk, BCAP);
-        const ent_t *src = reinterpret_cast<const ent_t *>(a.res_ent) + t.res_begin;
-        ent_t tmp[ECAP / WAVE];
+        const stored_t *src = reinterpret_cast<const stored_t *>(a.res_ent) + t.res_begin;
+        stored_t tmp[ECAP / WAVE];
 #pragma unroll
         for (int k = 0; k < ECAP / WAVE; ++k) tmp[k] = E::load_ent(src, max(min(k * WAVE + lane, nE - 1), 0));
         if constexpr (DENSE) {
@@ -508,9 +512,9 @@ __global__ __launch_bounds__(WAVE) __attribute__((amdgpu_waves_per_eu(N >= 128 ?
         const int nE = min(ECAP, L - e0);
         // the next round's entries go in flight now and wait in registers until this round is done
         const int nE_next = min(ECAP, L - e0 - ECAP);
-        ent_t next_ent[ECAP / WAVE];
+        stored_t next_ent[ECAP / WAVE];
         if (nE_next > 0) {
-            const ent_t *src = reinterpret_cast<const ent_t *>(a.res_ent) + t.res_begin + e0 + ECAP;
+            const stored_t *src = reinterpret_cast<const stored_t *>(a.res_ent) + t.res_begin + e0 + ECAP;
 #pragma unroll
             for (int k = 0; k < ECAP / WAVE; ++k) next_ent[k] = E::load_ent(src, min(k * WAVE + lane, nE_next - 1));
         }
@@ -1176,15 +1180,14 @@ struct Staging {
 };
 
 // Record layouts written on the device when the arrays come from the device planner.
+__device__ inline ResEnt16 make_entry(int32_t col, uint16_t val, int row_in_window) { return ResEnt16{col, val, (uint16_t)row_in_window}; }
+__device__ inline ResEnt32 make_entry(int32_t col, float val, int row_in_window) {
+    return ResEnt32{(uint32_t)col | (uint32_t)row_in_window << RES32_ROW_SHIFT, val};
+}
 template <class ENT, class V>
 __global__ __launch_bounds__(256) void pack_spmm_entries_kernel(const int32_t *col, const V *val, const int32_t *row, int64_t n, ENT *out) {
-    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
-        ENT e{};
-        e.col = col[i];
-        e.val = val[i];
-        e.row = (decltype(e.row))(row[i] % W);
-        out[i] = e;
-    }
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x)
+        out[i] = make_entry(col[i], val[i], row[i] % W);
 }
 template <class V>
 __global__ __launch_bounds__(256) void pack_sddmm_entries_kernel(const int32_t *row, const int32_t *col, const int32_t *perm, const V *val, int64_t n, SdEnt *out) {
@@ -1226,7 +1229,8 @@ void layout(libra_plan_t *P, Uploader &u, Staging *st, const DeviceSource *da, c
         } else {
             st->ent32.resize(nres);
             const float *v = reinterpret_cast<const float *>(sa.res_val.data());
-            for (size_t i = 0; i < nres; ++i) st->ent32[i] = {sa.res_col[i], v[i], sa.res_row[i] % Wp, 0};
+            for (size_t i = 0; i < nres; ++i)
+                st->ent32[i] = {(uint32_t)sa.res_col[i] | (uint32_t)(sa.res_row[i] % Wp) << RES32_ROW_SHIFT, v[i]};
         }
     }
     if (f16) u.put(from_host ? (const void *)st->ent16.data() : nullptr, nullptr, nres * sizeof(ResEnt16), sa.dev.res_ent);
@@ -1273,6 +1277,7 @@ size_t libra::plan_buffer_bytes(const libra_plan_t *plan) {
 int libra::adopt_device_arrays(libra_plan_t *P, const DeviceSource &da, const DeviceSource &dd, void *dev_buf, size_t bytes, void *stream) {
     if (!dev_buf) return LIBRA_ERR_NULL;
     if (bytes < plan_buffer_bytes(P) || ((uintptr_t)dev_buf & 255)) return LIBRA_ERR_BUFFER;
+    if (P->vdt == LIBRA_F32 && P->Kc > (int64_t)RES32_COL_MASK + 1) return LIBRA_ERR_UNSUPPORTED;    // see ResEnt32
     hipStream_t s = (hipStream_t)stream;
     try {
         Staging st;
@@ -1327,6 +1332,7 @@ extern "C" int libra_plan_upload(libra_plan_t *plan, void *dev_buf, size_t bytes
     size_t need = 0;
     libra_plan_device_bytes(plan, &need);
     if (bytes < need || ((uintptr_t)dev_buf & 255)) return LIBRA_ERR_BUFFER;
+    if (plan->vdt == LIBRA_F32 && plan->Kc > (int64_t)RES32_COL_MASK + 1) return LIBRA_ERR_UNSUPPORTED;      // see ResEnt32
     try {
         Staging st;
         Uploader u;

@@ -39,12 +39,13 @@ struct ResEnt16 {
     uint16_t val;               // IEEE binary16 bits
     uint16_t row;               // row inside the window
 };
-// Same, fp32 values: 16 bytes.
+// Same, fp32 values: also 8 bytes.  The first word holds the column in its low RES32_ROW_SHIFT bits and the row inside
+// the window above them, so such a plan is limited to 2^27 columns.
+constexpr int RES32_ROW_SHIFT = 27;                             // windows of up to 32 rows
+constexpr uint32_t RES32_COL_MASK = (1u << RES32_ROW_SHIFT) - 1u;
 struct ResEnt32 {
-    int32_t col;
+    uint32_t col_row;
     float val;
-    int32_t row;
-    int32_t pad;
 };
 // Residual entry of the SDDMM sub-plan: 16 bytes.
 struct SdEnt {
