@@ -214,9 +214,6 @@ template <> struct Elem<float> {
     __device__ static float word_val(uint32_t bits) { return __uint_as_float(bits); }
 };
 
-__device__ inline void lds_add(float *p, float v) {
-    __hip_atomic_fetch_add(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-}
 __device__ inline void global_add(float *p, float v) {
     __hip_atomic_fetch_add(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }

@@ -49,23 +49,27 @@ extern "C" int libra_probe_coissue(int iters, float *sink_dev, float times_us[3]
     if (!sink_dev || !times_us) return LIBRA_ERR_NULL;
     if (iters < 1 || iters > (1 << 24)) return LIBRA_ERR_SHAPE;
     hipStream_t s = (hipStream_t)stream;
-    hipEvent_t e0, e1;
-    if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) return LIBRA_ERR_HIP;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    if (hipEventCreate(&e0) != hipSuccess) return LIBRA_ERR_HIP;
+    if (hipEventCreate(&e1) != hipSuccess) {
+        (void)hipEventDestroy(e0);
+        return LIBRA_ERR_HIP;
+    }
     int rc = LIBRA_OK;
     for (int mode = 1; mode <= 3 && rc == LIBRA_OK; ++mode) {
         float best = 1e30f;
         for (int rep = 0; rep < 4; ++rep) {          // the first repetition warms up
-            hipEventRecord(e0, s);
+            bool ok = hipEventRecord(e0, s) == hipSuccess;
             hipLaunchKernelGGL(coissue_kernel, dim3(1024), dim3(512), 0, s, mode, iters, sink_dev);
-            hipEventRecord(e1, s);
-            if (hipEventSynchronize(e1) != hipSuccess || hipGetLastError() != hipSuccess) { rc = LIBRA_ERR_HIP; break; }
+            ok = ok && hipGetLastError() == hipSuccess && hipEventRecord(e1, s) == hipSuccess && hipEventSynchronize(e1) == hipSuccess;
             float ms = 0.f;
-            hipEventElapsedTime(&ms, e0, e1);
+            ok = ok && hipEventElapsedTime(&ms, e0, e1) == hipSuccess;
+            if (!ok) { rc = LIBRA_ERR_HIP; break; }
             if (rep > 0 && ms < best) best = ms;
         }
         times_us[mode - 1] = best * 1e3f;
     }
-    hipEventDestroy(e0);
-    hipEventDestroy(e1);
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
     return rc;
 }

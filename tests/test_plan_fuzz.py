@@ -1,7 +1,5 @@
 """Randomised cross-check of the product planner against the reference planner: random small matrices with
 random shapes, densities, long rows and options must give bit-identical plans.  CPU only."""
-import numpy as np
-import pytest
 from hypothesis import HealthCheck, given, settings
 from hypothesis import strategies as st
 
