@@ -9,11 +9,11 @@ from paper_2506_22714_amd import workloads as wl
 from test_plan_host import check_subplan, ref_opts
 
 
-@settings(max_examples=40, deadline=None, suppress_health_check=[HealthCheck.too_slow])
+@settings(max_examples=60, deadline=None, suppress_health_check=[HealthCheck.too_slow])
 @given(M=st.integers(1, 90), Kc=st.integers(1, 120), density=st.floats(0.0, 0.5), seed=st.integers(0, 10_000),
        W=st.sampled_from([1, 4, 8, 16, 32]), KB=st.sampled_from([1, 4, 16, 64]),
        tau=st.integers(1, 6), tau_blk=st.integers(1, 64), ts=st.integers(1, 5), cs=st.integers(1, 20),
-       short_len=st.integers(1, 4), sddmm_cs=st.integers(1, 50), mode=st.integers(0, 2), flags=st.sampled_from([0, 1, 8, 9]),
+       short_len=st.integers(1, 4), sddmm_cs=st.integers(1, 50), mode=st.integers(0, 2), flags=st.sampled_from([0, 1, 8, 9, 16, 17, 32, 33, 64, 128, 256, 257, 288]),
        threads=st.integers(1, 5))
 def test_random_plans_match_reference(M, Kc, density, seed, W, KB, tau, tau_blk, ts, cs, short_len, sddmm_cs, mode, flags, threads):
     A = wl.random_pattern(M, Kc, density, seed=seed, empty_rows=0.2)
