@@ -875,10 +875,10 @@ __device__ inline float row16_max(float s) {
 
 // Rows of up to 64 nonzeros (the bulk of a graph): 16 lanes per row, read once and kept in registers.
 template <class TO>
-__global__ __launch_bounds__(256) void edge_softmax_rows_kernel(const int32_t *rowptr, int64_t M, const float *score, float scale, TO *out) {
+__device__ inline void edge_softmax_short_rows(unsigned block, unsigned nblocks, const int32_t *rowptr, int64_t M, const float *score, float scale, TO *out) {
     const int l = threadIdx.x & 15;
-    const int64_t group = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 4;
-    const int64_t ngroups = ((int64_t)gridDim.x * blockDim.x) >> 4;
+    const int64_t group = ((int64_t)block * blockDim.x + threadIdx.x) >> 4;
+    const int64_t ngroups = ((int64_t)nblocks * blockDim.x) >> 4;
     for (int64_t i = group; i < M; i += ngroups) {
         const int s = rowptr[i], n = rowptr[i + 1] - s;
         if (n == 0 || n > 64) continue;         // longer rows are listed at plan time and run below
@@ -902,14 +902,14 @@ __global__ __launch_bounds__(256) void edge_softmax_rows_kernel(const int32_t *r
     }
 }
 
-// Rows listed at plan time: 65 .. LIBRA_SOFTMAX_LONG_ROW nonzeros, one wave per row (THREADS = 64, four rows per
-// workgroup), and longer ones, one 256-thread workgroup per row.  A thread takes UNR scores per round, all loads in flight
+// Rows listed at plan time: 65 .. LIBRA_SOFTMAX_LONG_ROW nonzeros, THREADS = MEDIUM_LANES lanes per row (whole groups
+// of lanes inside a wave), and longer ones, one 256-thread workgroup per row.  A thread takes UNR scores per round, all loads in flight
 // together; the row's maximum and denominator come from one pass (running maximum, sum rescaled when it grows); the second
 // pass writes, from the registers if the whole row fitted one round and from a second read (cache) otherwise.
 template <int THREADS>
 __device__ inline float list_sum(float x, float *red) {
 #pragma unroll
-    for (int m = 1; m < WAVE; m <<= 1) x += __shfl_xor(x, m, WAVE);
+    for (int m = 1; m < (THREADS < WAVE ? THREADS : WAVE); m <<= 1) x += __shfl_xor(x, m, WAVE);
     if constexpr (THREADS > WAVE) {
         __syncthreads();                // earlier readers of `red` are done
         if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = x;
@@ -923,7 +923,7 @@ __device__ inline float list_sum(float x, float *red) {
 template <int THREADS>
 __device__ inline float list_max(float x, float *red) {
 #pragma unroll
-    for (int m = 1; m < WAVE; m <<= 1) x = fmaxf(x, __shfl_xor(x, m, WAVE));
+    for (int m = 1; m < (THREADS < WAVE ? THREADS : WAVE); m <<= 1) x = fmaxf(x, __shfl_xor(x, m, WAVE));
     if constexpr (THREADS > WAVE) {
         __syncthreads();
         if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = x;
@@ -936,11 +936,12 @@ __device__ inline float list_max(float x, float *red) {
 }
 
 template <class TO, int THREADS, int UNR>
-__global__ __launch_bounds__(256) void edge_softmax_list_kernel(const int32_t *rowptr, const int32_t *rows, int nrows, const float *score, float scale, TO *out) {
+__device__ inline void edge_softmax_listed_row(unsigned block, const int32_t *rowptr, const int32_t *rows, int nrows, const float *score, float scale, TO *out) {
     __shared__ float red[4];
-    const int tid = THREADS == WAVE ? (int)(threadIdx.x & 63) : (int)threadIdx.x;
-    const int w = THREADS == WAVE ? (int)((blockIdx.x * blockDim.x + threadIdx.x) >> 6) : (int)blockIdx.x;
-    if (w >= nrows) return;             // whole waves (THREADS == WAVE) or whole workgroups leave together
+    static_assert(THREADS == 256 || (THREADS <= WAVE && WAVE % THREADS == 0), "a workgroup per row, or whole groups of lanes inside a wave");
+    const int tid = (int)threadIdx.x % THREADS;
+    const int w = (int)((block * 256u + threadIdx.x) / THREADS);
+    if (w >= nrows) return;             // whole lane groups or whole workgroups leave together
     const int64_t i = rows[w];
     const int s = rowptr[i], n = rowptr[i + 1] - s;
     const float *sc = score + s;
@@ -980,16 +981,42 @@ __global__ __launch_bounds__(256) void edge_softmax_list_kernel(const int32_t *r
     }
 }
 
+// The three row classes in one launch of 256-thread workgroups: first one workgroup per long row (the plan lists them
+// longest first: the longest row sets the time of its class, so it starts first and the rest of the launch runs beside
+// it), then 256 / MEDIUM_LANES medium rows per workgroup, then the workgroups that walk the rows of 64 nonzeros or fewer.
+// GAT graph (2^20 rows, 60.7 M nonzeros): 196 us as three launches, 159 us as one, 150 us with 32 instead of 64 lanes per
+// medium row (more rows in flight per wave; 16 lanes: 149 us).
+constexpr int MEDIUM_LANES = 32;        // lanes per medium row
+struct SoftmaxRows {
+    const int32_t *rowptr, *long_rows, *medium_rows;
+    int64_t M;
+    int32_t nlong, nmedium;
+    uint32_t medium_blocks, short_blocks;
+};
+__host__ inline SoftmaxRows softmax_rows(const libra_plan_t *P) {
+    SoftmaxRows r{P->d_rowptr, P->d_long_rows, P->d_medium_rows, P->M, (int32_t)P->long_rows.size(), (int32_t)P->medium_rows.size(), 0u, 0u};
+    r.medium_blocks = ((uint32_t)r.nmedium + 256u / MEDIUM_LANES - 1u) / (256u / MEDIUM_LANES);
+    r.short_blocks = (uint32_t)std::min<int64_t>((P->M + 15) / 16, 1 << 18);
+    return r;
+}
+template <class TO>
+__global__ __launch_bounds__(256) void edge_softmax_kernel(SoftmaxRows r, const float *score, float scale, TO *out) {
+    const unsigned b = blockIdx.x;
+    if (b < (unsigned)r.nlong) edge_softmax_listed_row<TO, 256, 16>(b, r.rowptr, r.long_rows, r.nlong, score, scale, out);
+    else if (b < (unsigned)r.nlong + r.medium_blocks) edge_softmax_listed_row<TO, MEDIUM_LANES, 8>(b - (unsigned)r.nlong, r.rowptr, r.medium_rows, r.nmedium, score, scale, out);
+    else edge_softmax_short_rows<TO>(b - (unsigned)r.nlong - r.medium_blocks, r.short_blocks, r.rowptr, r.M, score, scale, out);
+}
+
 // Backward of the edge softmax: dscore_p = scale * alpha_p * (dalpha_p - sum_row alpha_q dalpha_q).  Same three row
 // classes as the forward kernels.
 template <class TA> __device__ inline float from_storage(TA x) { return (float)x; }
 template <> __device__ inline float from_storage<bf16_t>(bf16_t x) { return __uint_as_float((uint32_t)x.bits << 16); }
 
 template <class TA>
-__global__ __launch_bounds__(256) void edge_softmax_bwd_rows_kernel(const int32_t *rowptr, int64_t M, const TA *alpha, const float *dalpha, float scale, float *dscore) {
+__device__ inline void edge_softmax_bwd_short_rows(unsigned block, unsigned nblocks, const int32_t *rowptr, int64_t M, const TA *alpha, const float *dalpha, float scale, float *dscore) {
     const int l = threadIdx.x & 15;
-    const int64_t group = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 4;
-    const int64_t ngroups = ((int64_t)gridDim.x * blockDim.x) >> 4;
+    const int64_t group = ((int64_t)block * blockDim.x + threadIdx.x) >> 4;
+    const int64_t ngroups = ((int64_t)nblocks * blockDim.x) >> 4;
     for (int64_t i = group; i < M; i += ngroups) {
         const int s = rowptr[i], n = rowptr[i + 1] - s;
         if (n == 0 || n > 64) continue;
@@ -1008,14 +1035,15 @@ __global__ __launch_bounds__(256) void edge_softmax_bwd_rows_kernel(const int32_
     }
 }
 
-// one wave per listed row (65 .. LIBRA_SOFTMAX_LONG_ROW nonzeros), or one 256-thread workgroup per listed long row;
+// MEDIUM_LANES lanes per listed row (65 .. LIBRA_SOFTMAX_LONG_ROW nonzeros), or one 256-thread workgroup per listed long row;
 // UNR pairs per thread and round, as in the forward kernel
 template <class TA, int THREADS, int UNR>
-__global__ __launch_bounds__(256) void edge_softmax_bwd_list_kernel(const int32_t *rowptr, const int32_t *rows, int nrows, const TA *alpha, const float *dalpha, float scale, float *dscore) {
+__device__ inline void edge_softmax_bwd_listed_row(unsigned block, const int32_t *rowptr, const int32_t *rows, int nrows, const TA *alpha, const float *dalpha, float scale, float *dscore) {
     __shared__ float red[4];
-    const int tid = THREADS == WAVE ? (int)(threadIdx.x & 63) : (int)threadIdx.x;
-    const int w = THREADS == WAVE ? (int)((blockIdx.x * blockDim.x + threadIdx.x) >> 6) : (int)blockIdx.x;
-    if (w >= nrows) return;             // whole waves (THREADS == WAVE) or whole workgroups leave together
+    static_assert(THREADS == 256 || (THREADS <= WAVE && WAVE % THREADS == 0), "a workgroup per row, or whole groups of lanes inside a wave");
+    const int tid = (int)threadIdx.x % THREADS;
+    const int w = (int)((block * 256u + threadIdx.x) / THREADS);
+    if (w >= nrows) return;             // whole lane groups or whole workgroups leave together
     const int64_t i = rows[w];
     const int s = rowptr[i], n = rowptr[i + 1] - s;
     float a[UNR], g[UNR];
@@ -1046,6 +1074,14 @@ __global__ __launch_bounds__(256) void edge_softmax_bwd_list_kernel(const int32_
             if (q < n) dscore[s + q] = scale * a[u] * (g[u] - dot);
         }
     }
+}
+
+template <class TA>
+__global__ __launch_bounds__(256) void edge_softmax_bwd_kernel(SoftmaxRows r, const TA *alpha, const float *dalpha, float scale, float *dscore) {
+    const unsigned b = blockIdx.x;
+    if (b < (unsigned)r.nlong) edge_softmax_bwd_listed_row<TA, 256, 8>(b, r.rowptr, r.long_rows, r.nlong, alpha, dalpha, scale, dscore);
+    else if (b < (unsigned)r.nlong + r.medium_blocks) edge_softmax_bwd_listed_row<TA, MEDIUM_LANES, 8>(b - (unsigned)r.nlong, r.rowptr, r.medium_rows, r.nmedium, alpha, dalpha, scale, dscore);
+    else edge_softmax_bwd_short_rows<TA>(b - (unsigned)r.nlong - r.medium_blocks, r.short_blocks, r.rowptr, r.M, alpha, dalpha, scale, dscore);
 }
 
 // dst[i * stride + offset] (as T) = src[perm[i]]: new values into a packed array or into entry records
@@ -1434,14 +1470,11 @@ extern "C" int libra_edge_softmax(const libra_plan_t *P, const float *scores, fl
     if (!P->dev_base) return LIBRA_ERR_NOT_UPLOADED;
     hipStream_t s = (hipStream_t)stream;
     if (P->nnz == 0) return LIBRA_OK;
-    const unsigned blocks = (unsigned)std::min<int64_t>((P->M + 15) / 16, 1 << 18);
-    const unsigned nlong = (unsigned)P->long_rows.size(), nmed = (unsigned)P->medium_rows.size();
+    const SoftmaxRows r = softmax_rows(P);
+    const unsigned blocks = (unsigned)r.nlong + r.medium_blocks + r.short_blocks;
     auto run = [&](auto tag) {
         typedef decltype(tag) TO;
-        TO *o = reinterpret_cast<TO *>(vals_out);
-        hipLaunchKernelGGL((edge_softmax_rows_kernel<TO>), dim3(blocks), dim3(256), 0, s, P->d_rowptr, P->M, scores, scale, o);
-        if (nmed) hipLaunchKernelGGL((edge_softmax_list_kernel<TO, WAVE, 8>), dim3((nmed + 3) / 4), dim3(256), 0, s, P->d_rowptr, P->d_medium_rows, (int)nmed, scores, scale, o);
-        if (nlong) hipLaunchKernelGGL((edge_softmax_list_kernel<TO, 256, 16>), dim3(nlong), dim3(256), 0, s, P->d_rowptr, P->d_long_rows, (int)nlong, scores, scale, o);
+        hipLaunchKernelGGL((edge_softmax_kernel<TO>), dim3(blocks), dim3(256), 0, s, r, scores, scale, reinterpret_cast<TO *>(vals_out));
     };
     if (out_dtype == LIBRA_F16) run(half_t{});
     else if (out_dtype == LIBRA_BF16) run(bf16_t{});
@@ -1457,14 +1490,11 @@ extern "C" int libra_edge_softmax_backward(const libra_plan_t *P, const void *al
     if (!P->dev_base) return LIBRA_ERR_NOT_UPLOADED;
     hipStream_t s = (hipStream_t)stream;
     if (P->nnz == 0) return LIBRA_OK;
-    const unsigned blocks = (unsigned)std::min<int64_t>((P->M + 15) / 16, 1 << 18);
-    const unsigned nlong = (unsigned)P->long_rows.size(), nmed = (unsigned)P->medium_rows.size();
+    const SoftmaxRows r = softmax_rows(P);
+    const unsigned blocks = (unsigned)r.nlong + r.medium_blocks + r.short_blocks;
     auto run = [&](auto tag) {
         typedef decltype(tag) TA;
-        const TA *a = reinterpret_cast<const TA *>(alpha);
-        hipLaunchKernelGGL((edge_softmax_bwd_rows_kernel<TA>), dim3(blocks), dim3(256), 0, s, P->d_rowptr, P->M, a, dalpha, scale, dscores);
-        if (nmed) hipLaunchKernelGGL((edge_softmax_bwd_list_kernel<TA, WAVE, 8>), dim3((nmed + 3) / 4), dim3(256), 0, s, P->d_rowptr, P->d_medium_rows, (int)nmed, a, dalpha, scale, dscores);
-        if (nlong) hipLaunchKernelGGL((edge_softmax_bwd_list_kernel<TA, 256, 8>), dim3(nlong), dim3(256), 0, s, P->d_rowptr, P->d_long_rows, (int)nlong, a, dalpha, scale, dscores);
+        hipLaunchKernelGGL((edge_softmax_bwd_kernel<TA>), dim3(blocks), dim3(256), 0, s, r, reinterpret_cast<const TA *>(alpha), dalpha, scale, dscores);
     };
     if (alpha_dtype == LIBRA_F16) run(half_t{});
     else if (alpha_dtype == LIBRA_BF16) run(bf16_t{});

@@ -554,6 +554,10 @@ void libra::finish_plan(libra_plan_t *P, const ColumnFetch &cols, const int64_t 
         if (n > LIBRA_SOFTMAX_LONG_ROW) P->long_rows.push_back((int32_t)i);
         else if (n > 64) P->medium_rows.push_back((int32_t)i);
     }
+    // longest first: one workgroup takes a long row, and the longest one sets the time of the whole class
+    std::stable_sort(P->long_rows.begin(), P->long_rows.end(), [&](int32_t a, int32_t b) {
+        return rowptr[a + 1] - rowptr[a] > rowptr[b + 1] - rowptr[b];
+    });
     if (!o.build_spmm) sa = SubPlan();
     if (!o.build_sddmm) sd = SubPlan();
     if (P->host_arrays) {
