@@ -62,8 +62,8 @@ template <class T> struct Elem;
 template <> struct Elem<half_t> {
     static constexpr int PER_LANE = 8;                   // 16 bytes
     typedef uint4 raw_t;
-    typedef ResEnt16 ent_t;                              // a residual entry in registers ...
-    typedef ResEnt16 stored_t;                           // ... and in memory
+    struct ent_t {};                                     // (16-bit residual entries live in two arrays, see RES_BLOCK)
+    typedef uint32_t stored_t;
     __device__ static raw_t load(const void *base, int64_t elem_off) {
         return *reinterpret_cast<const uint4 *>(reinterpret_cast<const half_t *>(base) + elem_off);
     }
@@ -81,51 +81,19 @@ template <> struct Elem<half_t> {
         for (int e = 0; e < 8; ++e) s = fmaf((float)a[e], (float)b[e], s);
         return s;
     }
-    __device__ static ent_t load_ent(const void *base, int64_t i) {
-        const uint2 u = reinterpret_cast<const uint2 *>(base)[i];
-        ent_t e;
-        e.col = (int32_t)u.x;
-        e.val = (uint16_t)(u.y & 0xffffu);
-        e.row = (uint16_t)(u.y >> 16);
-        return e;
-    }
-    __device__ static float ent_val(const ent_t &e) {
+    __device__ static float pair_lo(uint32_t w) {
+        const uint16_t lo = (uint16_t)(w & 0xffffu);
         half_t h;
-        __builtin_memcpy(&h, &e.val, 2);
+        __builtin_memcpy(&h, &lo, 2);
         return (float)h;
     }
-    // one 8-byte LDS read per entry (the second word goes through an opaque move so that it is read once, whole)
-    __device__ static ent_t lds_ent(const ent_t *lds, int i) {
-        const uint2 u = reinterpret_cast<const uint2 *>(lds)[i];
-        uint32_t w = u.y;
-        asm volatile("" : "+v"(w));
-        ent_t e;
-        e.col = (int32_t)u.x;
-        e.val = (uint16_t)(w & 0xffffu);
-        e.row = (uint16_t)(w >> 16);
-        return e;
+    __device__ static float pair_hi(uint32_t w) {
+        const uint16_t hi = (uint16_t)(w >> 16);
+        half_t h;
+        __builtin_memcpy(&h, &hi, 2);
+        return (float)h;
     }
     __device__ static void mask(raw_t &r, uint32_t keep) { r.x &= keep; r.y &= keep; r.z &= keep; r.w &= keep; }
-    // a batch of U consecutive entries from a 16-byte aligned address: U/2 16-byte LDS reads issued back to back, one wait;
-    // the words that hold {value, row} go through an opaque move afterwards so that each is read once, whole
-    template <int U>
-    __device__ static void lds_batch(const ent_t *lds, ent_t (&en)[U]) {
-        static_assert(U % 2 == 0, "two 8-byte entries per 16-byte read");
-        uint4 v[U / 2];
-#pragma unroll
-        for (int k = 0; k < U / 2; ++k) v[k] = reinterpret_cast<const uint4 *>(lds)[k];
-#pragma unroll
-        for (int k = 0; k < U / 2; ++k) {
-            uint32_t w0 = v[k].y, w1 = v[k].w;
-            asm volatile("" : "+v"(w0), "+v"(w1));
-            en[2 * k].col = (int32_t)v[k].x;
-            en[2 * k].val = (uint16_t)(w0 & 0xffffu);
-            en[2 * k].row = (uint16_t)(w0 >> 16);
-            en[2 * k + 1].col = (int32_t)v[k].z;
-            en[2 * k + 1].val = (uint16_t)(w1 & 0xffffu);
-            en[2 * k + 1].row = (uint16_t)(w1 >> 16);
-        }
-    }
     // the lane's 16 bytes of row `col`: one 32x32->64 multiply-add for the address
     __device__ static raw_t load_row(const void *base, int32_t col, uint32_t ld_bytes, int sub) {
         const char *p = reinterpret_cast<const char *>(base) + ((uint64_t)(uint32_t)col * ld_bytes + (uint32_t)sub * 16u);
@@ -158,7 +126,8 @@ template <> struct Elem<bf16_t> : Elem<half_t> {
         }
         return s;
     }
-    __device__ static float ent_val(const ent_t &e) { return widen(e.val); }
+    __device__ static float pair_lo(uint32_t w) { return __uint_as_float(w << 16); }
+    __device__ static float pair_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
     __device__ static float word_val(uint32_t bits) { return widen(bits & 0xffffu); }
 };
 template <> struct Elem<float> {
@@ -213,6 +182,32 @@ template <> struct Elem<float> {
     }
     __device__ static float word_val(uint32_t bits) { return __uint_as_float(bits); }
 };
+
+// NW 32-bit words from an LDS address aligned to their size (16 bytes from four words up): 16-byte reads issued back to
+// back; every word then goes through an opaque move, so that it is read once and whole however its fields are used.
+template <int NW>
+__device__ inline void lds_words(const void *lds, uint32_t (&w)[NW]) {
+    static_assert(NW == 2 || NW % 4 == 0, "8 bytes, or whole 16-byte reads");
+    if constexpr (NW == 2) {
+        const uint2 v = *reinterpret_cast<const uint2 *>(lds);
+        w[0] = v.x; w[1] = v.y;
+    } else {
+#pragma unroll
+        for (int k = 0; k < NW / 4; ++k) {
+            const uint4 v = reinterpret_cast<const uint4 *>(lds)[k];
+            w[4 * k] = v.x; w[4 * k + 1] = v.y; w[4 * k + 2] = v.z; w[4 * k + 3] = v.w;
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < NW; ++k) asm volatile("" : "+v"(w[k]));
+}
+// entry i of the blocked 16-bit layout: its word and its value
+__device__ inline void load_blocked_entry(const void *base, int64_t i, uint32_t &word, uint16_t &val) {
+    const char *blk = reinterpret_cast<const char *>(base) + (i >> 6) * RES_BLOCK_BYTES;
+    const int slot = (int)(i & (RES_BLOCK - 1));
+    word = reinterpret_cast<const uint32_t *>(blk)[slot];
+    val = reinterpret_cast<const uint16_t *>(blk + RES_BLOCK * 4)[slot];
+}
 
 __device__ inline void global_add(float *p, float v) {
     __hip_atomic_fetch_add(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -302,7 +297,8 @@ __global__ __launch_bounds__(WAVE) __attribute__((amdgpu_waves_per_eu(N >= 128 ?
     constexpr int U = N >= 128 ? SPMM_U : SPMM_U / 2;   // B-row fetches in flight per lane group (narrow rows: fewer, for more waves)
     // the B stage (dense phase) and the C tile (afterwards) share the same LDS bytes
     __shared__ __attribute__((aligned(16))) unsigned char smem[SMEM];
-    __shared__ __attribute__((aligned(16))) stored_t ent_lds[ECAP];
+    __shared__ __attribute__((aligned(16))) stored_t ent_lds[ECAP];                 // fp32: records; 16-bit: the entries' words
+    __shared__ __attribute__((aligned(16))) uint16_t val_lds[F32 ? 8 : ECAP];       // 16-bit: the entries' values
     __shared__ __attribute__((aligned(16))) int32_t cols_lds[DENSE ? BCAP * KB : 4];
     __shared__ __attribute__((aligned(16))) uint64_t bm_lds[DENSE ? BCAP * 4 : 2];
     float *tile = reinterpret_cast<float *>(smem);
@@ -335,10 +331,14 @@ __global__ __launch_bounds__(WAVE) __attribute__((amdgpu_waves_per_eu(N >= 128 ?
     // First round of each kind of metadata, all loads in flight together, then the LDS writes.
     {
         const int nE = min(L, ECAP), nb = min(nblk, BCAP);
-        const stored_t *src = reinterpret_cast<const stored_t *>(a.res_ent) + t.res_begin;
         stored_t tmp[ECAP / WAVE];
+        uint16_t tmp_val[ECAP / WAVE];
 #pragma unroll
-        for (int k = 0; k < ECAP / WAVE; ++k) tmp[k] = E::load_ent(src, max(min(k * WAVE + lane, nE - 1), 0));
+        for (int k = 0; k < ECAP / WAVE; ++k) {
+            const int64_t i = (int64_t)t.res_begin + max(min(k * WAVE + lane, nE - 1), 0);
+            if constexpr (F32) tmp[k] = E::load_ent(a.res_ent, i);
+            else load_blocked_entry(a.res_ent, i, tmp[k], tmp_val[k]);
+        }
         if constexpr (DENSE) {
             const int32_t *csrc = a.blk_cols + (int64_t)t.blk_begin * KB;
             int32_t c[BCAP * KB / WAVE];
@@ -350,7 +350,10 @@ __global__ __launch_bounds__(WAVE) __attribute__((amdgpu_waves_per_eu(N >= 128 ?
             if (lane < BCAP * 4) bm_lds[lane] = w;
         }
 #pragma unroll
-        for (int k = 0; k < ECAP / WAVE; ++k) ent_lds[k * WAVE + lane] = tmp[k];
+        for (int k = 0; k < ECAP / WAVE; ++k) {
+            ent_lds[k * WAVE + lane] = tmp[k];
+            if constexpr (!F32) val_lds[k * WAVE + lane] = tmp_val[k];
+        }
     }
     // later rounds of a task with more than BCAP blocks are fetched in place
     auto fetch_blocks = [&](int b0, int nb) {
@@ -510,10 +513,14 @@ __global__ __launch_bounds__(WAVE) __attribute__((amdgpu_waves_per_eu(N >= 128 ?
         // the next round's entries go in flight now and wait in registers until this round is done
         const int nE_next = min(ECAP, L - e0 - ECAP);
         stored_t next_ent[ECAP / WAVE];
+        uint16_t next_val[ECAP / WAVE];
         if (nE_next > 0) {
-            const stored_t *src = reinterpret_cast<const stored_t *>(a.res_ent) + t.res_begin + e0 + ECAP;
 #pragma unroll
-            for (int k = 0; k < ECAP / WAVE; ++k) next_ent[k] = E::load_ent(src, min(k * WAVE + lane, nE_next - 1));
+            for (int k = 0; k < ECAP / WAVE; ++k) {
+                const int64_t i = (int64_t)t.res_begin + e0 + ECAP + min(k * WAVE + lane, nE_next - 1);
+                if constexpr (F32) next_ent[k] = E::load_ent(a.res_ent, i);
+                else load_blocked_entry(a.res_ent, i, next_ent[k], next_val[k]);
+            }
         }
         // runs are whole batches of U entries (the longest run, which sets the time of the round, needs no more batches
         // for it), so a batch is U consecutive entries from an aligned base address and never leaves the staged array
@@ -524,7 +531,9 @@ __global__ __launch_bounds__(WAVE) __attribute__((amdgpu_waves_per_eu(N >= 128 ?
         // A row is added into the tile by the group that holds its first entry (plain read-add-write:
         // one owner per row).  A group whose run starts inside a row keeps that row's partial sum in
         // registers instead and adds it after the others, in group order, so the order of additions is fixed.
-        bool first_is_shared = q0 > 0 && q0 < q1 && E::lds_ent(ent_lds, q0 - 1).row == E::lds_ent(ent_lds, q0).row;
+        bool first_is_shared;
+        if constexpr (F32) first_is_shared = q0 > 0 && q0 < q1 && E::lds_ent(ent_lds, q0 - 1).row == E::lds_ent(ent_lds, q0).row;
+        else first_is_shared = q0 > 0 && q0 < q1 && ((ent_lds[q0 - 1] ^ ent_lds[q0]) >> RES32_ROW_SHIFT) == 0;
         int kept_row = -1;
         float kept[8] = {0, 0, 0, 0, 0, 0, 0, 0};
         int cur = -1;
@@ -550,20 +559,36 @@ __global__ __launch_bounds__(WAVE) __attribute__((amdgpu_waves_per_eu(N >= 128 ?
         };
         for (int q = q0; q < q1; q += U) {
             // all entry reads, then all row fetches, back to back
-            ent_t en[U];
             typename E::raw_t raw[U];
             const bool full = q + U <= q1;
             // U consecutive entries from one aligned base address; slots past the run hold valid entries whose fetch is
             // harmless and whose product is never formed
-            E::template lds_batch<U>(ent_lds + q, en);
+            int ecol[U], erow[U];
+            float eval[U];
+            if constexpr (F32) {
+                ent_t en[U];
+                E::template lds_batch<U>(ent_lds + q, en);
 #pragma unroll
-            for (int u = 0; u < U; ++u) raw[u] = E::load_row(Bp, en[u].col, ldb_bytes, sub);
+                for (int u = 0; u < U; ++u) { ecol[u] = en[u].col; erow[u] = en[u].row; eval[u] = en[u].val; }
+            } else {
+                uint32_t cr[U], vw[U / 2];
+                lds_words<U>(ent_lds + q, cr);
+                lds_words<U / 2>(val_lds + q, vw);
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    ecol[u] = (int)(cr[u] & RES32_COL_MASK);
+                    erow[u] = (int)(cr[u] >> RES32_ROW_SHIFT);
+                    eval[u] = (u & 1) ? E::pair_hi(vw[u >> 1]) : E::pair_lo(vw[u >> 1]);
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) raw[u] = E::load_row(Bp, ecol[u], ldb_bytes, sub);
             bool one_row = full;
 #pragma unroll
-            for (int u = 1; u < U; ++u) one_row = one_row && en[u].row == en[0].row;
+            for (int u = 1; u < U; ++u) one_row = one_row && erow[u] == erow[0];
             if (one_row) {
                 // common case (long rows, segments of decomposed rows): the whole batch belongs to one row
-                const int r = (int)en[0].row;
+                const int r = erow[0];
                 if (r != cur) {
                     if (cur >= 0) flush();
 #pragma unroll
@@ -571,19 +596,19 @@ __global__ __launch_bounds__(WAVE) __attribute__((amdgpu_waves_per_eu(N >= 128 ?
                     cur = r;
                 }
 #pragma unroll
-                for (int u = 0; u < U; ++u) E::fma(E::ent_val(en[u]), raw[u], acc);
+                for (int u = 0; u < U; ++u) E::fma(eval[u], raw[u], acc);
             } else {
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
                     if (q + u < q1) {
-                        const int r = (int)en[u].row;
+                        const int r = erow[u];
                         if (r != cur) {
                             if (cur >= 0) flush();
 #pragma unroll
                             for (int e = 0; e < PL; ++e) acc[e] = 0.f;
                             cur = r;
                         }
-                        E::fma(E::ent_val(en[u]), raw[u], acc);
+                        E::fma(eval[u], raw[u], acc);
                     }
                 }
             }
@@ -596,7 +621,10 @@ __global__ __launch_bounds__(WAVE) __attribute__((amdgpu_waves_per_eu(N >= 128 ?
         if (nE_next > 0) {
             wave_sync();
 #pragma unroll
-            for (int k = 0; k < ECAP / WAVE; ++k) ent_lds[k * WAVE + lane] = next_ent[k];
+            for (int k = 0; k < ECAP / WAVE; ++k) {
+                ent_lds[k * WAVE + lane] = next_ent[k];
+                if constexpr (!F32) val_lds[k * WAVE + lane] = next_val[k];
+            }
             wave_sync();
         }
     }
@@ -1091,6 +1119,12 @@ __global__ __launch_bounds__(256) void scatter_values_kernel(const T *src, const
         *reinterpret_cast<T *>(reinterpret_cast<char *>(dst) + i * stride + offset) = src[perm[i]];
 }
 
+// the same into the value runs of the blocked 16-bit entry layout
+__global__ __launch_bounds__(256) void scatter_blocked_values_kernel(const uint16_t *src, const int32_t *perm, int64_t n, unsigned char *dst) {
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x)
+        reinterpret_cast<uint16_t *>(dst + (i >> 6) * RES_BLOCK_BYTES + RES_BLOCK * 4)[i & (RES_BLOCK - 1)] = src[perm[i]];
+}
+
 inline int hip_rc(hipError_t e) { return e == hipSuccess ? LIBRA_OK : LIBRA_ERR_HIP; }
 
 template <class T, int N>
@@ -1206,14 +1240,21 @@ std::vector<DevTask> pack_tasks(const libra_plan_t *P, const SubPlan &sp, bool s
 // Host staging of everything the kernels read in packed form; alive until the copies have finished.
 struct Staging {
     std::vector<DevTask> tasks_a, tasks_d;
-    std::vector<ResEnt16> ent16;
+    std::vector<unsigned char> ent16;       // blocked words and values
     std::vector<ResEnt32> ent32;
     std::vector<SdEnt> sdent;
     std::vector<SdPv> sdpv;
 };
 
 // Record layouts written on the device when the arrays come from the device planner.
-__device__ inline ResEnt16 make_entry(int32_t col, uint16_t val, int row_in_window) { return ResEnt16{col, val, (uint16_t)row_in_window}; }
+__global__ __launch_bounds__(256) void pack_blocked_entries_kernel(const int32_t *col, const uint16_t *val, const int32_t *row, int64_t n, unsigned char *out) {
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
+        unsigned char *blk = out + (i >> 6) * RES_BLOCK_BYTES;
+        const int slot = (int)(i & (RES_BLOCK - 1));
+        reinterpret_cast<uint32_t *>(blk)[slot] = (uint32_t)col[i] | (uint32_t)(row[i] % W) << RES32_ROW_SHIFT;
+        reinterpret_cast<uint16_t *>(blk + RES_BLOCK * 4)[slot] = val[i];
+    }
+}
 __device__ inline ResEnt32 make_entry(int32_t col, float val, int row_in_window) {
     return ResEnt32{(uint32_t)col | (uint32_t)row_in_window << RES32_ROW_SHIFT, val};
 }
@@ -1256,9 +1297,14 @@ void layout(libra_plan_t *P, Uploader &u, Staging *st, const DeviceSource *da, c
     if (from_host) {
         const int Wp = P->o.W;
         if (f16) {
-            st->ent16.resize(nres);
+            st->ent16.assign(res_blocked_bytes(nres + 1), 0);
             const uint16_t *v = reinterpret_cast<const uint16_t *>(sa.res_val.data());
-            for (size_t i = 0; i < nres; ++i) st->ent16[i] = {sa.res_col[i], v[i], (uint16_t)(sa.res_row[i] % Wp)};
+            for (size_t i = 0; i < nres; ++i) {
+                unsigned char *blk = st->ent16.data() + i / RES_BLOCK * RES_BLOCK_BYTES;
+                const uint32_t word = (uint32_t)sa.res_col[i] | (uint32_t)(sa.res_row[i] % Wp) << RES32_ROW_SHIFT;
+                std::memcpy(blk + i % RES_BLOCK * 4, &word, 4);
+                std::memcpy(blk + RES_BLOCK * 4 + i % RES_BLOCK * 2, &v[i], 2);
+            }
         } else {
             st->ent32.resize(nres);
             const float *v = reinterpret_cast<const float *>(sa.res_val.data());
@@ -1266,7 +1312,7 @@ void layout(libra_plan_t *P, Uploader &u, Staging *st, const DeviceSource *da, c
                 st->ent32[i] = {(uint32_t)sa.res_col[i] | (uint32_t)(sa.res_row[i] % Wp) << RES32_ROW_SHIFT, v[i]};
         }
     }
-    if (f16) u.put(from_host ? (const void *)st->ent16.data() : nullptr, nullptr, nres * sizeof(ResEnt16), sa.dev.res_ent);
+    if (f16) u.put(from_host ? (const void *)st->ent16.data() : nullptr, nullptr, res_blocked_bytes(nres + 1), sa.dev.res_ent);     // + 1: a task without entries still reads the slot at its (clamped) first index
     else u.put(from_host ? (const void *)st->ent32.data() : nullptr, nullptr, nres * sizeof(ResEnt32), sa.dev.res_ent);
     u.put(H(sa.res_perm.data()), da ? da->res_perm : nullptr, nres * 4, sa.dev.res_perm);
     u.put(H(sa.zero_rows.data()), da ? da->zero_rows : nullptr, (size_t)sa.n.zero_rows * 4, sa.dev.zero_rows);
@@ -1310,7 +1356,7 @@ size_t libra::plan_buffer_bytes(const libra_plan_t *plan) {
 int libra::adopt_device_arrays(libra_plan_t *P, const DeviceSource &da, const DeviceSource &dd, void *dev_buf, size_t bytes, void *stream) {
     if (!dev_buf) return LIBRA_ERR_NULL;
     if (bytes < plan_buffer_bytes(P) || ((uintptr_t)dev_buf & 255)) return LIBRA_ERR_BUFFER;
-    if (P->vdt == LIBRA_F32 && P->Kc > (int64_t)RES32_COL_MASK + 1) return LIBRA_ERR_UNSUPPORTED;    // see ResEnt32
+    if (P->Kc > (int64_t)RES32_COL_MASK + 1) return LIBRA_ERR_UNSUPPORTED;    // a residual entry keeps its column in RES32_ROW_SHIFT bits
     hipStream_t s = (hipStream_t)stream;
     try {
         Staging st;
@@ -1325,8 +1371,8 @@ int libra::adopt_device_arrays(libra_plan_t *P, const DeviceSource &da, const De
                 hipLaunchKernelGGL((pack_spmm_entries_kernel<ResEnt32, float>), grid(sa.n.res), dim3(256), 0, s, da.res_col,
                                    (const float *)da.res_val, da.res_row, sa.n.res, (ResEnt32 *)sa.dev.res_ent);
             else
-                hipLaunchKernelGGL((pack_spmm_entries_kernel<ResEnt16, uint16_t>), grid(sa.n.res), dim3(256), 0, s, da.res_col,
-                                   (const uint16_t *)da.res_val, da.res_row, sa.n.res, (ResEnt16 *)sa.dev.res_ent);
+                hipLaunchKernelGGL(pack_blocked_entries_kernel, grid(sa.n.res), dim3(256), 0, s, da.res_col,
+                                   (const uint16_t *)da.res_val, da.res_row, sa.n.res, (unsigned char *)sa.dev.res_ent);
         }
         if (sd.n.res) {
             if (P->vdt == LIBRA_F32)
@@ -1365,7 +1411,7 @@ extern "C" int libra_plan_upload(libra_plan_t *plan, void *dev_buf, size_t bytes
     size_t need = 0;
     libra_plan_device_bytes(plan, &need);
     if (bytes < need || ((uintptr_t)dev_buf & 255)) return LIBRA_ERR_BUFFER;
-    if (plan->vdt == LIBRA_F32 && plan->Kc > (int64_t)RES32_COL_MASK + 1) return LIBRA_ERR_UNSUPPORTED;      // see ResEnt32
+    if (plan->Kc > (int64_t)RES32_COL_MASK + 1) return LIBRA_ERR_UNSUPPORTED;      // a residual entry keeps its column in RES32_ROW_SHIFT bits
     try {
         Staging st;
         Uploader u;
@@ -1519,14 +1565,16 @@ extern "C" int libra_plan_set_values_for(libra_plan_t *P, const void *vals, int 
     const SubPlan &sa = P->spmm, &sd = P->sddmm;
     const Seg segs[4] = {
         {sa.dev.dense_perm, sa.dev.dense_val, sa.n.dense, vs, 0},
-        {sa.dev.res_perm, sa.dev.res_ent, sa.n.res, f16 ? (int)sizeof(ResEnt16) : (int)sizeof(ResEnt32), 4},
+        {sa.dev.res_perm, sa.dev.res_ent, sa.n.res, f16 ? 0 : (int)sizeof(ResEnt32), 4},       // stride 0: the blocked 16-bit layout
         {sd.dev.dense_perm, sd.dev.dense_pv, sd.n.dense, (int)sizeof(SdPv), 4},
         {sd.dev.res_perm, sd.dev.res_ent, sd.n.res, (int)sizeof(SdEnt), 12}};
     for (int k = 0; k < 4; ++k) {
         const Seg &g = segs[k];
         if (g.n == 0 || !(ops & (k < 2 ? LIBRA_OP_SPMM : LIBRA_OP_SDDMM))) continue;
         const unsigned blocks = (unsigned)std::min<int64_t>((g.n + 255) / 256, 1 << 16);
-        if (f16)
+        if (f16 && g.stride == 0)
+            hipLaunchKernelGGL(scatter_blocked_values_kernel, dim3(blocks), dim3(256), 0, s, (const uint16_t *)vals, g.perm, g.n, (unsigned char *)g.dst);
+        else if (f16)
             hipLaunchKernelGGL((scatter_values_kernel<uint16_t>), dim3(blocks), dim3(256), 0, s, (const uint16_t *)vals, g.perm, g.n, g.dst, g.stride, g.offset);
         else
             hipLaunchKernelGGL((scatter_values_kernel<float>), dim3(blocks), dim3(256), 0, s, (const float *)vals, g.perm, g.n, g.dst, g.stride, g.offset);

@@ -33,14 +33,15 @@ struct DevTask {
     int32_t val_begin;          // first packed value of block blk_begin
 };
 
-// Residual entry of the SpMM sub-plan, fp16 values: 8 bytes.
-struct ResEnt16 {
-    int32_t col;
-    uint16_t val;               // IEEE binary16 bits
-    uint16_t row;               // row inside the window
-};
-// Same, fp32 values: also 8 bytes.  The first word holds the column in its low RES32_ROW_SHIFT bits and the row inside
-// the window above them, so such a plan is limited to 2^27 columns.
+// Residual entries of the SpMM sub-plan, 16-bit values: blocks of RES_BLOCK entries, each block RES_BLOCK 32-bit words
+// (column in the low RES32_ROW_SHIFT bits, row inside the window above them) followed by RES_BLOCK 2-byte values, 384
+// bytes.  Entry i is slot i % RES_BLOCK of block i / RES_BLOCK, so a task's entries are addressed from their index alone,
+// a task reads words and values from neighbouring lines, and new values overwrite whole 128-byte runs.
+constexpr int RES_BLOCK = 64;
+constexpr int RES_BLOCK_BYTES = RES_BLOCK * 6;
+inline size_t res_blocked_bytes(size_t n) { return (n + RES_BLOCK - 1) / RES_BLOCK * RES_BLOCK_BYTES; }
+// fp32 values: 8-byte records.  The first word holds the column in its low RES32_ROW_SHIFT bits and the row inside
+// the window above them, so a plan on the device is limited to 2^27 columns (both layouts).
 constexpr int RES32_ROW_SHIFT = 27;                             // windows of up to 32 rows
 constexpr uint32_t RES32_COL_MASK = (1u << RES32_ROW_SHIFT) - 1u;
 struct ResEnt32 {

@@ -272,16 +272,15 @@ def test_unsupported_requests_return_codes():
     with pytest.raises(lb.LibraError) as e:
         p8.spmm(torch.zeros((64, 32), dtype=torch.float16, device="cuda"))
     assert e.value.code == lb.ERR["UNSUPPORTED"]
-    # fp32 residual entries keep their column in 27 bits: a wider matrix plans, and is refused when it is uploaded
+    # residual entries keep their column in 27 bits: a wider matrix plans, and is refused when it is uploaded
     rowptr = np.array([0, 2] + [2] * 15, dtype=np.int32)
     col = np.array([5, (1 << 27) + 3], dtype=np.int32)
-    wide16 = lb.Plan(16, (1 << 27) + 8, rowptr, col, np.ones(2, dtype=np.float16)).upload()
-    wide16.close()
-    wide32 = lb.Plan(16, (1 << 27) + 8, rowptr, col, np.ones(2, dtype=np.float32))
-    with pytest.raises(lb.LibraError) as e:
-        wide32.upload()
-    assert e.value.code == lb.ERR["UNSUPPORTED"]
-    lb.Plan(16, 1 << 27, rowptr, np.array([5, (1 << 27) - 1], dtype=np.int32), np.ones(2, dtype=np.float32)).upload().close()
+    for dt in (np.float16, np.float32):
+        wide = lb.Plan(16, (1 << 27) + 8, rowptr, col, np.ones(2, dtype=dt))
+        with pytest.raises(lb.LibraError) as e:
+            wide.upload()
+        assert e.value.code == lb.ERR["UNSUPPORTED"]
+        lb.Plan(16, 1 << 27, rowptr, np.array([5, (1 << 27) - 1], dtype=np.int32), np.ones(2, dtype=dt)).upload().close()
 
 
 # ---------------------------------------------- softmax glue and new values
