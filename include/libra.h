@@ -217,9 +217,9 @@ int libra_plan_device_bytes(const libra_plan_t *plan, size_t *bytes);
  *   dev_buf  device pointer, 256-byte aligned, at least libra_plan_device_bytes() bytes;
  *            the plan borrows it until libra_plan_destroy or the next upload.
  * The copies are enqueued on `stream` and the stream is synchronised before returning
- * (the sources are pageable host memory).  Errors: NULL, BUFFER, HIP; UNSUPPORTED for an
- * fp32 plan with more than 2^27 columns (the device copy of an fp32 residual nonzero keeps its
- * column in 27 bits; libra_plan_device with a plan buffer returns the same).
+ * (the sources are pageable host memory).  Errors: NULL, BUFFER, HIP; UNSUPPORTED for a
+ * plan with more than 2^27 columns (the device copy of a residual nonzero keeps its column
+ * in 27 bits; libra_plan_device with a plan buffer returns the same).
  */
 int libra_plan_upload(libra_plan_t *plan, void *dev_buf, size_t bytes, void *stream);
 

@@ -62,8 +62,8 @@ template <class T> struct Elem;
 template <> struct Elem<half_t> {
     static constexpr int PER_LANE = 8;                   // 16 bytes
     typedef uint4 raw_t;
-    struct ent_t {};                                     // (16-bit residual entries live in two arrays, see RES_BLOCK)
-    typedef uint32_t stored_t;
+    typedef uint16_t val_t;                              // a residual entry's value as stored
+    static constexpr int VALS_PER_WORD = 2;
     __device__ static raw_t load(const void *base, int64_t elem_off) {
         return *reinterpret_cast<const uint4 *>(reinterpret_cast<const half_t *>(base) + elem_off);
     }
@@ -133,8 +133,8 @@ template <> struct Elem<bf16_t> : Elem<half_t> {
 template <> struct Elem<float> {
     static constexpr int PER_LANE = 4;                   // 16 bytes
     typedef float4_t raw_t;
-    struct ent_t { int32_t col; float val; int32_t row; };
-    typedef ResEnt32 stored_t;
+    typedef float val_t;
+    static constexpr int VALS_PER_WORD = 1;
     __device__ static raw_t load(const void *base, int64_t elem_off) {
         return *reinterpret_cast<const float4_t *>(reinterpret_cast<const float *>(base) + elem_off);
     }
@@ -147,34 +147,11 @@ template <> struct Elem<float> {
         for (int e = 0; e < 4; ++e) s = fmaf(x[e], y[e], s);
         return s;
     }
-    __device__ static stored_t load_ent(const void *base, int64_t i) {
-        const uint2 u = reinterpret_cast<const uint2 *>(base)[i];
-        return stored_t{u.x, __uint_as_float(u.y)};
-    }
-    __device__ static float ent_val(const ent_t &e) { return e.val; }
-    __device__ static ent_t unpack(uint32_t col_row, uint32_t val_bits) {
-        return ent_t{(int32_t)(col_row & RES32_COL_MASK), __uint_as_float(val_bits), (int32_t)(col_row >> RES32_ROW_SHIFT)};
-    }
-    __device__ static ent_t lds_ent(const stored_t *lds, int i) {
-        const uint2 u = reinterpret_cast<const uint2 *>(lds)[i];
-        return unpack(u.x, u.y);
-    }
+    __device__ static float pair_lo(uint32_t w) { return __uint_as_float(w); }
+    __device__ static float pair_hi(uint32_t w) { return __uint_as_float(w); }
     __device__ static void mask(raw_t &r, uint32_t keep) {
 #pragma unroll
         for (int e = 0; e < 4; ++e) r[e] = __uint_as_float(__float_as_uint(r[e]) & keep);
-    }
-    // U consecutive entries from a 16-byte aligned address, two per 16-byte read
-    template <int U>
-    __device__ static void lds_batch(const stored_t *lds, ent_t (&en)[U]) {
-        static_assert(U % 2 == 0, "two 8-byte entries per 16-byte read");
-        uint4 v[U / 2];
-#pragma unroll
-        for (int k = 0; k < U / 2; ++k) v[k] = reinterpret_cast<const uint4 *>(lds)[k];
-#pragma unroll
-        for (int k = 0; k < U / 2; ++k) {
-            en[2 * k] = unpack(v[k].x, v[k].y);
-            en[2 * k + 1] = unpack(v[k].z, v[k].w);
-        }
     }
     __device__ static raw_t load_row(const void *base, int32_t col, uint32_t ld_bytes, int sub) {
         const char *p = reinterpret_cast<const char *>(base) + ((uint64_t)(uint32_t)col * ld_bytes + (uint32_t)sub * 16u);
@@ -201,12 +178,13 @@ __device__ inline void lds_words(const void *lds, uint32_t (&w)[NW]) {
 #pragma unroll
     for (int k = 0; k < NW; ++k) asm volatile("" : "+v"(w[k]));
 }
-// entry i of the blocked 16-bit layout: its word and its value
-__device__ inline void load_blocked_entry(const void *base, int64_t i, uint32_t &word, uint16_t &val) {
-    const char *blk = reinterpret_cast<const char *>(base) + (i >> 6) * RES_BLOCK_BYTES;
-    const int slot = (int)(i & (RES_BLOCK - 1));
+// entry i of the blocked layout: its word and its value
+template <class V>
+__device__ inline void load_blocked_entry(const void *base, int64_t i, uint32_t &word, V &val) {
+    const char *blk = reinterpret_cast<const char *>(base) + (i / RES_BLOCK) * (RES_BLOCK * (4 + (int)sizeof(V)));
+    const int slot = (int)(i % RES_BLOCK);
     word = reinterpret_cast<const uint32_t *>(blk)[slot];
-    val = reinterpret_cast<const uint16_t *>(blk + RES_BLOCK * 4)[slot];
+    val = reinterpret_cast<const V *>(blk + RES_BLOCK * 4)[slot];
 }
 
 __device__ inline void global_add(float *p, float v) {
@@ -278,8 +256,7 @@ __device__ inline void wave_sync() {
 template <class T, int N>
 __global__ __launch_bounds__(WAVE) __attribute__((amdgpu_waves_per_eu(N >= 128 ? 4 : 6))) void spmm_task_kernel(SpmmArgs a) {
     using E = Elem<T>;
-    typedef typename E::ent_t ent_t;
-    typedef typename E::stored_t stored_t;
+    typedef typename E::val_t val_t;
     constexpr bool F32 = std::is_same<T, float>::value;        // fp32 storage: v_mfma_f32_16x16x4_f32, operands straight from the stage
     constexpr bool DENSE = true;
     constexpr int PL = E::PER_LANE;          // elements of a row per lane
@@ -297,8 +274,8 @@ __global__ __launch_bounds__(WAVE) __attribute__((amdgpu_waves_per_eu(N >= 128 ?
     constexpr int U = N >= 128 ? SPMM_U : SPMM_U / 2;   // B-row fetches in flight per lane group (narrow rows: fewer, for more waves)
     // the B stage (dense phase) and the C tile (afterwards) share the same LDS bytes
     __shared__ __attribute__((aligned(16))) unsigned char smem[SMEM];
-    __shared__ __attribute__((aligned(16))) stored_t ent_lds[ECAP];                 // fp32: records; 16-bit: the entries' words
-    __shared__ __attribute__((aligned(16))) uint16_t val_lds[F32 ? 8 : ECAP];       // 16-bit: the entries' values
+    __shared__ __attribute__((aligned(16))) uint32_t ent_lds[ECAP];          // the staged entries' words (column | row in window) ...
+    __shared__ __attribute__((aligned(16))) val_t val_lds[ECAP];             // ... and values
     __shared__ __attribute__((aligned(16))) int32_t cols_lds[DENSE ? BCAP * KB : 4];
     __shared__ __attribute__((aligned(16))) uint64_t bm_lds[DENSE ? BCAP * 4 : 2];
     float *tile = reinterpret_cast<float *>(smem);
@@ -331,14 +308,11 @@ __global__ __launch_bounds__(WAVE) __attribute__((amdgpu_waves_per_eu(N >= 128 ?
     // First round of each kind of metadata, all loads in flight together, then the LDS writes.
     {
         const int nE = min(L, ECAP), nb = min(nblk, BCAP);
-        stored_t tmp[ECAP / WAVE];
-        uint16_t tmp_val[ECAP / WAVE];
+        uint32_t tmp[ECAP / WAVE];
+        val_t tmp_val[ECAP / WAVE];
 #pragma unroll
-        for (int k = 0; k < ECAP / WAVE; ++k) {
-            const int64_t i = (int64_t)t.res_begin + max(min(k * WAVE + lane, nE - 1), 0);
-            if constexpr (F32) tmp[k] = E::load_ent(a.res_ent, i);
-            else load_blocked_entry(a.res_ent, i, tmp[k], tmp_val[k]);
-        }
+        for (int k = 0; k < ECAP / WAVE; ++k)
+            load_blocked_entry(a.res_ent, (int64_t)t.res_begin + max(min(k * WAVE + lane, nE - 1), 0), tmp[k], tmp_val[k]);
         if constexpr (DENSE) {
             const int32_t *csrc = a.blk_cols + (int64_t)t.blk_begin * KB;
             int32_t c[BCAP * KB / WAVE];
@@ -352,7 +326,7 @@ __global__ __launch_bounds__(WAVE) __attribute__((amdgpu_waves_per_eu(N >= 128 ?
 #pragma unroll
         for (int k = 0; k < ECAP / WAVE; ++k) {
             ent_lds[k * WAVE + lane] = tmp[k];
-            if constexpr (!F32) val_lds[k * WAVE + lane] = tmp_val[k];
+            val_lds[k * WAVE + lane] = tmp_val[k];
         }
     }
     // later rounds of a task with more than BCAP blocks are fetched in place
@@ -512,15 +486,12 @@ __global__ __launch_bounds__(WAVE) __attribute__((amdgpu_waves_per_eu(N >= 128 ?
         const int nE = min(ECAP, L - e0);
         // the next round's entries go in flight now and wait in registers until this round is done
         const int nE_next = min(ECAP, L - e0 - ECAP);
-        stored_t next_ent[ECAP / WAVE];
-        uint16_t next_val[ECAP / WAVE];
+        uint32_t next_ent[ECAP / WAVE];
+        val_t next_val[ECAP / WAVE];
         if (nE_next > 0) {
 #pragma unroll
-            for (int k = 0; k < ECAP / WAVE; ++k) {
-                const int64_t i = (int64_t)t.res_begin + e0 + ECAP + min(k * WAVE + lane, nE_next - 1);
-                if constexpr (F32) next_ent[k] = E::load_ent(a.res_ent, i);
-                else load_blocked_entry(a.res_ent, i, next_ent[k], next_val[k]);
-            }
+            for (int k = 0; k < ECAP / WAVE; ++k)
+                load_blocked_entry(a.res_ent, (int64_t)t.res_begin + e0 + ECAP + min(k * WAVE + lane, nE_next - 1), next_ent[k], next_val[k]);
         }
         // runs are whole batches of U entries (the longest run, which sets the time of the round, needs no more batches
         // for it), so a batch is U consecutive entries from an aligned base address and never leaves the staged array
@@ -531,9 +502,7 @@ __global__ __launch_bounds__(WAVE) __attribute__((amdgpu_waves_per_eu(N >= 128 ?
         // A row is added into the tile by the group that holds its first entry (plain read-add-write:
         // one owner per row).  A group whose run starts inside a row keeps that row's partial sum in
         // registers instead and adds it after the others, in group order, so the order of additions is fixed.
-        bool first_is_shared;
-        if constexpr (F32) first_is_shared = q0 > 0 && q0 < q1 && E::lds_ent(ent_lds, q0 - 1).row == E::lds_ent(ent_lds, q0).row;
-        else first_is_shared = q0 > 0 && q0 < q1 && ((ent_lds[q0 - 1] ^ ent_lds[q0]) >> RES32_ROW_SHIFT) == 0;
+        bool first_is_shared = q0 > 0 && q0 < q1 && ((ent_lds[q0 - 1] ^ ent_lds[q0]) >> RES_ROW_SHIFT) == 0;
         int kept_row = -1;
         float kept[8] = {0, 0, 0, 0, 0, 0, 0, 0};
         int cur = -1;
@@ -563,22 +532,18 @@ __global__ __launch_bounds__(WAVE) __attribute__((amdgpu_waves_per_eu(N >= 128 ?
             const bool full = q + U <= q1;
             // U consecutive entries from one aligned base address; slots past the run hold valid entries whose fetch is
             // harmless and whose product is never formed
+            constexpr int VPW = E::VALS_PER_WORD;
             int ecol[U], erow[U];
             float eval[U];
-            if constexpr (F32) {
-                ent_t en[U];
-                E::template lds_batch<U>(ent_lds + q, en);
-#pragma unroll
-                for (int u = 0; u < U; ++u) { ecol[u] = en[u].col; erow[u] = en[u].row; eval[u] = en[u].val; }
-            } else {
-                uint32_t cr[U], vw[U / 2];
+            {
+                uint32_t cr[U], vw[U / VPW];
                 lds_words<U>(ent_lds + q, cr);
-                lds_words<U / 2>(val_lds + q, vw);
+                lds_words<U / VPW>(val_lds + q, vw);
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
-                    ecol[u] = (int)(cr[u] & RES32_COL_MASK);
-                    erow[u] = (int)(cr[u] >> RES32_ROW_SHIFT);
-                    eval[u] = (u & 1) ? E::pair_hi(vw[u >> 1]) : E::pair_lo(vw[u >> 1]);
+                    ecol[u] = (int)(cr[u] & RES_COL_MASK);
+                    erow[u] = (int)(cr[u] >> RES_ROW_SHIFT);
+                    eval[u] = (u % VPW) ? E::pair_hi(vw[u / VPW]) : E::pair_lo(vw[u / VPW]);
                 }
             }
 #pragma unroll
@@ -623,7 +588,7 @@ __global__ __launch_bounds__(WAVE) __attribute__((amdgpu_waves_per_eu(N >= 128 ?
 #pragma unroll
             for (int k = 0; k < ECAP / WAVE; ++k) {
                 ent_lds[k * WAVE + lane] = next_ent[k];
-                if constexpr (!F32) val_lds[k * WAVE + lane] = next_val[k];
+                val_lds[k * WAVE + lane] = next_val[k];
             }
             wave_sync();
         }
@@ -1119,10 +1084,11 @@ __global__ __launch_bounds__(256) void scatter_values_kernel(const T *src, const
         *reinterpret_cast<T *>(reinterpret_cast<char *>(dst) + i * stride + offset) = src[perm[i]];
 }
 
-// the same into the value runs of the blocked 16-bit entry layout
-__global__ __launch_bounds__(256) void scatter_blocked_values_kernel(const uint16_t *src, const int32_t *perm, int64_t n, unsigned char *dst) {
+// the same into the value runs of the blocked entry layout
+template <class T>
+__global__ __launch_bounds__(256) void scatter_blocked_values_kernel(const T *src, const int32_t *perm, int64_t n, unsigned char *dst) {
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x)
-        reinterpret_cast<uint16_t *>(dst + (i >> 6) * RES_BLOCK_BYTES + RES_BLOCK * 4)[i & (RES_BLOCK - 1)] = src[perm[i]];
+        reinterpret_cast<T *>(dst + (i / RES_BLOCK) * (RES_BLOCK * (4 + (int)sizeof(T))) + RES_BLOCK * 4)[i % RES_BLOCK] = src[perm[i]];
 }
 
 inline int hip_rc(hipError_t e) { return e == hipSuccess ? LIBRA_OK : LIBRA_ERR_HIP; }
@@ -1240,28 +1206,20 @@ std::vector<DevTask> pack_tasks(const libra_plan_t *P, const SubPlan &sp, bool s
 // Host staging of everything the kernels read in packed form; alive until the copies have finished.
 struct Staging {
     std::vector<DevTask> tasks_a, tasks_d;
-    std::vector<unsigned char> ent16;       // blocked words and values
-    std::vector<ResEnt32> ent32;
+    std::vector<unsigned char> res_blocks;  // SpMM residual entries: blocked words and values
     std::vector<SdEnt> sdent;
     std::vector<SdPv> sdpv;
 };
 
 // Record layouts written on the device when the arrays come from the device planner.
-__global__ __launch_bounds__(256) void pack_blocked_entries_kernel(const int32_t *col, const uint16_t *val, const int32_t *row, int64_t n, unsigned char *out) {
+template <class V>
+__global__ __launch_bounds__(256) void pack_blocked_entries_kernel(const int32_t *col, const V *val, const int32_t *row, int64_t n, unsigned char *out) {
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
-        unsigned char *blk = out + (i >> 6) * RES_BLOCK_BYTES;
-        const int slot = (int)(i & (RES_BLOCK - 1));
-        reinterpret_cast<uint32_t *>(blk)[slot] = (uint32_t)col[i] | (uint32_t)(row[i] % W) << RES32_ROW_SHIFT;
-        reinterpret_cast<uint16_t *>(blk + RES_BLOCK * 4)[slot] = val[i];
+        unsigned char *blk = out + (i / RES_BLOCK) * (RES_BLOCK * (4 + (int)sizeof(V)));
+        const int slot = (int)(i % RES_BLOCK);
+        reinterpret_cast<uint32_t *>(blk)[slot] = (uint32_t)col[i] | (uint32_t)(row[i] % W) << RES_ROW_SHIFT;
+        reinterpret_cast<V *>(blk + RES_BLOCK * 4)[slot] = val[i];
     }
-}
-__device__ inline ResEnt32 make_entry(int32_t col, float val, int row_in_window) {
-    return ResEnt32{(uint32_t)col | (uint32_t)row_in_window << RES32_ROW_SHIFT, val};
-}
-template <class ENT, class V>
-__global__ __launch_bounds__(256) void pack_spmm_entries_kernel(const int32_t *col, const V *val, const int32_t *row, int64_t n, ENT *out) {
-    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x)
-        out[i] = make_entry(col[i], val[i], row[i] % W);
 }
 template <class V>
 __global__ __launch_bounds__(256) void pack_sddmm_entries_kernel(const int32_t *row, const int32_t *col, const int32_t *perm, const V *val, int64_t n, SdEnt *out) {
@@ -1294,26 +1252,18 @@ void layout(libra_plan_t *P, Uploader &u, Staging *st, const DeviceSource *da, c
     u.put(H(sa.dense_val.data()), da ? da->dense_val : nullptr, (size_t)sa.n.dense * vs, sa.dev.dense_val);
     u.put(H(sa.dense_perm.data()), da ? da->dense_perm : nullptr, (size_t)sa.n.dense * 4, sa.dev.dense_perm);
     const size_t nres = (size_t)sa.n.res;
+    const size_t res_bytes = res_blocked_bytes(nres + 1, vs);      // + 1: a task without entries still reads the slot at its (clamped) first index
     if (from_host) {
         const int Wp = P->o.W;
-        if (f16) {
-            st->ent16.assign(res_blocked_bytes(nres + 1), 0);
-            const uint16_t *v = reinterpret_cast<const uint16_t *>(sa.res_val.data());
-            for (size_t i = 0; i < nres; ++i) {
-                unsigned char *blk = st->ent16.data() + i / RES_BLOCK * RES_BLOCK_BYTES;
-                const uint32_t word = (uint32_t)sa.res_col[i] | (uint32_t)(sa.res_row[i] % Wp) << RES32_ROW_SHIFT;
-                std::memcpy(blk + i % RES_BLOCK * 4, &word, 4);
-                std::memcpy(blk + RES_BLOCK * 4 + i % RES_BLOCK * 2, &v[i], 2);
-            }
-        } else {
-            st->ent32.resize(nres);
-            const float *v = reinterpret_cast<const float *>(sa.res_val.data());
-            for (size_t i = 0; i < nres; ++i)
-                st->ent32[i] = {(uint32_t)sa.res_col[i] | (uint32_t)(sa.res_row[i] % Wp) << RES32_ROW_SHIFT, v[i]};
+        st->res_blocks.assign(res_bytes, 0);
+        for (size_t i = 0; i < nres; ++i) {
+            unsigned char *blk = st->res_blocks.data() + i / RES_BLOCK * res_block_bytes(vs);
+            const uint32_t word = (uint32_t)sa.res_col[i] | (uint32_t)(sa.res_row[i] % Wp) << RES_ROW_SHIFT;
+            std::memcpy(blk + i % RES_BLOCK * 4, &word, 4);
+            std::memcpy(blk + RES_BLOCK * 4 + i % RES_BLOCK * vs, sa.res_val.data() + i * vs, vs);
         }
     }
-    if (f16) u.put(from_host ? (const void *)st->ent16.data() : nullptr, nullptr, res_blocked_bytes(nres + 1), sa.dev.res_ent);     // + 1: a task without entries still reads the slot at its (clamped) first index
-    else u.put(from_host ? (const void *)st->ent32.data() : nullptr, nullptr, nres * sizeof(ResEnt32), sa.dev.res_ent);
+    u.put(from_host ? (const void *)st->res_blocks.data() : nullptr, nullptr, res_bytes, sa.dev.res_ent);
     u.put(H(sa.res_perm.data()), da ? da->res_perm : nullptr, nres * 4, sa.dev.res_perm);
     u.put(H(sa.zero_rows.data()), da ? da->zero_rows : nullptr, (size_t)sa.n.zero_rows * 4, sa.dev.zero_rows);
     // ---- SDDMM ----
@@ -1356,7 +1306,7 @@ size_t libra::plan_buffer_bytes(const libra_plan_t *plan) {
 int libra::adopt_device_arrays(libra_plan_t *P, const DeviceSource &da, const DeviceSource &dd, void *dev_buf, size_t bytes, void *stream) {
     if (!dev_buf) return LIBRA_ERR_NULL;
     if (bytes < plan_buffer_bytes(P) || ((uintptr_t)dev_buf & 255)) return LIBRA_ERR_BUFFER;
-    if (P->Kc > (int64_t)RES32_COL_MASK + 1) return LIBRA_ERR_UNSUPPORTED;    // a residual entry keeps its column in RES32_ROW_SHIFT bits
+    if (P->Kc > (int64_t)RES_COL_MASK + 1) return LIBRA_ERR_UNSUPPORTED;    // a residual entry keeps its column in RES_ROW_SHIFT bits
     hipStream_t s = (hipStream_t)stream;
     try {
         Staging st;
@@ -1368,10 +1318,10 @@ int libra::adopt_device_arrays(libra_plan_t *P, const DeviceSource &da, const De
         const SubPlan &sa = P->spmm, &sd = P->sddmm;
         if (sa.n.res) {
             if (P->vdt == LIBRA_F32)
-                hipLaunchKernelGGL((pack_spmm_entries_kernel<ResEnt32, float>), grid(sa.n.res), dim3(256), 0, s, da.res_col,
-                                   (const float *)da.res_val, da.res_row, sa.n.res, (ResEnt32 *)sa.dev.res_ent);
+                hipLaunchKernelGGL((pack_blocked_entries_kernel<float>), grid(sa.n.res), dim3(256), 0, s, da.res_col,
+                                   (const float *)da.res_val, da.res_row, sa.n.res, (unsigned char *)sa.dev.res_ent);
             else
-                hipLaunchKernelGGL(pack_blocked_entries_kernel, grid(sa.n.res), dim3(256), 0, s, da.res_col,
+                hipLaunchKernelGGL((pack_blocked_entries_kernel<uint16_t>), grid(sa.n.res), dim3(256), 0, s, da.res_col,
                                    (const uint16_t *)da.res_val, da.res_row, sa.n.res, (unsigned char *)sa.dev.res_ent);
         }
         if (sd.n.res) {
@@ -1411,7 +1361,7 @@ extern "C" int libra_plan_upload(libra_plan_t *plan, void *dev_buf, size_t bytes
     size_t need = 0;
     libra_plan_device_bytes(plan, &need);
     if (bytes < need || ((uintptr_t)dev_buf & 255)) return LIBRA_ERR_BUFFER;
-    if (plan->Kc > (int64_t)RES32_COL_MASK + 1) return LIBRA_ERR_UNSUPPORTED;      // a residual entry keeps its column in RES32_ROW_SHIFT bits
+    if (plan->Kc > (int64_t)RES_COL_MASK + 1) return LIBRA_ERR_UNSUPPORTED;      // a residual entry keeps its column in RES_ROW_SHIFT bits
     try {
         Staging st;
         Uploader u;
@@ -1565,15 +1515,17 @@ extern "C" int libra_plan_set_values_for(libra_plan_t *P, const void *vals, int 
     const SubPlan &sa = P->spmm, &sd = P->sddmm;
     const Seg segs[4] = {
         {sa.dev.dense_perm, sa.dev.dense_val, sa.n.dense, vs, 0},
-        {sa.dev.res_perm, sa.dev.res_ent, sa.n.res, f16 ? 0 : (int)sizeof(ResEnt32), 4},       // stride 0: the blocked 16-bit layout
+        {sa.dev.res_perm, sa.dev.res_ent, sa.n.res, 0, 0},                  // stride 0: the blocked entry layout
         {sd.dev.dense_perm, sd.dev.dense_pv, sd.n.dense, (int)sizeof(SdPv), 4},
         {sd.dev.res_perm, sd.dev.res_ent, sd.n.res, (int)sizeof(SdEnt), 12}};
     for (int k = 0; k < 4; ++k) {
         const Seg &g = segs[k];
         if (g.n == 0 || !(ops & (k < 2 ? LIBRA_OP_SPMM : LIBRA_OP_SDDMM))) continue;
         const unsigned blocks = (unsigned)std::min<int64_t>((g.n + 255) / 256, 1 << 16);
-        if (f16 && g.stride == 0)
-            hipLaunchKernelGGL(scatter_blocked_values_kernel, dim3(blocks), dim3(256), 0, s, (const uint16_t *)vals, g.perm, g.n, (unsigned char *)g.dst);
+        if (g.stride == 0 && f16)
+            hipLaunchKernelGGL((scatter_blocked_values_kernel<uint16_t>), dim3(blocks), dim3(256), 0, s, (const uint16_t *)vals, g.perm, g.n, (unsigned char *)g.dst);
+        else if (g.stride == 0)
+            hipLaunchKernelGGL((scatter_blocked_values_kernel<float>), dim3(blocks), dim3(256), 0, s, (const float *)vals, g.perm, g.n, (unsigned char *)g.dst);
         else if (f16)
             hipLaunchKernelGGL((scatter_values_kernel<uint16_t>), dim3(blocks), dim3(256), 0, s, (const uint16_t *)vals, g.perm, g.n, g.dst, g.stride, g.offset);
         else

@@ -33,21 +33,16 @@ struct DevTask {
     int32_t val_begin;          // first packed value of block blk_begin
 };
 
-// Residual entries of the SpMM sub-plan, 16-bit values: blocks of RES_BLOCK entries, each block RES_BLOCK 32-bit words
-// (column in the low RES32_ROW_SHIFT bits, row inside the window above them) followed by RES_BLOCK 2-byte values, 384
-// bytes.  Entry i is slot i % RES_BLOCK of block i / RES_BLOCK, so a task's entries are addressed from their index alone,
-// a task reads words and values from neighbouring lines, and new values overwrite whole 128-byte runs.
+// Residual entries of the SpMM sub-plan: blocks of RES_BLOCK entries, each block RES_BLOCK 32-bit words (column in the
+// low RES_ROW_SHIFT bits, row inside the window above them) followed by RES_BLOCK values of the storage type: 384 bytes
+// with 16-bit values, 512 with fp32.  Entry i is slot i % RES_BLOCK of block i / RES_BLOCK, so a task's entries are
+// addressed from their index alone, a task reads words and values from neighbouring lines, and new values overwrite
+// whole 128-byte runs.  A plan on the device is therefore limited to 2^27 columns.
 constexpr int RES_BLOCK = 64;
-constexpr int RES_BLOCK_BYTES = RES_BLOCK * 6;
-inline size_t res_blocked_bytes(size_t n) { return (n + RES_BLOCK - 1) / RES_BLOCK * RES_BLOCK_BYTES; }
-// fp32 values: 8-byte records.  The first word holds the column in its low RES32_ROW_SHIFT bits and the row inside
-// the window above them, so a plan on the device is limited to 2^27 columns (both layouts).
-constexpr int RES32_ROW_SHIFT = 27;                             // windows of up to 32 rows
-constexpr uint32_t RES32_COL_MASK = (1u << RES32_ROW_SHIFT) - 1u;
-struct ResEnt32 {
-    uint32_t col_row;
-    float val;
-};
+constexpr int RES_ROW_SHIFT = 27;                               // windows of up to 32 rows
+constexpr uint32_t RES_COL_MASK = (1u << RES_ROW_SHIFT) - 1u;
+inline size_t res_block_bytes(size_t value_bytes) { return RES_BLOCK * (4 + value_bytes); }
+inline size_t res_blocked_bytes(size_t n, size_t value_bytes) { return (n + RES_BLOCK - 1) / RES_BLOCK * res_block_bytes(value_bytes); }
 // Residual entry of the SDDMM sub-plan: 16 bytes.
 struct SdEnt {
     int32_t row, col, perm;
@@ -69,7 +64,7 @@ struct SubPlanDev {
     void *dense_val = nullptr;          // SpMM: packed values in bit order
     void *dense_pv = nullptr;           // SDDMM: SdPv per packed value
     const int32_t *dense_perm = nullptr;
-    void *res_ent = nullptr;            // ResEnt16 / ResEnt32 (SpMM) or SdEnt (SDDMM)
+    void *res_ent = nullptr;            // SpMM: blocked words and values (see RES_BLOCK); SDDMM: SdEnt per entry
     const int32_t *res_perm = nullptr;
     const int32_t *zero_rows = nullptr;
 };
