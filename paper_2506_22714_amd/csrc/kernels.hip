@@ -853,44 +853,51 @@ __global__ __launch_bounds__(WAVE) void sddmm_task_kernel(SddmmArgs a) {
 // ---------------------------------------------------------------------------------------
 // Edge softmax (one wave per row, rows dealt round-robin) and value scatter
 // ---------------------------------------------------------------------------------------
-// Maximum over the 16 lanes of a DPP row; every lane gets the result.
-__device__ inline float row16_max(float s) {
+// Maximum over a group of LPN (2, 4, 8 or 16) neighbouring lanes of a DPP row; every lane gets the result.
+template <int LPN>
+__device__ inline float group_max(float s) {
+    static_assert(LPN == 2 || LPN == 4 || LPN == 8 || LPN == 16, "inside one DPP row");
     auto dpp = [](float v, auto ctrl) {
         return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), decltype(ctrl)::value, 0xf, 0xf, true));
     };
-    s = fmaxf(s, dpp(s, std::integral_constant<int, 0xB1>{}));      // quad_perm [1,0,3,2]
-    s = fmaxf(s, dpp(s, std::integral_constant<int, 0x4E>{}));      // quad_perm [2,3,0,1]
-    s = fmaxf(s, dpp(s, std::integral_constant<int, 0x141>{}));     // row_half_mirror
-    s = fmaxf(s, dpp(s, std::integral_constant<int, 0x140>{}));     // row_mirror
+    if constexpr (LPN >= 2) s = fmaxf(s, dpp(s, std::integral_constant<int, 0xB1>{}));      // quad_perm [1,0,3,2]
+    if constexpr (LPN >= 4) s = fmaxf(s, dpp(s, std::integral_constant<int, 0x4E>{}));      // quad_perm [2,3,0,1]
+    if constexpr (LPN >= 8) s = fmaxf(s, dpp(s, std::integral_constant<int, 0x141>{}));     // row_half_mirror
+    if constexpr (LPN >= 16) s = fmaxf(s, dpp(s, std::integral_constant<int, 0x140>{}));    // row_mirror
     return s;
 }
+constexpr int SHORT_LANES = 8;                  // lanes per row of up to 64 nonzeros
+constexpr int SHORT_LOADS = 64 / SHORT_LANES;   // scores per lane
 
 
-// Rows of up to 64 nonzeros (the bulk of a graph): 16 lanes per row, read once and kept in registers.
+// Rows of up to 64 nonzeros (the bulk of a graph): SHORT_LANES lanes per row, read once and kept in registers.
 template <class TO>
 __device__ inline void edge_softmax_short_rows(unsigned block, unsigned nblocks, const int32_t *rowptr, int64_t M, const float *score, float scale, TO *out) {
-    const int l = threadIdx.x & 15;
-    const int64_t group = ((int64_t)block * blockDim.x + threadIdx.x) >> 4;
-    const int64_t ngroups = ((int64_t)nblocks * blockDim.x) >> 4;
+    constexpr int SL = SHORT_LANES, KPL = SHORT_LOADS;
+    const int l = threadIdx.x % SL;
+    const int64_t group = ((int64_t)block * blockDim.x + threadIdx.x) / SL;
+    const int64_t ngroups = ((int64_t)nblocks * blockDim.x) / SL;
     for (int64_t i = group; i < M; i += ngroups) {
         const int s = rowptr[i], n = rowptr[i + 1] - s;
         if (n == 0 || n > 64) continue;         // longer rows are listed at plan time and run below
         {
-            float v[4];
+            float v[KPL];
 #pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                const int q = l + 16 * k;
-                v[k] = scale * score[s + min(q, n - 1)];
-                if (q >= n) v[k] = -INFINITY;
+            for (int k = 0; k < KPL; ++k) v[k] = score[s + min(l + SL * k, n - 1)];
+            float mx = -INFINITY;
+#pragma unroll
+            for (int k = 0; k < KPL; ++k) {
+                v[k] = l + SL * k < n ? scale * v[k] : -INFINITY;
+                mx = fmaxf(mx, v[k]);
             }
-            const float mx = row16_max(fmaxf(fmaxf(v[0], v[1]), fmaxf(v[2], v[3])));
-            float ex[4], den = 0.f;
+            mx = group_max<SL>(mx);
+            float den = 0.f;
 #pragma unroll
-            for (int k = 0; k < 4; ++k) { ex[k] = __expf(v[k] - mx); den += ex[k]; }      // exp(-inf) = 0 for the padding
-            const float inv = 1.f / group_sum<16>(den);
+            for (int k = 0; k < KPL; ++k) { v[k] = __expf(v[k] - mx); den += v[k]; }      // exp(-inf) = 0 for the padding
+            const float inv = 1.f / group_sum<SL>(den);
 #pragma unroll
-            for (int k = 0; k < 4; ++k)
-                if (l + 16 * k < n) out[s + l + 16 * k] = to_storage<TO>(ex[k] * inv);
+            for (int k = 0; k < KPL; ++k)
+                if (l + SL * k < n) out[s + l + SL * k] = to_storage<TO>(v[k] * inv);
         }
     }
 }
@@ -989,7 +996,7 @@ struct SoftmaxRows {
 __host__ inline SoftmaxRows softmax_rows(const libra_plan_t *P) {
     SoftmaxRows r{P->d_rowptr, P->d_long_rows, P->d_medium_rows, P->M, (int32_t)P->long_rows.size(), (int32_t)P->medium_rows.size(), 0u, 0u};
     r.medium_blocks = ((uint32_t)r.nmedium + 256u / MEDIUM_LANES - 1u) / (256u / MEDIUM_LANES);
-    r.short_blocks = (uint32_t)std::min<int64_t>((P->M + 15) / 16, 1 << 18);
+    r.short_blocks = (uint32_t)std::min<int64_t>((P->M * SHORT_LANES + 255) / 256, 1 << 18);
     return r;
 }
 template <class TO>
@@ -1007,24 +1014,31 @@ template <> __device__ inline float from_storage<bf16_t>(bf16_t x) { return __ui
 
 template <class TA>
 __device__ inline void edge_softmax_bwd_short_rows(unsigned block, unsigned nblocks, const int32_t *rowptr, int64_t M, const TA *alpha, const float *dalpha, float scale, float *dscore) {
-    const int l = threadIdx.x & 15;
-    const int64_t group = ((int64_t)block * blockDim.x + threadIdx.x) >> 4;
-    const int64_t ngroups = ((int64_t)nblocks * blockDim.x) >> 4;
+    constexpr int SL = SHORT_LANES, KPL = SHORT_LOADS;
+    const int l = threadIdx.x % SL;
+    const int64_t group = ((int64_t)block * blockDim.x + threadIdx.x) / SL;
+    const int64_t ngroups = ((int64_t)nblocks * blockDim.x) / SL;
     for (int64_t i = group; i < M; i += ngroups) {
         const int s = rowptr[i], n = rowptr[i + 1] - s;
         if (n == 0 || n > 64) continue;
-        float a[4], g[4], dot = 0.f;
+        // clamped addresses, all loads in flight together; the padding contributes zero
+        TA ar[KPL];
+        float a[KPL], g[KPL], dot = 0.f;
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const int q = l + 16 * k;
-            a[k] = q < n ? from_storage<TA>(alpha[s + q]) : 0.f;
-            g[k] = q < n ? dalpha[s + q] : 0.f;
+        for (int k = 0; k < KPL; ++k) {
+            const int q = s + min(l + SL * k, n - 1);
+            ar[k] = alpha[q];
+            g[k] = dalpha[q];
+        }
+#pragma unroll
+        for (int k = 0; k < KPL; ++k) {
+            a[k] = l + SL * k < n ? from_storage<TA>(ar[k]) : 0.f;
             dot += a[k] * g[k];
         }
-        dot = group_sum<16>(dot);
+        dot = group_sum<SL>(dot);
 #pragma unroll
-        for (int k = 0; k < 4; ++k)
-            if (l + 16 * k < n) dscore[s + l + 16 * k] = scale * a[k] * (g[k] - dot);
+        for (int k = 0; k < KPL; ++k)
+            if (l + SL * k < n) dscore[s + l + SL * k] = scale * a[k] * (g[k] - dot);
     }
 }
 
