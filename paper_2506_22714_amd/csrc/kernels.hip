@@ -107,7 +107,7 @@ template <> struct Elem<half_t> {
     }
 };
 template <> struct Elem<bf16_t> : Elem<half_t> {
-    // same 16-byte pieces and entry records as binary16; only the widening differs (a shift)
+    // same 16-byte pieces and 2-byte entry values as binary16; only the widening differs (a shift)
     __device__ static float widen(uint32_t bits16) { return __uint_as_float(bits16 << 16); }
     __device__ static void fma(float v, const raw_t &r, float (&acc)[8]) {
         const uint32_t w[4] = {r.x, r.y, r.z, r.w};
@@ -1253,7 +1253,6 @@ void layout(libra_plan_t *P, Uploader &u, Staging *st, const DeviceSource *da, c
     u.putv(P->long_rows, P->d_long_rows);
     u.putv(P->medium_rows, P->d_medium_rows);
     SubPlan &sa = P->spmm, &sd = P->sddmm;
-    const bool f16 = P->vdt != LIBRA_F32;      // 16-bit storage (binary16 or bfloat16): same records
     const size_t vs = (size_t)P->vsize;
     const bool from_host = st && !da;
     auto H = [&](const void *p) { return from_host ? p : nullptr; };
