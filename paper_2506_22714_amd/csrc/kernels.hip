@@ -277,7 +277,7 @@ __global__ __launch_bounds__(WAVE) __attribute__((amdgpu_waves_per_eu(N >= 128 ?
     __shared__ __attribute__((aligned(16))) uint32_t ent_lds[ECAP];          // the staged entries' words (column | row in window) ...
     __shared__ __attribute__((aligned(16))) val_t val_lds[ECAP];             // ... and values
     __shared__ __attribute__((aligned(16))) int32_t cols_lds[DENSE ? BCAP * KB : 4];
-    __shared__ __attribute__((aligned(16))) uint64_t bm_lds[DENSE ? BCAP * 4 : 2];
+    __shared__ __attribute__((aligned(16))) uint64_t bm_lds[DENSE ? WAVE : 2];   // BCAP * 4 words used
     float *tile = reinterpret_cast<float *>(smem);
 
     // workgroup b: die b mod 8, then the pieces of one task next to each other (they read the same plan data through
@@ -321,7 +321,8 @@ __global__ __launch_bounds__(WAVE) __attribute__((amdgpu_waves_per_eu(N >= 128 ?
             const uint64_t w = a.blk_bitmap[(int64_t)t.blk_begin * 4 + max(min(lane, nb * 4 - 1), 0)];
 #pragma unroll
             for (int k = 0; k < BCAP * KB / WAVE; ++k) cols_lds[k * WAVE + lane] = c[k];
-            if (lane < BCAP * 4) bm_lds[lane] = w;
+            bm_lds[lane] = w;        // all 64 lanes write (the upper ones a copy of the last word): under a `lane < 32` branch
+                                     // the compiler moves the load there too and issues it only after the loads before it returned
         }
 #pragma unroll
         for (int k = 0; k < ECAP / WAVE; ++k) {
@@ -339,7 +340,8 @@ __global__ __launch_bounds__(WAVE) __attribute__((amdgpu_waves_per_eu(N >= 128 ?
             const uint64_t w = a.blk_bitmap[(int64_t)(t.blk_begin + b0) * 4 + min(lane, nb * 4 - 1)];
 #pragma unroll
             for (int k = 0; k < BCAP * KB / WAVE; ++k) cols_lds[k * WAVE + lane] = c[k];
-            if (lane < BCAP * 4) bm_lds[lane] = w;
+            bm_lds[lane] = w;        // all 64 lanes write (the upper ones a copy of the last word): under a `lane < 32` branch
+                                     // the compiler moves the load there too and issues it only after the loads before it returned
         }
     };
     wave_sync();
