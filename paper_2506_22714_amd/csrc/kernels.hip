@@ -396,12 +396,22 @@ __global__ __launch_bounds__(WAVE) __attribute__((amdgpu_waves_per_eu(N >= 128 ?
                     // ... and this lane's 4 A elements (row j, slots 4g..4g+3) of each block, decoded from its bitmap
                     typedef typename std::conditional<F32, float, short>::type aval_t;
                     typedef typename std::conditional<F32, float4_t, short4_t>::type afrag_t;
+                    // All value loads of the FPI blocks are issued before any of them is used: unconditional loads (an unset
+                    // slot reads a neighbouring value, at most 3 values past the array's end, inside its 16 spare bytes; a
+                    // block past the last one repeats the last one), and the selects afterwards.  With two blocks per round
+                    // trip an opaque move sits between the two: without it the compiler moves a load under its select's
+                    // condition and waits block by block (community N=128 261 -> 255 us with it, GAT graph N=64 624 -> 581 us
+                    // against the same code without it); with one block per round trip (fp32) it only forces the wait early
+                    // (community 388 -> 436 us) and is left out.
                     afrag_t af[FPI];
+                    typedef typename std::conditional<F32, float, int>::type areg_t;
+                    areg_t av[FPI][4];
+                    unsigned nib[FPI];
+                    {
+                        int vb = vbase;
 #pragma unroll
-                    for (int x = 0; x < FPI; ++x) {
-                        af[x] = afrag_t{0, 0, 0, 0};
-                        if (x < nb) {
-                            const uint64_t *bm = &bm_lds[(bb + x) * 4];
+                        for (int x = 0; x < FPI; ++x) {
+                            const uint64_t *bm = &bm_lds[(bb + min(x, nb - 1)) * 4];
                             const uint64_t w0 = bm[0], w1 = bm[1], w2 = bm[2], w3 = bm[3];
                             const int q = j >> 2;
                             const uint64_t word = q == 0 ? w0 : q == 1 ? w1 : q == 2 ? w2 : w3;
@@ -409,18 +419,23 @@ __global__ __launch_bounds__(WAVE) __attribute__((amdgpu_waves_per_eu(N >= 128 ?
                             int prefix = (q > 0 ? c0 : 0) + (q > 1 ? c1 : 0) + (q > 2 ? c2 : 0);
                             const int bitpos = (j & 3) * 16 + 4 * g;
                             prefix += __popcll(word & ((1ull << bitpos) - 1ull));
-                            const unsigned nib = (unsigned)(word >> bitpos) & 0xFu;
-                            const aval_t *vals = reinterpret_cast<const aval_t *>(a.dense_val) + vbase + prefix;
-                            // unconditional loads (an unset slot reads a neighbouring value, at most 3 values past the
-                            // array's end, inside its 16 spare bytes) and a select afterwards
-                            aval_t av[4];
+                            nib[x] = x < nb ? (unsigned)(word >> bitpos) & 0xFu : 0u;
+                            const aval_t *vals = reinterpret_cast<const aval_t *>(a.dense_val) + vb + prefix;
 #pragma unroll
-                            for (int e = 0; e < 4; ++e) av[e] = vals[__popc(nib & ((1u << e) - 1u))];
-#pragma unroll
-                            for (int e = 0; e < 4; ++e) af[x][e] = (nib >> e & 1u) ? av[e] : (aval_t)0;
-                            vbase += c0 + c1 + c2 + c3;
+                            for (int e = 0; e < 4; ++e) av[x][e] = (areg_t)vals[__popc(nib[x] & ((1u << e) - 1u))];
+                            if (x + 1 < nb) vb += c0 + c1 + c2 + c3;       // the next block's values follow; a repeated block re-reads its own
+                            if (x < nb) vbase += c0 + c1 + c2 + c3;
                         }
                     }
+#pragma unroll
+                    for (int x = 0; x < FPI; ++x)
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            if constexpr (FPI > 1) asm volatile("" : "+v"(av[x][e]));
+#pragma unroll
+                    for (int x = 0; x < FPI; ++x)
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) af[x][e] = (nib[x] >> e & 1u) ? (aval_t)av[x][e] : (aval_t)0;
                     // the fetched rows go through the LDS stage BPI blocks at a time
 #pragma unroll
                     for (int h = 0; h < H; ++h) {
