@@ -739,6 +739,12 @@ __device__ inline void sddmm_window_task(const SddmmArgs &a, const DevTask &t) {
 #pragma unroll
             for (int s = 0; s < KS; ++s) d[x] = mfma_k32<T>(xa[s], yb[x][s], d[x]);
         }
+        // every record load has been issued by here: without this the compiler moves the last one under the first
+        // store's condition, where it is issued after the products and waited for on its own
+#pragma unroll
+        for (int x = 0; x < BB; ++x)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) asm volatile("" : "+v"(pv[x][e].x), "+v"(pv[x][e].y));
 #pragma unroll
         for (int x = 0; x < BB; ++x)
 #pragma unroll
