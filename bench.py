@@ -30,7 +30,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per libra_spmm call on the default workload, from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE,
 # each scaled by the reading of the 1 GiB copy (--copy-calibration); see profiles/spmm_powerlaw_n128_counters.md.
 # Only quoted when the run uses exactly that configuration.
-MEASURED_TRAFFIC_BYTES = {("powerlaw", 128): int((2.0 * 103_900 + 1.0 * 75_430) * 1024)}
+MEASURED_TRAFFIC_BYTES = {("powerlaw", 128): int((2.0 * 101_740 + 1.0 * 75_412) * 1024)}
 
 
 def spmm_algorithmic_bytes(A, N: int, kref: int, es: int = 2) -> int:
