@@ -716,3 +716,48 @@ def test_full_gat_config_one_head_sampled():
     assert err <= bound(TOL_F16, deg[rows].max()), err
     assert torch.isfinite(C).all()
     p.close()
+
+
+# ---------------------------------------------- seeded sweep over shapes, value types, modes, orders and both planners
+def test_seeded_sweep_of_shapes_types_modes_and_planners():
+    """Small matrices of drawn shape and density (some with a long row), drawn feature widths, value type, mode and
+    order flags, planned on the host and on the device; SpMM and SDDMM against the oracle, then again after new values."""
+    rng = np.random.default_rng(20250622)
+    for it in range(24):
+        M, Kc = int(rng.integers(1, 700)), int(rng.integers(8, 600))
+        density = float(rng.choice([0.002, 0.01, 0.05, 0.2, 0.5]))
+        A = wl.random_pattern(M, Kc, density, seed=int(rng.integers(1 << 30)), empty_rows=float(rng.choice([0, 0.3])))
+        if M > 8 and Kc > 300 and rng.random() < 0.5:
+            A = wl.with_long_rows(A, [int(rng.integers(0, M))], int(rng.integers(100, Kc)), seed=it)
+        f32 = bool(rng.random() < 0.3)
+        N = int(rng.choice([1, 2, 3, 4, 8])) * (16 if f32 else 32)
+        K = int(rng.choice([32, 64, 128]))
+        mode = int(rng.choice([lb.MODE_HYBRID, lb.MODE_HYBRID, lb.MODE_DENSE_ONLY, lb.MODE_SCALAR_ONLY]))
+        flags = int(rng.choice([0, lb.FLAG_XCD_ORDER, lb.FLAG_NO_XCD_ORDER, lb.FLAG_SEGMENTS_BY_COST, lb.FLAG_TWO_KERNELS]))
+        dt, tol = (np.float32, TOL_F32) if f32 else (np.float16, TOL_F16)
+        val = A.val.astype(dt)
+        B, X, Y = (wl.dense_normal(r, c, seed=it + s).astype(dt) for r, c, s in ((A.Kc, N, 100), (A.M, K, 200), (A.Kc, K, 300)))
+        new_val = wl.uniform_values(np.random.default_rng(it), A.nnz).astype(dt)
+        for planner in ("host", "device"):
+            if planner == "device" and A.nnz == 0:
+                continue
+            if planner == "host":
+                p = lb.Plan(A.M, A.Kc, A.rowptr, A.col, val, mode=mode, flags=flags).upload()
+            else:
+                rp, col, v = (dev(x) for x in (A.rowptr.astype(np.int32), A.col.astype(np.int32), val))
+                p = lb.Plan.from_device_csr(A.M, A.Kc, rp, col, v, resident=True, keep_host_copy=False, mode=mode, flags=flags)
+            where = f"case {it} ({planner} planner): M={M} Kc={Kc} nnz={A.nnz} f32={f32} N={N} K={K} mode={mode} flags={flags}"
+            out = torch.full((A.nnz,), float("nan"), dtype=torch.float32, device="cuda")
+            for values in (val, new_val):
+                if values is new_val:
+                    if A.nnz == 0:
+                        break
+                    p.set_values(dev(new_val))
+                try:
+                    check_spmm(A, B, p.spmm(dev(B)).cpu().numpy(), tol, val=values)
+                    if A.nnz:
+                        p.sddmm(dev(X), dev(Y), out=out)
+                        check_sddmm(A, X, Y, out.cpu().numpy(), tol, val=values)
+                except AssertionError as e:
+                    raise AssertionError(f"{where}: {e}") from e
+            p.close()
