@@ -78,9 +78,7 @@ extern "C" {
                                            rows are sorted by their first column and cut into one run per die, so that a
                                            die fetches dense-operand rows of one column range only and its L2 holds eight
                                            times as many distinct hot rows; the flat SDDMM segments that lie inside one row are
-                                           placed the same way.  On this box: GAT graph SpMM 868 -> 644 us, SDDMM 1.02 -> 0.80 ms;
-                                           irregular graph 2.29 -> 1.95 ms and 2.37 -> 1.95 ms; power-law config 72.6 -> 71.4 us
-                                           and 32.1 -> 30.7 us */
+                                           placed the same way */
 #define LIBRA_FLAG_TWO_KERNELS    128u  /* libra_spmm runs the task table twice on the stream: first the dense blocks (MFMA), then the
                                            residual nonzeros (VALU), which add to what the first launch wrote - the paper's
                                            sequential schedule of its two kernels (Section 4.4.1).  Same results up to the order
@@ -209,11 +207,17 @@ int libra_plan_device(int64_t M, int64_t Kc, int64_t nnz, const int32_t *d_rowpt
                       void *workspace, size_t workspace_bytes, void *plan_buf, size_t plan_bytes,
                       int keep_host_copy, void *stream, libra_plan_t **out);
 
-/* Bytes of device memory the plan's arrays need (256-byte aligned layout). */
+/*
+ * libra_plan_device_bytes - bytes of device memory the plan's arrays need (256-byte aligned layout).  The plan is the
+ * paper's one-off preprocessing result (Section 4.1: the matrix is translated once into bitmap blocks for the matrix
+ * unit and a CSR-like residual for the scalar path, item 3, and reused by every later call); this is the size of that
+ * translated form, which the caller allocates.  Errors: NULL.
+ */
 int libra_plan_device_bytes(const libra_plan_t *plan, size_t *bytes);
 
 /*
- * libra_plan_upload - copy the plan's arrays into caller-owned device memory.
+ * libra_plan_upload - copy the plan's arrays (the translated formats of Section 4.1, item 3: bitmap blocks, packed
+ * values, residual entries, task tables of Section 4.3) into caller-owned device memory, once per matrix.
  *   dev_buf  device pointer, 256-byte aligned, at least libra_plan_device_bytes() bytes;
  *            the plan borrows it until libra_plan_destroy or the next upload.
  * The copies are enqueued on `stream` and the stream is synchronised before returning
@@ -232,6 +236,11 @@ int libra_plan_upload(libra_plan_t *plan, void *dev_buf, size_t bytes, void *str
  * Dense blocks run on MFMA (operands of the plan's value type, fp32 accumulate), residual nonzeros on the VALU (fp32 FMA);
  * rows with one writer are stored once, rows with several writers are cleared and accumulated with
  * fp32 atomics (their summation order is not deterministic).
+ * B must hold finite numbers: a dense block multiplies the empty slots of its tile (zeros) by the gathered rows of B, so
+ * an Inf or NaN in row j of B reaches every row of a window that has a dense block with column j, not only the rows
+ * with a nonzero in column j (0 * Inf = NaN), where the definition would leave them untouched.  The same holds for
+ * X and Y in libra_sddmm only for outputs that exist (an output is always a sampled product).
+ * ldb * (bytes per element) must be below 2^32.
  * Errors: NULL, SHAPE, UNSUPPORTED, NOT_UPLOADED, NOT_BUILT, HIP.
  */
 int libra_spmm(const libra_plan_t *plan, const void *B, int32_t N, int64_t ldb,
@@ -304,7 +313,9 @@ int libra_probe_coissue(int iters, float *sink_dev, float times_us[3], void *str
 
 /*
  * libra_plan_set_values - replace A's values (same pattern): scatters CSR-ordered device values into the
- * packed dense-block and residual arrays of both sub-plans' device copies.  The host copy keeps the old
+ * packed dense-block and residual arrays of both sub-plans' device copies.  The distribution of Section 4.2 depends
+ * on the pattern only, so the preprocessing of Section 4.1 is reused as it is when only the values change (an
+ * attention layer writes new coefficients on a fixed graph in every pass, Section 5.5).  The host copy keeps the old
  * values.  `dtype` must equal the plan's value type.  Errors: NULL, DTYPE, NOT_UPLOADED, HIP.
  */
 int libra_plan_set_values(libra_plan_t *plan, const void *vals_csr_dev, int dtype, void *stream);

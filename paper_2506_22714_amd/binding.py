@@ -240,11 +240,24 @@ def libra_csr_transpose_device(M: int, Kc: int, nnz: int, rowptr_ptr: int, col_p
                                             C.c_void_p(stream)), "libra_csr_transpose_device")
 
 
+def _csr_operands(M: int, rowptr, col) -> int:
+    """Checks the device CSR arrays a planner or the transposition reads (sizes, types, layout, device); returns nnz."""
+    import torch
+    for name, t in (("rowptr", rowptr), ("col", col)):
+        if not isinstance(t, torch.Tensor) or t.dtype != torch.int32 or not t.is_contiguous():
+            raise ValueError(f"{name}: expected a contiguous int32 torch tensor")
+    if rowptr.numel() != M + 1:
+        raise ValueError(f"rowptr: {rowptr.numel()} elements, expected M + 1 = {M + 1}")
+    if not rowptr.is_cuda or not col.is_cuda or col.device != rowptr.device:
+        raise ValueError("rowptr and col must be on one GPU")
+    return int(col.numel())
+
+
 def transpose_csr(M: int, Kc: int, rowptr, col):
     """(rowptr_t, col_t, perm_t) of the transposed pattern, torch int32 tensors on the device of the inputs."""
     import torch
     nnz = int(col.numel())
-    assert rowptr.is_cuda and rowptr.dtype == torch.int32 and rowptr.numel() == M + 1 and col.dtype == torch.int32
+    _csr_operands(M, rowptr, col)
     rowptr_t = torch.empty(Kc + 1, dtype=torch.int32, device=rowptr.device)
     col_t = torch.empty(nnz, dtype=torch.int32, device=rowptr.device)
     perm_t = torch.empty(nnz, dtype=torch.int32, device=rowptr.device)
@@ -328,10 +341,13 @@ class Plan:
         """Plan built on the GPU from torch tensors (int32 rowptr/col, float16 / bfloat16 / float32 values).
         ``resident``: the device copy is written during planning into a buffer of the bound size (no upload)."""
         import torch
-        assert rowptr.is_cuda and rowptr.dtype == torch.int32 and rowptr.is_contiguous() and rowptr.numel() == M + 1
-        nnz = int(col.numel())
-        assert col.is_cuda and col.dtype == torch.int32 and col.is_contiguous() and val.is_cuda and val.is_contiguous()
-        assert val.numel() == nnz
+        nnz = _csr_operands(M, rowptr, col)
+        if val.dtype not in (torch.float16, torch.bfloat16, torch.float32):
+            raise ValueError(f"val: dtype {val.dtype} is not float16, bfloat16 or float32")
+        if val.numel() != nnz or not val.is_contiguous():
+            raise ValueError(f"val: {val.numel()} elements (contiguous: {val.is_contiguous()}), expected {nnz} contiguous")
+        if not val.is_cuda or val.device != rowptr.device:
+            raise ValueError("val: must be on the same GPU as rowptr")
         self = cls.__new__(cls)
         self.M, self.Kc = int(M), int(Kc)
         self.val_dtype = {torch.float16: F16, torch.bfloat16: BF16, torch.float32: F32}[val.dtype]
@@ -384,50 +400,96 @@ class Plan:
         import torch
         return {F16: torch.float16, BF16: torch.bfloat16, F32: torch.float32}[self.val_dtype]
 
+    # The C ABI sees pointers only: the sizes behind them are checked here, before any launch, and a mismatch raises
+    # (an undersized operand would make a kernel read or write past its end).  Shape, type and layout first, the device last.
+    @staticmethod
+    def _operand(t, name, dtype, shape=None, numel=None, rows_contiguous=False):
+        import torch
+        if not isinstance(t, torch.Tensor):
+            raise ValueError(f"{name}: expected a torch tensor, got {type(t).__name__}")
+        if dtype is not None and t.dtype != dtype:
+            raise ValueError(f"{name}: dtype {t.dtype}, expected {dtype}")
+        if shape is not None:
+            if t.dim() != len(shape) or any(want is not None and int(have) != int(want) for have, want in zip(t.shape, shape)):
+                raise ValueError(f"{name}: shape {tuple(t.shape)}, expected {tuple('*' if w is None else w for w in shape)}")
+        if numel is not None and t.numel() != numel:
+            raise ValueError(f"{name}: {t.numel()} elements, expected {numel}")
+        if rows_contiguous:
+            if t.dim() != 2 or (t.shape[1] > 1 and t.stride(1) != 1) or (t.shape[0] > 1 and t.stride(0) < t.shape[1]):
+                raise ValueError(f"{name}: rows must be contiguous (strides {tuple(t.stride())})")
+        elif not t.is_contiguous():
+            raise ValueError(f"{name}: must be contiguous")
+        if not t.is_cuda:
+            raise ValueError(f"{name}: must be a GPU tensor")
+
+    def _value_code(self, t, name):
+        import torch
+        code = {torch.float16: F16, torch.bfloat16: BF16, torch.float32: F32}.get(t.dtype)
+        if code is None:
+            raise ValueError(f"{name}: dtype {t.dtype} is not float16, bfloat16 or float32")
+        return code
+
     def spmm(self, B, out=None):
         import torch
-        assert B.is_cuda and B.dtype == self._torch_dtype() and B.dim() == 2 and B.stride(1) == 1
-        N = B.shape[1]
+        self._operand(B, "B", self._torch_dtype(), shape=(self.Kc, None), rows_contiguous=True)
+        N = int(B.shape[1])
         if out is None:
             out = torch.empty((self.M, N), dtype=torch.float32, device=B.device)
-        assert out.is_cuda and out.dtype == torch.float32 and out.shape == (self.M, N) and out.stride(1) == 1
+        self._operand(out, "out", torch.float32, shape=(self.M, N), rows_contiguous=True)
+        if out.device != B.device:
+            raise ValueError("out: on another device than B")
         libra_spmm(self.handle, B.data_ptr(), N, B.stride(0), out.data_ptr(), out.stride(0),
                    torch.cuda.current_stream().cuda_stream)
         return out
 
     def sddmm(self, X, Y, out=None, pattern_only: bool = False):
         import torch
-        assert X.is_cuda and Y.is_cuda and X.dtype == Y.dtype == self._torch_dtype()
-        assert X.is_contiguous() and Y.is_contiguous() and X.shape[1] == Y.shape[1]
+        self._operand(X, "X", self._torch_dtype(), shape=(self.M, None))
+        self._operand(Y, "Y", self._torch_dtype(), shape=(self.Kc, int(X.shape[1])))
         if out is None:
             out = torch.empty(self.nnz, dtype=torch.float32, device=X.device)
-        assert out.is_cuda and out.dtype == torch.float32 and out.numel() == self.nnz and out.is_contiguous()
+        self._operand(out, "out", torch.float32, numel=self.nnz)
+        if Y.device != X.device or out.device != X.device:
+            raise ValueError("X, Y and out must be on one device")
         (libra_sddmm_pattern if pattern_only else libra_sddmm)(self.handle, X.data_ptr(), Y.data_ptr(), X.shape[1], out.data_ptr(),
                                                                torch.cuda.current_stream().cuda_stream)
         return out
 
     def edge_softmax(self, scores, scale: float, out=None):
         import torch
-        assert scores.is_cuda and scores.dtype == torch.float32 and scores.is_contiguous()
+        self._operand(scores, "scores", torch.float32, numel=self.nnz)
         if out is None:
             out = torch.empty(self.nnz, dtype=self._torch_dtype(), device=scores.device)
-        code = {torch.float16: F16, torch.bfloat16: BF16, torch.float32: F32}[out.dtype]
+        code = self._value_code(out, "out")
+        self._operand(out, "out", None, numel=self.nnz)
+        if out.device != scores.device:
+            raise ValueError("out: on another device than scores")
         libra_edge_softmax(self.handle, scores.data_ptr(), scale, out.data_ptr(), code,
                            torch.cuda.current_stream().cuda_stream)
         return out
 
     def edge_softmax_backward(self, alpha, dalpha, scale: float, out=None):
         import torch
-        assert alpha.is_cuda and alpha.is_contiguous() and alpha.numel() == self.nnz
-        assert dalpha.is_cuda and dalpha.dtype == torch.float32 and dalpha.is_contiguous() and dalpha.numel() == self.nnz
+        code = self._value_code(alpha, "alpha")
+        self._operand(alpha, "alpha", None, numel=self.nnz)
+        self._operand(dalpha, "dalpha", torch.float32, numel=self.nnz)
         if out is None:
             out = torch.empty(self.nnz, dtype=torch.float32, device=alpha.device)
-        code = {torch.float16: F16, torch.bfloat16: BF16, torch.float32: F32}[alpha.dtype]
+        self._operand(out, "out", torch.float32, numel=self.nnz)
+        if dalpha.device != alpha.device or out.device != alpha.device:
+            raise ValueError("alpha, dalpha and out must be on one device")
         libra_edge_softmax_backward(self.handle, alpha.data_ptr(), code, dalpha.data_ptr(), scale, out.data_ptr(),
                                     torch.cuda.current_stream().cuda_stream)
         return out
 
-    def set_values(self, vals, ops: int = OP_SPMM | OP_SDDMM):
+    def set_values(self, vals, ops: int = OP_SPMM | OP_SDDMM, one_call: bool = False):
+        """New values of A in CSR order.  ``one_call``: through libra_plan_set_values (both operators) instead of
+        libra_plan_set_values_for."""
         import torch
-        assert vals.is_cuda and vals.dtype == self._torch_dtype() and vals.is_contiguous() and vals.numel() == self.nnz
-        libra_plan_set_values_for(self.handle, vals.data_ptr(), self.val_dtype, ops, torch.cuda.current_stream().cuda_stream)
+        self._operand(vals, "vals", self._torch_dtype(), numel=self.nnz)
+        if one_call:
+            if ops != OP_SPMM | OP_SDDMM:
+                raise ValueError("one_call refreshes both operators")
+            libra_plan_set_values(self.handle, vals.data_ptr(), self.val_dtype, torch.cuda.current_stream().cuda_stream)
+        else:
+            libra_plan_set_values_for(self.handle, vals.data_ptr(), self.val_dtype, ops, torch.cuda.current_stream().cuda_stream)

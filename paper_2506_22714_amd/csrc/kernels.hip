@@ -861,7 +861,7 @@ __device__ inline void sddmm_segment_task(const SddmmArgs &a, const DevTask &t) 
 }
 
 // One launch for both kinds of SDDMM task (one wave each): the window tasks, heaviest first, then the
-// residual segments.  fp32 plans have no window tasks.
+// residual segments.
 template <class T, int K>
 __global__ __launch_bounds__(WAVE) void sddmm_task_kernel(SddmmArgs a) {
     const DevTask t = a.tasks[task_slot(blockIdx.x, a.tasks_per_die)];
@@ -1421,7 +1421,8 @@ extern "C" int libra_spmm(const libra_plan_t *P, const void *B, int32_t N, int64
     const int unit = P->vdt != LIBRA_F32 ? 32 : 16;
     if (N < unit || N > 512) return LIBRA_ERR_SHAPE;
     if (N % unit) return LIBRA_ERR_UNSUPPORTED;
-    if (ldb < N || ldc < N || ldb > (1ll << 30)) return LIBRA_ERR_SHAPE;
+    // a kernel forms a row's byte offset as a 32 x 32 -> 64 bit product: the row stride in bytes has to fit in 32 bits
+    if (ldb < N || ldc < N || ldb * (int64_t)P->vsize >= (1ll << 32)) return LIBRA_ERR_SHAPE;
     if (ldb % (P->vdt != LIBRA_F32 ? 8 : 4) || ldc % 4) return LIBRA_ERR_UNSUPPORTED;
     if (((uintptr_t)B & 15) || ((uintptr_t)C & 15)) return LIBRA_ERR_BUFFER;
     hipStream_t s = (hipStream_t)stream;

@@ -485,11 +485,18 @@ double neighbour_share(int64_t M, const int32_t *rowptr, const ColumnFetch &cols
     } else {
         std::vector<std::exception_ptr> failed(nthr);
         std::vector<std::thread> pool;
-        for (int t = 0; t < nthr; ++t)
-            pool.emplace_back([&, t]() {
-                try { work(t); } catch (...) { failed[t] = std::current_exception(); }
-            });
+        std::exception_ptr start_failed;
+        pool.reserve(nthr);
+        // a thread that cannot be started must not leave the started ones joinable (their destructor would terminate the
+        // process): they are joined first, then the error travels on
+        try {
+            for (int t = 0; t < nthr; ++t)
+                pool.emplace_back([&, t]() {
+                    try { work(t); } catch (...) { failed[t] = std::current_exception(); }
+                });
+        } catch (...) { start_failed = std::current_exception(); }
         for (auto &th : pool) th.join();
+        if (start_failed) std::rethrow_exception(start_failed);
         for (auto &f : failed)
             if (f) std::rethrow_exception(f);
     }
@@ -714,13 +721,18 @@ extern "C" int libra_plan(int64_t M, int64_t Kc, const int32_t *rowptr, const in
         std::vector<Part> parts(nranges);
         std::vector<std::thread> pool;
         std::vector<int> failed(nthr, 0);
-        for (int t = 0; t < nthr; ++t)
-            pool.emplace_back([&, t] {
-                try {
-                    for (int64_t r = t; r < nranges; r += nthr) plan_range(c, cut[r], cut[r + 1], parts[r]);
-                } catch (...) { failed[t] = 1; }
-            });
+        bool start_failed = false;
+        pool.reserve(nthr);
+        try {               // as above: started threads are joined before a failure to start another one is reported
+            for (int t = 0; t < nthr; ++t)
+                pool.emplace_back([&, t] {
+                    try {
+                        for (int64_t r = t; r < nranges; r += nthr) plan_range(c, cut[r], cut[r + 1], parts[r]);
+                    } catch (...) { failed[t] = 1; }
+                });
+        } catch (...) { start_failed = true; }
         for (auto &th : pool) th.join();
+        if (start_failed) throw std::bad_alloc();
         for (int f : failed) if (f) throw std::bad_alloc();
 
         SubPlan &sa = P->spmm, &sd = P->sddmm;

@@ -89,6 +89,27 @@ def test_device_planner_equals_host_planner(case):
         pd.close()
 
 
+@pytest.mark.parametrize("case", range(len(CASES)))
+def test_device_planner_equals_reference_planner(case):
+    """The device-built plan against the reference planner written from the paper (not against the host planner, with
+    which it shares the code that orders the task tables): same blocks, bitmaps, residual arrays, tasks, cleared rows."""
+    from test_plan_host import check_subplan, ref_opts
+    from oracle import planner_ref as pr
+    kw = CASES[case]
+    fl = kw.get("flags", 0)
+    for name, A in matrices():
+        if A.nnz > 20000:
+            continue                    # the reference planner walks Python dictionaries
+        print("case", case, name, flush=True)
+        pd = device_plan(A, **kw)
+        o = ref_opts(kw)
+        if not fl & lb.FLAG_NO_SPMM:
+            check_subplan(A, pd.export(0), pr.plan_spmm(A.M, A.rowptr, A.col, o), spmm=True)
+        if not fl & lb.FLAG_NO_SDDMM:
+            check_subplan(A, pd.export(1), pr.plan_sddmm(A.M, A.rowptr, A.col, o), spmm=False)
+        pd.close()
+
+
 def test_device_planner_random_options():
     rng = np.random.default_rng(20250622)
     for it in range(40):

@@ -204,6 +204,43 @@ def test_attention_head_constant_features_give_neighbourhood_mean():
             np.testing.assert_allclose(C[i], w * B[A.col[lo:hi]].astype(np.float64).sum(axis=0), rtol=1e-12)
 
 
+def test_attention_head_against_dense_softmax_with_nonzero_features():
+    # scores are kept as fp32 (the kernel's output type) before the softmax, the scale multiplies the scores inside
+    # the exponential, alpha is rounded once to fp16: every step redone with dense numpy / scipy on a small graph
+    from scipy.special import softmax
+    M = Kc = 48
+    K = 8
+    A = wl.random_pattern(M, Kc, 0.25, seed=23)
+    rng = np.random.default_rng(5)
+    A.val = wl.uniform_values(rng, A.nnz)
+    X = wl.dense_normal(M, K, seed=3)
+    Y = wl.dense_normal(Kc, K, seed=4)
+    B = wl.dense_normal(Kc, 8, seed=6)
+    scale = 0.37
+    s32, a16, C, _S = oracle.attention_head(A.rowptr, A.col, A.val, X, Y, B, scale=scale)
+    assert s32.dtype == np.float32 and a16.dtype == np.float16
+    D = np.zeros((M, Kc))
+    for i in range(M):
+        D[i, A.col[A.rowptr[i]:A.rowptr[i + 1]]] = A.val[A.rowptr[i]:A.rowptr[i + 1]].astype(np.float64)
+    full = D * (X.astype(np.float64) @ Y.astype(np.float64).T)          # scores on the pattern, exact products in double
+    want_C = np.zeros((M, B.shape[1]))
+    changed_by_scale = 0
+    for i in range(M):
+        lo, hi = A.rowptr[i], A.rowptr[i + 1]
+        if hi == lo:
+            assert not C[i].any()
+            continue
+        cols = A.col[lo:hi]
+        sc = full[i, cols].astype(np.float32)                            # one rounding to fp32
+        np.testing.assert_array_equal(s32[lo:hi], sc)
+        alpha = softmax(scale * sc.astype(np.float64))
+        np.testing.assert_array_equal(a16[lo:hi], alpha.astype(np.float16))
+        changed_by_scale += int(np.any(softmax(sc.astype(np.float64)).astype(np.float16) != a16[lo:hi]))
+        want_C[i] = alpha.astype(np.float16).astype(np.float64) @ B[cols].astype(np.float64)
+    np.testing.assert_allclose(C, want_C, rtol=1e-13, atol=1e-15)
+    assert changed_by_scale > M // 2        # a dropped or misplaced scale would be seen
+
+
 # ------------------------------------------------------------- error measure
 def test_graded_error_is_relative_for_ordinary_outputs_and_scaled_for_cancelled():
     ref = np.array([1.0, 1e-9])

@@ -277,3 +277,37 @@ def test_segments_by_column_keeps_the_tasks_and_gives_each_die_one_column_range(
     for q in range(8):                              # and a die meets its segments in ascending column order
         c = first_col[q::8][seg[q::8]]
         assert (np.diff(c) < 0).sum() <= 0.1 * c.size
+
+
+def test_binding_rejects_operands_of_the_wrong_size_before_any_launch():
+    """The C ABI takes pointers; the wrapper is the only place that sees the sizes behind them.  Every mismatch raises
+    ValueError before a kernel could read or write past an operand's end (no GPU is needed to see that)."""
+    torch = pytest.importorskip("torch")
+    A = wl.random_pattern(40, 56, 0.2, seed=3)
+    p = lb.Plan.from_csr(A)
+    h = torch.float16
+    ok_B = torch.zeros((A.Kc, 32), dtype=h)
+
+    def rejected(call, what):
+        with pytest.raises(ValueError, match=what):
+            call()
+
+    # well-formed operands pass every size check and stop at the last one: they are not on a GPU
+    rejected(lambda: p.spmm(ok_B), "B: must be a GPU tensor")
+    rejected(lambda: p.spmm(torch.zeros((A.Kc - 1, 32), dtype=h)), "B: shape")
+    rejected(lambda: p.spmm(torch.zeros((A.Kc, 32), dtype=torch.float32)), "B: dtype")
+    rejected(lambda: p.spmm(torch.zeros((A.Kc * 32,), dtype=h)), "B: shape")
+    rejected(lambda: p.spmm(torch.zeros((32, A.Kc), dtype=h).t()), "B: rows must be contiguous")
+    rejected(lambda: p.spmm(ok_B, out=torch.zeros((A.M - 1, 32))), "B: must be a GPU")      # B is checked first
+    rejected(lambda: p.sddmm(torch.zeros((A.M + 1, 32), dtype=h), torch.zeros((A.Kc, 32), dtype=h)), "X: shape")
+    rejected(lambda: p.sddmm(torch.zeros((A.M, 32), dtype=h), torch.zeros((A.Kc - 1, 32), dtype=h)), "X: must be a GPU")
+    rejected(lambda: p.edge_softmax(torch.zeros(A.nnz - 1), 1.0), "scores: .* elements")
+    rejected(lambda: p.edge_softmax(torch.zeros(A.nnz, dtype=torch.float64), 1.0), "scores: dtype")
+    rejected(lambda: p.edge_softmax_backward(torch.zeros(A.nnz + 1, dtype=h), torch.zeros(A.nnz), 1.0), "alpha: .* elements")
+    rejected(lambda: p.edge_softmax_backward(torch.zeros(A.nnz, dtype=torch.int32), torch.zeros(A.nnz), 1.0), "alpha: dtype")
+    rejected(lambda: p.set_values(torch.zeros(A.nnz - 1, dtype=h)), "vals: .* elements")
+    rejected(lambda: p.set_values(torch.zeros(A.nnz, dtype=torch.float32)), "vals: dtype")
+    rejected(lambda: lb.Plan.from_device_csr(A.M, A.Kc, torch.zeros(A.M, dtype=torch.int32), torch.zeros(3, dtype=torch.int32),
+                                             torch.zeros(3, dtype=h)), "rowptr: .* elements")
+    rejected(lambda: lb.transpose_csr(A.M, A.Kc, torch.zeros(A.M + 1, dtype=torch.int64), torch.zeros(3, dtype=torch.int32)), "rowptr: expected")
+    p.close()

@@ -75,6 +75,21 @@ def test_spmm_rule_4x4_example():
     assert sp.blocks[0].cols == [0, 2, 1, 3] and int(sp.label.sum()) == A.nnz
 
 
+def test_filler_vectors_are_promoted_by_nnz_descending_then_column():
+    # W=4, KB=4, tau=3: only column 0 qualifies; the three free slots of its block go to the scalar-bound vectors in
+    # (NNZ descending, column ascending) order: columns 1 and 3 (two nonzeros each), then column 2 (one; column 4 is left)
+    A = window_from_counts([3, 2, 1, 2, 1], W=4)
+    o = pr.Opts(W=4, KB=4, tau_spmm=3, fill_padding=True, Ts=4, Cs=5, short_len=2)
+    sp = pr.plan_spmm(A.M, A.rowptr, A.col, o)
+    assert len(sp.blocks) == 1 and sp.blocks[0].cols == [0, 1, 3, 2]       # by column alone it would be [0, 1, 2, 3]
+    assert set(A.col[sp.label == 0]) == {4}
+    # the same through the product's host planner
+    from paper_2506_22714_amd import binding as lb
+    p = lb.Plan.from_csr(A, window_rows=4, block_cols=4, spmm_min_vec_nnz=3, ts=4, cs=5, short_len=2)
+    assert p.export(0)["blk_cols"].tolist() == [[0, 1, 3, 2]]
+    p.close()
+
+
 def test_sddmm_rule_4x4_example():
     # W=4, KB=4, tau=4 (eta_thr = 0.25): vectors sorted by NNZ desc, blocks with NNZ >= 4 are dense
     counts = [1, 3, 1, 2, 1, 1, 1, 1, 1]          # sorted: c1(3) c3(2) c0 c2 | c4 c5 c6 c7 | c8
