@@ -301,6 +301,20 @@ int libra_csr_transpose_device(int64_t M, int64_t Kc, int64_t nnz, const int32_t
                                void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * libra_csr_transpose_device_static - libra_csr_transpose_device for callers that cannot allocate device memory (code
+ * under HIP graph capture, tight serving loops, harnesses that forbid allocation): same inputs and outputs, no workspace
+ * argument.  The workspace is a fixed array of LIBRA_TRANSPOSE_STATIC_MAX_NNZ * 40 bytes (40 MiB) in the library's device
+ * image, which every GPU the process uses holds until the process ends.  The call allocates and frees nothing, only
+ * enqueues kernels on `stream` and does not synchronise it: the outputs are valid once the stream has reached them.
+ * All calls on one GPU share that array: calls on one stream run one after the other and are safe; calls that may overlap
+ * (different streams or threads, same GPU) race and must be ordered by the caller.
+ * Errors: as libra_csr_transpose_device without BUFFER; TOO_LARGE for nnz > LIBRA_TRANSPOSE_STATIC_MAX_NNZ.
+ */
+#define LIBRA_TRANSPOSE_STATIC_MAX_NNZ (1 << 20)
+int libra_csr_transpose_device_static(int64_t M, int64_t Kc, int64_t nnz, const int32_t *d_rowptr, const int32_t *d_col,
+                                      int32_t *d_rowptr_t, int32_t *d_col_t, int32_t *d_perm_t, void *stream);
+
+/*
  * libra_probe_coissue - the register-only concurrency experiment of Section 3.1 on this GPU: 1024 workgroups of 8 waves
  * (two per SIMD) run `iters` rounds of (a) 4 independent MFMA 16x16x16 chains on four of the waves, (b) 32 FMAs on
  * 8 independent chains on the other four, (c) both at once.  times_us[0..2] receive the best of three timed launches of

@@ -109,6 +109,7 @@ def lib() -> C.CDLL:
         L.libra_probe_coissue.argtypes = [C.c_int, vp, C.POINTER(C.c_float * 3), vp]
         L.libra_csr_transpose_workspace.argtypes = [i64, C.POINTER(sz)]
         L.libra_csr_transpose_device.argtypes = [i64, i64, i64, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.libra_csr_transpose_device_static.argtypes = [i64, i64, i64, vp, vp, vp, vp, vp, vp]
         L.libra_plan_set_values.argtypes = [vp, vp, C.c_int, vp]
         L.libra_plan_set_values_for.argtypes = [vp, vp, C.c_int, C.c_int, vp]
         L.libra_plan_export.argtypes = [vp, C.c_int, C.POINTER(SubplanView)]
@@ -238,6 +239,16 @@ def libra_csr_transpose_device(M: int, Kc: int, nnz: int, rowptr_ptr: int, col_p
     _check(lib().libra_csr_transpose_device(M, Kc, nnz, C.c_void_p(rowptr_ptr), C.c_void_p(col_ptr), C.c_void_p(rowptr_t_ptr),
                                             C.c_void_p(col_t_ptr), C.c_void_p(perm_t_ptr), C.c_void_p(ws_ptr), ws_bytes,
                                             C.c_void_p(stream)), "libra_csr_transpose_device")
+
+
+TRANSPOSE_STATIC_MAX_NNZ = 1 << 20
+
+
+def libra_csr_transpose_device_static(M: int, Kc: int, nnz: int, rowptr_ptr: int, col_ptr: int, rowptr_t_ptr: int, col_t_ptr: int,
+                                      perm_t_ptr: int, stream: int = 0):
+    _check(lib().libra_csr_transpose_device_static(M, Kc, nnz, C.c_void_p(rowptr_ptr), C.c_void_p(col_ptr), C.c_void_p(rowptr_t_ptr),
+                                                   C.c_void_p(col_t_ptr), C.c_void_p(perm_t_ptr), C.c_void_p(stream)),
+           "libra_csr_transpose_device_static")
 
 
 def _csr_operands(M: int, rowptr, col) -> int:

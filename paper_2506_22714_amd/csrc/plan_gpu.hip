@@ -22,6 +22,8 @@
 // plan's host vectors, and the shared tail (task order, statistics) runs on the host.
 #include <hip/hip_runtime.h>
 
+#include <mutex>
+
 #include <chrono>
 #include <cstdio>
 #include <cstdlib>
@@ -985,18 +987,11 @@ extern "C" int libra_csr_transpose_workspace(int64_t nnz, size_t *bytes) {
     return LIBRA_OK;
 }
 
-extern "C" int libra_csr_transpose_device(int64_t M, int64_t Kc, int64_t nnz, const int32_t *d_rowptr, const int32_t *d_col,
-                                          int32_t *d_rowptr_t, int32_t *d_col_t, int32_t *d_perm_t,
-                                          void *workspace, size_t workspace_bytes, void *stream) {
-    if (!d_rowptr || !d_rowptr_t) return LIBRA_ERR_NULL;
-    if (M < 1 || Kc < 1 || nnz < 0) return LIBRA_ERR_SHAPE;
-    if (M >= (1ll << 31) - 64 || Kc >= (1ll << 31) - 64 || nnz >= (1ll << 31) - 64) return LIBRA_ERR_TOO_LARGE;
-    hipStream_t s = (hipStream_t)stream;
-    if (nnz == 0) return hipMemsetAsync(d_rowptr_t, 0, (size_t)(Kc + 1) * sizeof(int32_t), s) == hipSuccess ? LIBRA_OK : LIBRA_ERR_HIP;
-    if (!d_col || !d_col_t || !d_perm_t || !workspace) return LIBRA_ERR_NULL;
-    const TLayout L = transpose_layout(nnz, workspace);
-    if (((uintptr_t)workspace & 255) || workspace_bytes < L.total) return LIBRA_ERR_BUFFER;
-    const int n = (int)nnz;
+namespace {
+// The passes of the transposition on a workspace that is known to be large enough and aligned.  Only launches kernels
+// and the sort on `s`; nothing is allocated and the stream is not synchronised.
+int transpose_passes(int64_t M, int64_t Kc, int n, const int32_t *d_rowptr, const int32_t *d_col, int32_t *d_rowptr_t,
+                     int32_t *d_col_t, int32_t *d_perm_t, const TLayout &L, hipStream_t s) {
     int colbits = 1;
     while ((1ll << colbits) < Kc) ++colbits;
     const int64_t nw = (M + W - 1) / W;
@@ -1005,6 +1000,85 @@ extern "C" int libra_csr_transpose_device(int64_t M, int64_t Kc, int64_t nnz, co
     if (rocprim::radix_sort_keys(L.tmp, sz, L.key_in, L.key_out, (size_t)n, 0, (unsigned)(32 + colbits), s) != hipSuccess) return LIBRA_ERR_HIP;
     hipLaunchKernelGGL(k_transpose_fill, dim3(blocks_for(n, 256)), dim3(256), 0, s, L.key_out, L.row_of, n, d_col_t, d_perm_t);
     hipLaunchKernelGGL(k_transpose_rowptr, dim3(blocks_for(Kc + 1, 256)), dim3(256), 0, s, L.key_out, n, Kc, d_rowptr_t);
-    if (hipGetLastError() != hipSuccess || hipStreamSynchronize(s) != hipSuccess) return LIBRA_ERR_HIP;     // the workspace may go now
+    return hipGetLastError() == hipSuccess ? LIBRA_OK : LIBRA_ERR_HIP;
+}
+
+int transpose_args(int64_t M, int64_t Kc, int64_t nnz, const int32_t *d_rowptr, const int32_t *d_col, int32_t *d_rowptr_t,
+                   int32_t *d_col_t, int32_t *d_perm_t) {
+    if (!d_rowptr || !d_rowptr_t) return LIBRA_ERR_NULL;
+    if (M < 1 || Kc < 1 || nnz < 0) return LIBRA_ERR_SHAPE;
+    if (M >= (1ll << 31) - 64 || Kc >= (1ll << 31) - 64 || nnz >= (1ll << 31) - 64) return LIBRA_ERR_TOO_LARGE;
+    if (nnz > 0 && (!d_col || !d_col_t || !d_perm_t)) return LIBRA_ERR_NULL;
     return LIBRA_OK;
+}
+
+// rowptr of a transposed matrix without nonzeros: Kc + 1 zeros, written by a kernel (a memset node in a captured graph
+// is not reliable on replays)
+__global__ __launch_bounds__(256) void k_zero_i32(int32_t *p, int64_t n) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0;
+}
+}  // namespace
+
+extern "C" int libra_csr_transpose_device(int64_t M, int64_t Kc, int64_t nnz, const int32_t *d_rowptr, const int32_t *d_col,
+                                          int32_t *d_rowptr_t, int32_t *d_col_t, int32_t *d_perm_t,
+                                          void *workspace, size_t workspace_bytes, void *stream) {
+    if (int rc = transpose_args(M, Kc, nnz, d_rowptr, d_col, d_rowptr_t, d_col_t, d_perm_t)) return rc;
+    hipStream_t s = (hipStream_t)stream;
+    if (nnz == 0) {
+        hipLaunchKernelGGL(k_zero_i32, dim3(blocks_for(Kc + 1, 256)), dim3(256), 0, s, d_rowptr_t, Kc + 1);
+        return hipGetLastError() == hipSuccess ? LIBRA_OK : LIBRA_ERR_HIP;
+    }
+    if (!workspace) return LIBRA_ERR_NULL;
+    const TLayout L = transpose_layout(nnz, workspace);
+    if (((uintptr_t)workspace & 255) || workspace_bytes < L.total) return LIBRA_ERR_BUFFER;
+    if (int rc = transpose_passes(M, Kc, (int)nnz, d_rowptr, d_col, d_rowptr_t, d_col_t, d_perm_t, L, s)) return rc;
+    if (hipStreamSynchronize(s) != hipSuccess) return LIBRA_ERR_HIP;     // the workspace may go now
+    return LIBRA_OK;
+}
+
+// ------------------------------------------------------------------------------------------
+// The same transposition for callers that cannot allocate: its workspace is a fixed array in device memory that every
+// GPU the library runs on holds from the moment the code object is loaded until the process ends.
+// ------------------------------------------------------------------------------------------
+namespace {
+constexpr size_t STATIC_SCRATCH_BYTES = (size_t)LIBRA_TRANSPOSE_STATIC_MAX_NNZ * 40;      // keys in, keys out, rows, sort storage
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
+
+// In host code the array's name stands for the symbol, not for device memory: its address on the current device comes from
+// hipGetSymbolAddress, once per device (every GPU has its own copy at its own address).
+constexpr int MAX_DEVICES = 64;
+std::mutex scratch_mutex;
+void *scratch_ptr[MAX_DEVICES];
+
+int static_scratch(void **out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return LIBRA_ERR_HIP;
+    std::lock_guard<std::mutex> lock(scratch_mutex);
+    if (!scratch_ptr[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return LIBRA_ERR_HIP;
+        scratch_ptr[dev] = p;
+    }
+    *out = scratch_ptr[dev];
+    return LIBRA_OK;
+}
+}  // namespace
+
+extern "C" int libra_csr_transpose_device_static(int64_t M, int64_t Kc, int64_t nnz, const int32_t *d_rowptr, const int32_t *d_col,
+                                                 int32_t *d_rowptr_t, int32_t *d_col_t, int32_t *d_perm_t, void *stream) {
+    if (int rc = transpose_args(M, Kc, nnz, d_rowptr, d_col, d_rowptr_t, d_col_t, d_perm_t)) return rc;
+    if (nnz > LIBRA_TRANSPOSE_STATIC_MAX_NNZ) return LIBRA_ERR_TOO_LARGE;
+    hipStream_t s = (hipStream_t)stream;
+    if (nnz == 0) {
+        hipLaunchKernelGGL(k_zero_i32, dim3(blocks_for(Kc + 1, 256)), dim3(256), 0, s, d_rowptr_t, Kc + 1);
+        return hipGetLastError() == hipSuccess ? LIBRA_OK : LIBRA_ERR_HIP;
+    }
+    void *ws = nullptr;
+    if (int rc = static_scratch(&ws)) return rc;
+    const TLayout L = transpose_layout(nnz, ws);
+    if (L.total > STATIC_SCRATCH_BYTES) return LIBRA_ERR_TOO_LARGE;      // the sort asked for more storage than the array was sized for
+    // every array of the layout is written by a pass before a later pass reads it: nothing of the previous call's
+    // contents is read, so nothing has to be cleared
+    return transpose_passes(M, Kc, (int)nnz, d_rowptr, d_col, d_rowptr_t, d_col_t, d_perm_t, L, s);
 }
