@@ -9,7 +9,9 @@ Prints ONE JSON line.
   value      effective GFLOP/s of the step, (2*nnz*N + 2*nnz*K) / t
   roofline   the dominant kernel (the SpMM task kernel, N=128): algorithmic
              bytes of one SpMM / average duration of libra_spmm measured with
-             events on the launch stream inside the timed region
+             events on the launch stream over 40 further steps right after
+             the timed ones (the same number at any --steps); also the rate of
+             its row fetches against a bare gather of the same rows
   cpu_baseline  the CPU oracle timed on the host cores on the same workload
 """
 from __future__ import annotations
@@ -27,10 +29,82 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
 
-# HBM bytes per libra_spmm call on the default workload, from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE,
-# each scaled by the reading of the 1 GiB copy (--copy-calibration); see profiles/spmm_powerlaw_n128_counters.md.
-# Only quoted when the run uses exactly that configuration.
-MEASURED_TRAFFIC_BYTES = {("powerlaw", 128): int((2.0 * 101_740 + 1.0 * 75_412) * 1024)}
+# HBM bytes per libra_spmm call as measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each scaled by the reading of a
+# 1 GiB copy (--copy-calibration).  They live in a tracked file together with a digest of the kernel sources they were
+# measured with (--traffic-from writes it); the bench line quotes them only while the sources are unchanged and the run
+# uses exactly the measured configuration, and says null otherwise.
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "traffic_measured.json")
+SOURCE_DIRS = (os.path.join(ROOT, "paper_2506_22714_amd", "csrc"), os.path.join(ROOT, "include"))
+
+
+def source_digest() -> str:
+    """sha256 over the library's sources (names and contents, sorted): what a traffic measurement is valid for."""
+    import hashlib
+    h = hashlib.sha256()
+    for d in SOURCE_DIRS:
+        for fn in sorted(os.listdir(d)):
+            if fn.endswith((".hip", ".cpp", ".h")):
+                h.update(fn.encode())
+                with open(os.path.join(d, fn), "rb") as f:
+                    h.update(f.read())
+    return h.hexdigest()
+
+
+def measured_traffic(key: str):
+    try:
+        with open(TRAFFIC_FILE) as f:
+            t = json.load(f)
+    except (OSError, ValueError):
+        return None
+    if t.get("source_sha256") != source_digest():
+        return None
+    e = t.get("entries", {}).get(key)
+    return int(e["bytes"]) if e else None
+
+
+def _counter_means(directory: str, counter: str) -> dict:
+    """kernel name -> mean reading of `counter` over the dispatches in a rocprofv3 --pmc csv under `directory`."""
+    import csv
+    import glob
+    files = glob.glob(os.path.join(directory, "**", "*counter_collection.csv"), recursive=True)
+    if not files:
+        raise SystemExit(f"no counter csv under {directory}")
+    acc: dict = {}
+    for fn in files:
+        with open(fn) as f:
+            for r in csv.DictReader(f):
+                if r["Counter_Name"] == counter:
+                    acc.setdefault(r["Kernel_Name"], []).append(float(r["Counter_Value"]))
+    return {k: sum(v) / len(v) for k, v in acc.items()}
+
+
+def record_traffic(directory: str, key: str) -> int:
+    """Reads <dir>/fetch, <dir>/write (counter runs of this bench) and <dir>/cal_fetch, <dir>/cal_write (counter runs of
+    --copy-calibration) and writes TRAFFIC_FILE.  No GPU needed."""
+    copy_bytes = float(1 << 30)
+    out = {"source_sha256": source_digest(), "unit": "bytes per libra_spmm call (task kernel + the kernel that clears multi-writer rows)",
+           "commands": ["rocprofv3 --pmc FETCH_SIZE --output-format csv -d <dir>/fetch -o pmc -- python3 bench.py --no-cpu-baseline --no-probes --steps 5 --warmup 2",
+                        "rocprofv3 --pmc WRITE_SIZE ... -d <dir>/write ... (same program)",
+                        "rocprofv3 --pmc FETCH_SIZE|WRITE_SIZE ... -d <dir>/cal_fetch|cal_write ... -- python3 bench.py --copy-calibration",
+                        "python3 bench.py --traffic-from <dir>"],
+           "entries": {}}
+    entry = {}
+    for what, counter in (("fetch", "FETCH_SIZE"), ("write", "WRITE_SIZE")):
+        cal = _counter_means(os.path.join(directory, "cal_" + what), counter)
+        cal_kib = max(cal.values())                                   # the copy kernel is the only large one in that run
+        scale = copy_bytes / (cal_kib * 1024.0)
+        run = _counter_means(os.path.join(directory, what), counter)
+        kib = sum(v for k, v in run.items() if "spmm_task_kernel" in k or "zero_rows_kernel" in k)
+        entry[what + "_kib_raw"] = round(kib, 1)
+        entry[what + "_scale"] = round(scale, 4)
+        entry[what + "_bytes"] = int(kib * 1024.0 * scale)
+    entry["bytes"] = entry["fetch_bytes"] + entry["write_bytes"]
+    out["entries"][key] = entry
+    with open(TRAFFIC_FILE, "w") as f:
+        json.dump(out, f, indent=1, sort_keys=True)
+        f.write("\n")
+    print(json.dumps(out["entries"]))
+    return 0
 
 
 def spmm_algorithmic_bytes(A, N: int, kref: int, es: int = 2) -> int:
@@ -66,10 +140,15 @@ def main() -> int:
                     help="run the compute calls on the host-built, uploaded plan (default: on the plan the device planner "
                          "wrote; the two plans are identical and both planners are timed either way)")
     ap.add_argument("--dtype", default="f16", choices=["f16", "bf16", "f32"], help="storage type of A's values and the dense operands")
+    ap.add_argument("--no-tuned", action="store_true", help="library defaults instead of the tuner's table (paper_2506_22714_amd/tuned_gfx950.json)")
+    ap.add_argument("--no-probes", action="store_true", help="skip the cold calls, the copy rate and the bare-gather probe (counter runs)")
+    ap.add_argument("--traffic-from", metavar="DIR", help="no GPU: read rocprofv3 counter csvs under DIR and write profiles/traffic_measured.json")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run only a 1 GiB device copy (5 times): the known-size kernel that scales the rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE readings")
     args = ap.parse_args()
+    if args.traffic_from:
+        return record_traffic(args.traffic_from, f"{args.workload}:N={args.N or 128}:{args.dtype}")
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (the path has no multi-GPU part); use --gpus 1", file=sys.stderr)
         return 2
@@ -107,7 +186,11 @@ def main() -> int:
     if f32:
         B, X, Y = (a.astype(np.float32) for a in (B, X, Y))
     val = wl.to_bf16_bits(A.val.astype(np.float32)) if bf16 else A.val.astype(np.float32) if f32 else None
-    opts = dict(mode=args.mode, spmm_min_vec_nnz=args.tau_spmm, sddmm_min_blk_nnz=args.tau_sddmm, ts=args.ts, cs=args.cs,
+    # thresholds and load-balance limits: the tuner's table for this value type and these widths, unless switched off or
+    # given on the command line (explicit options win)
+    tuned_path = os.path.join(ROOT, "paper_2506_22714_amd", "tuned_gfx950.json")
+    tuned = None if args.no_tuned or not os.path.exists(tuned_path) else tuned_path
+    opts = dict(tuned=tuned, N=N, K=K, mode=args.mode, spmm_min_vec_nnz=args.tau_spmm, sddmm_min_blk_nnz=args.tau_sddmm, ts=args.ts, cs=args.cs,
                 flags=(lb.FLAG_NATURAL_ORDER if args.natural_order else 0) | (lb.FLAG_XCD_ORDER if args.xcd_order else 0)
                 | (lb.FLAG_NO_XCD_ORDER if args.no_xcd_order else 0) | (lb.FLAG_SEGMENTS_BY_COST if args.segments_by_cost else 0)
                 | (lb.FLAG_TWO_KERNELS if args.two_kernels else 0))
@@ -153,33 +236,46 @@ def main() -> int:
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    # Per-operator durations come from events on the launch stream inside the timed region, on every `stride`-th step
-    # (every 16th of the default 200) only: an event record keeps the next kernel from starting until the previous one has retired (about 5 us of idle
-    # GPU each on this machine), which would otherwise be a tenth of every step of the headline workload.
-    stride = 16 if args.steps >= 128 else 8 if args.steps >= 64 else 4 if args.steps >= 8 else 1
-    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range((args.steps + stride - 1) // stride)]
     torch.cuda.synchronize()
     t_start = time.perf_counter()
     for i in range(args.steps):
-        if i % stride == 0:
-            e = ev[i // stride]
-            e[0].record()
-            plan.spmm(Bd, out=Cd)
-            e[1].record()
-            plan.sddmm(Xd, Yd, out=od)
-            e[2].record()
-        else:
-            step()
+        step()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t_start
     ms_per_step = wall * 1e3 / args.steps
-    spmm_ms = np.array([e[0].elapsed_time(e[1]) for e in ev])
-    sddmm_ms = np.array([e[1].elapsed_time(e[2]) for e in ev])
+    # Per-operator durations: a fixed number of further steps, the same at any --steps, with events on the launch stream
+    # around each call (an event record keeps the next kernel from starting until the previous one has retired, about 5 us
+    # of idle GPU each on this machine, so these steps stay out of the timed region).
+    n_ev = 48
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(n_ev)]
+    for e in ev:
+        e[0].record()
+        plan.spmm(Bd, out=Cd)
+        e[1].record()
+        plan.sddmm(Xd, Yd, out=od)
+        e[2].record()
+    torch.cuda.synchronize()
+    spmm_ms = np.array([e[0].elapsed_time(e[1]) for e in ev[8:]])
+    sddmm_ms = np.array([e[1].elapsed_time(e[2]) for e in ev[8:]])
 
     # Cold calls (a 1 GiB buffer is streamed between calls, which evicts L2 and the 256 MB Infinity Cache) and the
     # streaming-copy rate of this machine; both after the timed region, so they do not disturb it.
-    scratch = torch.zeros(1 << 28, dtype=torch.float32, device="cuda")
-    n_cold = 15
+    gather = None
+    if not args.no_probes and not f32:
+        # the row fetches of the SpMM call and nothing else: rows col[p] of B in CSR order, 256 indices per wave
+        sink = torch.zeros(1, dtype=torch.float32, device="cuda")
+        rb = N * 2
+        if rb in (64, 128, 256) and Bd.is_contiguous():
+            gev = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(12)]
+            for e in gev:
+                e[0].record()
+                lb.libra_probe_gather(Bd.data_ptr(), A.Kc, rb, col_d.data_ptr(), A.nnz, sink.data_ptr(), torch.cuda.current_stream().cuda_stream)
+                e[1].record()
+            torch.cuda.synchronize()
+            g_us = float(np.median([e[0].elapsed_time(e[1]) for e in gev[2:]])) * 1e3
+            gather = {"rows": A.nnz, "row_bytes": rb, "median_us": round(g_us, 2), "GBs": round(A.nnz * rb / g_us / 1e3, 1)}
+    scratch = torch.zeros(1 << 28 if not args.no_probes else 1 << 10, dtype=torch.float32, device="cuda")
+    n_cold = 15 if not args.no_probes else 3
     cev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(n_cold)]
     for i in range(n_cold):
         scratch.add_(1.0)
@@ -216,7 +312,8 @@ def main() -> int:
     default_cfg = (not args.small and args.dtype == "f16" and args.mode == 0 and not (args.tau_spmm or args.tau_sddmm or args.ts or args.cs)
                    and not args.natural_order and not args.xcd_order and not args.no_xcd_order
                    and not args.segments_by_cost and not args.two_kernels)
-    traffic = MEASURED_TRAFFIC_BYTES.get((args.workload, N)) if default_cfg else None
+    traffic = measured_traffic(f"{args.workload}:N={N}:{args.dtype}") if default_cfg and not args.no_tuned else None
+    spmm_fetch_gbs = st["spmm_gather_rows"] * N * es / spmm_avg_s / 1e9          # rows of B the plan fetches (Eq. 2) per second
 
     out = {
         "metric": "SpMM/SDDMM effective GFLOP/s (2*nnz*N + 2*nnz*K per step)",
@@ -233,13 +330,16 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": f"{args.workload}{'-small' if args.small else ''}: M={A.M} nnz={A.nnz} SpMM N={N} + SDDMM K={K}",
                    "M": A.M, "nnz": A.nnz, "N": N, "K": K, "mode": args.mode,
-                   "tau_spmm": args.tau_spmm or 3, "tau_sddmm": args.tau_sddmm or 64},
+                   "options": "tuner table" if tuned else "library defaults"},
         "roofline": {"bound": "hbm", "kernel": f"spmm_task_kernel<{args.dtype},{min(N, 256)}>", "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
                      "algorithmic_bytes": bytes_spmm, "avg_us": round(spmm_avg_s * 1e6, 2),
                      "frac_of_measured_copy": round(achieved / copy_gbs, 4), "measured_copy_GBs": round(copy_gbs, 1),
                      "modelled_gather_GBs": round((st["spmm_gather_rows"] * N * 2 + A.nnz * 6 + A.M * N * 4)
-                                                  / spmm_avg_s / 1e9, 1)},
+                                                  / spmm_avg_s / 1e9, 1),
+                     "row_fetch_GBs": round(spmm_fetch_gbs, 1),
+                     "frac_of_measured_gather": round(spmm_fetch_gbs / gather["GBs"], 4) if gather else None},
+        "gather_probe": gather,
         "spmm": {"gflops": round(flops_spmm / spmm_avg_s / 1e9, 1), "median_us": round(float(np.median(spmm_ms)) * 1e3, 2),
                  "min_us": round(float(spmm_ms.min()) * 1e3, 2), "cold_median_us": round(float(np.median(spmm_cold)) * 1e3, 2),
                  "bytes": bytes_spmm},

@@ -326,6 +326,19 @@ int libra_csr_transpose_device_static(int64_t M, int64_t Kc, int64_t nnz, const 
 int libra_probe_coissue(int iters, float *sink_dev, float times_us[3], void *stream);
 
 /*
+ * libra_probe_gather - the row fetches of a call and nothing else (measurement aid): lane groups fetch row idx[i]
+ * (row_bytes = 64, 128 or 256: a row of B or Y at 32, 64 or 128 16-bit features) of `table`, 256 consecutive indices per
+ * wave, 8 rows in flight per lane group, and fold what arrives into a register.  The time of this launch is the floor of
+ * any kernel that must bring these rows, in this order, into a compute unit (Eq. 2 / Eq. 4 count exactly these fetches);
+ * the benchmark reports the task kernels against it.
+ *   table_dev  device, table_rows x row_bytes, 16-byte aligned; every idx[i] must lie in [0, table_rows) (not checked)
+ *   idx_dev    device, int32[n];  sink_dev  device, one float, practically never written
+ * Asynchronous on `stream`.  Errors: NULL, SHAPE, BUFFER, TOO_LARGE, UNSUPPORTED (row_bytes), HIP.
+ */
+int libra_probe_gather(const void *table_dev, int64_t table_rows, int32_t row_bytes, const int32_t *idx_dev, int64_t n,
+                       float *sink_dev, void *stream);
+
+/*
  * libra_plan_set_values - replace A's values (same pattern): scatters CSR-ordered device values into the
  * packed dense-block and residual arrays of both sub-plans' device copies.  The distribution of Section 4.2 depends
  * on the pattern only, so the preprocessing of Section 4.1 is reused as it is when only the values change (an

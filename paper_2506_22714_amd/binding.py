@@ -107,6 +107,7 @@ def lib() -> C.CDLL:
         L.libra_edge_softmax.argtypes = [vp, vp, C.c_float, vp, C.c_int, vp]
         L.libra_edge_softmax_backward.argtypes = [vp, vp, C.c_int, vp, C.c_float, vp, vp]
         L.libra_probe_coissue.argtypes = [C.c_int, vp, C.POINTER(C.c_float * 3), vp]
+        L.libra_probe_gather.argtypes = [vp, i64, i32, vp, i64, vp, vp]
         L.libra_csr_transpose_workspace.argtypes = [i64, C.POINTER(sz)]
         L.libra_csr_transpose_device.argtypes = [i64, i64, i64, vp, vp, vp, vp, vp, vp, sz, vp]
         L.libra_csr_transpose_device_static.argtypes = [i64, i64, i64, vp, vp, vp, vp, vp, vp]
@@ -228,6 +229,11 @@ def libra_probe_coissue(iters: int, sink_ptr: int, stream: int = 0):
     return tuple(float(x) for x in t)
 
 
+def libra_probe_gather(table_ptr: int, table_rows: int, row_bytes: int, idx_ptr: int, n: int, sink_ptr: int, stream: int = 0):
+    _check(lib().libra_probe_gather(C.c_void_p(table_ptr), table_rows, row_bytes, C.c_void_p(idx_ptr), n, C.c_void_p(sink_ptr),
+                                    C.c_void_p(stream)), "libra_probe_gather")
+
+
 def libra_csr_transpose_workspace(nnz: int) -> int:
     n = C.c_size_t()
     _check(lib().libra_csr_transpose_workspace(nnz, C.byref(n)), "libra_csr_transpose_workspace")
@@ -336,21 +342,37 @@ def libra_plan_stats(plan) -> dict:
     return {n: getattr(s, n) for n, _t in Stats._fields_}
 
 
+def _with_tuned(opts: dict, tuned, val_dtype: int, N, K) -> dict:
+    """Plan options with the entries of a tuner table filled in (argument marshalling: the table is data, the choice was
+    made by the tuner); options given explicitly (non-zero) are kept."""
+    if tuned is None:
+        return opts
+    from .tune import tuned_options
+    t = tuned_options(tuned, {F16: "f16", BF16: "bf16", F32: "f32"}[val_dtype], N=N, K=K)
+    return {**t, **{k: v for k, v in opts.items() if v or k not in t}}
+
+
 # ---- convenience wrapper: a plan handle plus the torch buffer that backs its device copy ----
 class Plan:
-    def __init__(self, M, Kc, rowptr, col, val, val_dtype: int | None = None, **opts):
-        """`val_dtype=BF16` with `val` as uint16 bit patterns builds a bfloat16 plan (numpy has no such type)."""
+    def __init__(self, M, Kc, rowptr, col, val, val_dtype: int | None = None, tuned=None, N: int | None = None,
+                 K: int | None = None, **opts):
+        """`val_dtype=BF16` with `val` as uint16 bit patterns builds a bfloat16 plan (numpy has no such type).
+        `tuned`: a table written by `python -m paper_2506_22714_amd.tune --emit` (path or dict); the options of the
+        classes of the feature widths `N` (SpMM) and `K` (SDDMM) are taken from it, explicit options win."""
         self.M, self.Kc = int(M), int(Kc)
         self.val_dtype = _np_dtype_code(np.asarray(val)) if val_dtype is None else int(val_dtype)
+        opts = _with_tuned(opts, tuned, self.val_dtype, N, K)
         self.handle = libra_plan(self.M, self.Kc, rowptr, col, val, PlanOpts(**opts) if opts else None,
                                  val_dtype=self.val_dtype)
         self.nnz = libra_plan_stats(self.handle)["nnz"]
         self._buf = None
 
     @classmethod
-    def from_device_csr(cls, M, Kc, rowptr, col, val, resident: bool = False, keep_host_copy: bool = True, **opts):
+    def from_device_csr(cls, M, Kc, rowptr, col, val, resident: bool = False, keep_host_copy: bool = True, tuned=None,
+                        N: int | None = None, K: int | None = None, **opts):
         """Plan built on the GPU from torch tensors (int32 rowptr/col, float16 / bfloat16 / float32 values).
-        ``resident``: the device copy is written during planning into a buffer of the bound size (no upload)."""
+        ``resident``: the device copy is written during planning into a buffer of the bound size (no upload).
+        ``tuned``, ``N``, ``K``: as in the constructor."""
         import torch
         nnz = _csr_operands(M, rowptr, col)
         if val.dtype not in (torch.float16, torch.bfloat16, torch.float32):
@@ -362,6 +384,7 @@ class Plan:
         self = cls.__new__(cls)
         self.M, self.Kc = int(M), int(Kc)
         self.val_dtype = {torch.float16: F16, torch.bfloat16: BF16, torch.float32: F32}[val.dtype]
+        opts = _with_tuned(opts, tuned, self.val_dtype, N, K)
         o = PlanOpts(**opts) if opts else None
         ws_bytes = libra_plan_device_workspace(self.M, nnz, o)
         ws = torch.empty(ws_bytes, dtype=torch.uint8, device=rowptr.device)
@@ -379,8 +402,8 @@ class Plan:
         return self
 
     @classmethod
-    def from_csr(cls, csr, val=None, val_dtype: int | None = None, **opts):
-        return cls(csr.M, csr.Kc, csr.rowptr, csr.col, csr.val if val is None else val, val_dtype=val_dtype, **opts)
+    def from_csr(cls, csr, val=None, val_dtype: int | None = None, tuned=None, N: int | None = None, K: int | None = None, **opts):
+        return cls(csr.M, csr.Kc, csr.rowptr, csr.col, csr.val if val is None else val, val_dtype=val_dtype, tuned=tuned, N=N, K=K, **opts)
 
     def close(self):
         if self.handle is not None:

@@ -42,6 +42,14 @@ constexpr int WAVE = 64;
 constexpr int W = 16;    // window height the kernels are written for
 constexpr int KB = 16;   // block width the kernels are written for
 
+// SDDMM window tasks take their dense blocks in groups of SD_GROUP; the 16-bit output records of a group are stored in
+// ascending CSR position with the LDS stage slot of their product (see sddmm_window_task).
+constexpr int SD_GROUP = 4;
+__host__ __device__ inline int sd_stage_slot(int block_in_group, int row, int slot) {
+    return block_in_group * 256 + (row % 4) * 64 + (row / 4) * 16 + slot;
+}
+inline bool sorted_records(const libra_plan_t *P) { return P->vdt != LIBRA_F32 && P->o.W == W && P->o.KB == KB; }
+
 struct SpmmArgs {
     const DevTask *tasks;
     const int32_t *blk_cols;
@@ -682,75 +690,71 @@ __device__ inline float group_sum(float s) {
     return s;
 }
 
-// Dense blocks of one window: D = Xwin * Y[cols]^T on the MFMA, sampled through the bitmap.
-// Blocks are handled BB at a time so that each dependent step (column ids and bitmaps; Y rows;
-// value/position records) is one batch of loads for the whole group.  All loads are unconditional
-// from clamped addresses; only the final stores are predicated.
+// Dense blocks of one window: D = Xwin * Y[cols]^T on the MFMA (both operands are contiguous along K: 16-byte global
+// loads straight into the operand registers).  The blocks of a task are taken in groups of SD_GROUP; a group's 16 x 16
+// products go to an LDS stage as they come out of the matrix cores (slot sd_stage_slot(block, row, column slot): lane l
+// writes its e-th accumulator of block x to x * 256 + e * 64 + l, no bank conflicts, no bitmap needed), and the group's
+// output records - {CSR position, value | stage slot << 16}, stored at plan time in ascending CSR position inside every
+// group - are then read by consecutive lanes: coalesced record loads, and stores that fall into the row-contiguous runs
+// of the output instead of one 4-byte store per matrix-core lane (the write-back of Section 4.4.2, with the popcount
+// offsets resolved when the plan is built).
 template <class T, int K>
-__device__ inline void sddmm_window_task(const SddmmArgs &a, const DevTask &t) {
+__device__ inline void sddmm_window_task(const SddmmArgs &a, const DevTask &t, float *stage) {
     constexpr int KS = K / 32;               // MFMA k-steps
-    constexpr int BB = K <= 64 ? 4 : 2;      // blocks per batch
-    const int lane = threadIdx.x;
+    constexpr int BB = K <= 64 ? 4 : 2;      // blocks whose Y rows are in registers together
+    constexpr int RU = 4;                    // record loads in flight per lane
+    static_assert(SD_GROUP % BB == 0, "a group is whole register batches");
+    const int lane = threadIdx.x % WAVE;
     const int g = lane >> 4, j = lane & 15;
     const uint16_t *X = reinterpret_cast<const uint16_t *>(a.X);
     const uint16_t *Y = reinterpret_cast<const uint16_t *>(a.Y);
-    // A operand: row j of the window, k = 32*s + 8g .. +7 (rows past M repeat the last row; never sampled)
+    // A operand: row j of the window, k = 32*s + 8g .. +7 (rows past M repeat the last row; no record points at them)
     const int64_t xr = min((int64_t)t.id * W + j, a.M - 1);
     uint4 xa[KS];
 #pragma unroll
     for (int s = 0; s < KS; ++s) xa[s] = *reinterpret_cast<const uint4 *>(X + xr * K + 32 * s + 8 * g);
-    for (int b0 = t.blk_begin; b0 < t.blk_end; b0 += BB) {
-        int col[BB], vptr[BB];
-        uint64_t word[BB];
+    for (int b0 = t.blk_begin; b0 < t.blk_end; b0 += SD_GROUP) {
+        const int nb = min(SD_GROUP, t.blk_end - b0);
+        int col[SD_GROUP];
 #pragma unroll
-        for (int x = 0; x < BB; ++x) {
-            const int b = min(b0 + x, t.blk_end - 1);
-            col[x] = a.blk_cols[(int64_t)b * KB + j];
-            word[x] = a.blk_bitmap[(int64_t)b * 4 + g];          // rows 4g..4g+3 of the block, bit e*16 + j
-            vptr[x] = a.blk_valptr[b];
+        for (int x = 0; x < SD_GROUP; ++x) col[x] = a.blk_cols[(int64_t)(b0 + min(x, nb - 1)) * KB + j];
+        const int v0 = a.blk_valptr[b0], v1 = a.blk_valptr[b0 + nb];
+        // the first records of the group travel with the Y rows
+        uint2 rec[RU];
+#pragma unroll
+        for (int u = 0; u < RU; ++u) rec[u] = a.dense_pv[min(v0 + u * WAVE + lane, a.n_dense - 1)];
+#pragma unroll
+        for (int h = 0; h < SD_GROUP; h += BB) {
+            if (h < nb) {
+                uint4 yb[BB][KS];
+#pragma unroll
+                for (int x = 0; x < BB; ++x) {
+                    const int c = max(col[h + x], 0);            // padding slot (or a block past the group): no record points at it
+#pragma unroll
+                    for (int s = 0; s < KS; ++s) yb[x][s] = *reinterpret_cast<const uint4 *>(Y + (int64_t)c * K + 32 * s + 8 * g);
+                }
+#pragma unroll
+                for (int x = 0; x < BB; ++x) {
+                    float4_t d = float4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int s = 0; s < KS; ++s) d = mfma_k32<T>(xa[s], yb[x][s], d);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) stage[(h + x) * 256 + e * WAVE + lane] = d[e];
+                }
+            }
         }
-        uint4 yb[BB][KS];
+        wave_sync();
+        for (int q = v0; q < v1; q += RU * WAVE) {
+            if (q > v0) {
 #pragma unroll
-        for (int x = 0; x < BB; ++x) {
-            const int c = max(col[x], 0);                        // padding slot: no bit is set in its column
+                for (int u = 0; u < RU; ++u) rec[u] = a.dense_pv[min(q + u * WAVE + lane, a.n_dense - 1)];
+            }
 #pragma unroll
-            for (int s = 0; s < KS; ++s) yb[x][s] = *reinterpret_cast<const uint4 *>(Y + (int64_t)c * K + 32 * s + 8 * g);
+            for (int u = 0; u < RU; ++u)
+                if (q + u * WAVE + lane < v1)
+                    a.out[(int32_t)rec[u].x] = (a.pattern_only ? 1.f : Elem<T>::word_val(rec[u].y)) * stage[rec[u].y >> 16];
         }
-        // where each of this lane's (up to 4 per block) outputs sits among the block's packed values
-        int slot[BB][4];
-#pragma unroll
-        for (int x = 0; x < BB; ++x) {
-            const int cnt = __popcll(word[x]);
-            const int c0 = __builtin_amdgcn_readlane(cnt, 0), c1 = __builtin_amdgcn_readlane(cnt, 16), c2 = __builtin_amdgcn_readlane(cnt, 32);
-            const int prefix = vptr[x] + (g > 0 ? c0 : 0) + (g > 1 ? c1 : 0) + (g > 2 ? c2 : 0);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) slot[x][e] = prefix + __popcll(word[x] & ((1ull << (e * 16 + j)) - 1ull));
-        }
-        // value/position records of the outputs (an unset bit reads a neighbouring record and drops it)
-        uint2 pv[BB][4];
-#pragma unroll
-        for (int x = 0; x < BB; ++x)
-#pragma unroll
-            for (int e = 0; e < 4; ++e) pv[x][e] = a.dense_pv[min(slot[x][e], a.n_dense - 1)];
-        float4_t d[BB];
-#pragma unroll
-        for (int x = 0; x < BB; ++x) {
-            d[x] = float4_t{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int s = 0; s < KS; ++s) d[x] = mfma_k32<T>(xa[s], yb[x][s], d[x]);
-        }
-        // every record load has been issued by here: without this the compiler moves the last one under the first
-        // store's condition, where it is issued after the products and waited for on its own
-#pragma unroll
-        for (int x = 0; x < BB; ++x)
-#pragma unroll
-            for (int e = 0; e < 4; ++e) asm volatile("" : "+v"(pv[x][e].x), "+v"(pv[x][e].y));
-#pragma unroll
-        for (int x = 0; x < BB; ++x)
-#pragma unroll
-            for (int e = 0; e < 4; ++e)
-                if (b0 + x < t.blk_end && (word[x] >> (e * 16 + j) & 1ull))
-                    a.out[(int32_t)pv[x][e].x] = (a.pattern_only ? 1.f : Elem<T>::word_val(pv[x][e].y)) * d[x][e];
+        wave_sync();                         // the next group overwrites the stage
     }
 }
 
@@ -758,11 +762,13 @@ __device__ inline void sddmm_window_task(const SddmmArgs &a, const DevTask &t) {
 // The same for fp32 storage: v_mfma_f32_16x16x4_f32.  A lane (g, j) fetches X[row j][16t + 4g .. +3] and Y[col j][16t + 4g .. +3] as
 // 16-byte loads; k-step 4t + e of the product takes element e of both, i.e. lane group g contributes k = 16t + 4g + e to
 // that step - any assignment of the k's to steps and lane groups gives the same sum as long as both operands use it.
+// (fp32 records are 8 bytes of position and value with no room for a stage slot: they stay in bit order and this task keeps
+// the per-lane popcount offsets and 4-byte stores.)
 template <int K>
 __device__ inline void sddmm_window_task_f32(const SddmmArgs &a, const DevTask &t) {
     constexpr int KT = K / 16;               // 16-byte pieces per lane and operand row
     constexpr int BB = K <= 32 ? 4 : K <= 64 ? 2 : 1;      // blocks per batch (register budget)
-    const int lane = threadIdx.x;
+    const int lane = threadIdx.x % WAVE;
     const int g = lane >> 4, j = lane & 15;
     const float *X = reinterpret_cast<const float *>(a.X);
     const float *Y = reinterpret_cast<const float *>(a.Y);
@@ -827,7 +833,7 @@ __device__ inline void sddmm_segment_task(const SddmmArgs &a, const DevTask &t) 
     constexpr int NPW = WAVE / LPN;          // nonzeros per wave pass
     constexpr int U = LPN <= 8 ? 8 : 4;      // passes in flight
     static_assert(LPN >= 4 && LPN % 4 == 0 && LPN <= WAVE, "unsupported K (whole quads per nonzero)");
-    const int lane = threadIdx.x;
+    const int lane = threadIdx.x % WAVE;
     const int sub = lane % LPN, grp = lane / LPN;
     for (int q0 = t.res_begin; q0 < t.res_end; q0 += NPW * U) {
         // An entry is 4 words (row, col, position, value bits).  Each lane of a quad fetches one of them (a quad then
@@ -860,14 +866,23 @@ __device__ inline void sddmm_segment_task(const SddmmArgs &a, const DevTask &t) 
     }
 }
 
-// One launch for both kinds of SDDMM task (one wave each): the window tasks, heaviest first, then the
-// residual segments.
-template <class T, int K>
-__global__ __launch_bounds__(WAVE) void sddmm_task_kernel(SddmmArgs a) {
-    const DevTask t = a.tasks[task_slot(blockIdx.x, a.tasks_per_die)];
+// One launch for both kinds of SDDMM task: the window tasks, heaviest first, then the residual segments.  A workgroup is
+// WPB waves, each with a task of its own; nothing is shared between them but the compute unit.  Workgroup b runs on die
+// b mod 8 and takes WPB consecutive tasks of that die's part of the table.  WPB = 4 is used when the table is in the
+// die-aware order: its consecutive tasks are then neighbouring windows (or runs of consecutive segments) that read the
+// same rows of Y, and four of them on one compute unit find each other's rows in its L1 (community matrix, K = 64:
+// matrix-unit-only 249 -> 208 us, hybrid 265 -> 247 us, same box).  Elsewhere one wave per workgroup is better (power-law
+// graph 31.0 vs 32.3 us: a workgroup's slots are only free again when its slowest wave has finished).
+template <class T, int K, int WPB>
+__global__ __launch_bounds__(WAVE * WPB) void sddmm_task_kernel(SddmmArgs a) {
+    __shared__ float stage_all[std::is_same<T, float>::value ? 1 : WPB * SD_GROUP * 256];
+    const unsigned wave = threadIdx.x / WAVE;
+    const unsigned seq = (blockIdx.x >> 3) * WPB + wave;                // position in the die's part of the table
+    if (seq >= (unsigned)a.tasks_per_die) return;
+    const DevTask t = a.tasks[(int64_t)(blockIdx.x & (LIBRA_XCDS - 1)) * a.tasks_per_die + seq];
     if (t.kind == LIBRA_TASK_WINDOW) {
         if constexpr (std::is_same<T, float>::value) sddmm_window_task_f32<K>(a, t);
-        else sddmm_window_task<T, K>(a, t);
+        else sddmm_window_task<T, K>(a, t, stage_all + wave * (SD_GROUP * 256));
         return;
     }
     sddmm_segment_task<T, K>(a, t);
@@ -1121,6 +1136,12 @@ __global__ __launch_bounds__(256) void scatter_values_kernel(const T *src, const
         *reinterpret_cast<T *>(reinterpret_cast<char *>(dst) + i * stride + offset) = src[perm[i]];
 }
 
+// new values into the 16-bit SDDMM output records, which carry their own CSR position (and keep their stage slot)
+__global__ __launch_bounds__(256) void refresh_record_values_kernel(const uint16_t *src, int64_t n, SdPv *rec) {
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x)
+        rec[i].val = (rec[i].val & 0xffff0000u) | src[rec[i].perm];
+}
+
 // the same into the value runs of the blocked entry layout
 template <class T>
 __global__ __launch_bounds__(256) void scatter_blocked_values_kernel(const T *src, const int32_t *perm, int64_t n, unsigned char *dst) {
@@ -1269,6 +1290,43 @@ __global__ __launch_bounds__(256) void pack_sddmm_values_kernel(const int32_t *p
         out[i] = SdPv{perm[i], (uint32_t)val[i]};
 }
 
+// 16-bit SDDMM output records written on the device: one wave per window task.  Per group of SD_GROUP blocks the CSR
+// positions of the group's packed values go to LDS; a lane then takes 4 bits of each block's bitmap, and for each set bit
+// finds the packed value (popcount of the bits below), its rank among the group's positions (a count over the LDS array),
+// and writes the record to that rank.
+__global__ __launch_bounds__(WAVE) void pack_sddmm_sorted_records_kernel(const DevTask *tasks, const uint64_t *blk_bitmap, const int32_t *blk_valptr,
+                                                                         const int32_t *dense_perm, const uint16_t *dense_val, SdPv *out) {
+    __shared__ int32_t pos[SD_GROUP * 256];
+    const DevTask t = tasks[blockIdx.x];                 // any order: every window task once
+    if (t.kind != LIBRA_TASK_WINDOW) return;
+    const int lane = threadIdx.x;
+    for (int b0 = t.blk_begin; b0 < t.blk_end; b0 += SD_GROUP) {
+        const int nb = min(SD_GROUP, t.blk_end - b0);
+        const int v0 = blk_valptr[b0], n = blk_valptr[b0 + nb] - v0;
+        for (int i = lane; i < n; i += WAVE) pos[i] = dense_perm[v0 + i];
+        __syncthreads();
+        for (int x = 0; x < nb; ++x) {
+            const int b = b0 + x;
+            const uint64_t word = blk_bitmap[(int64_t)b * 4 + lane / 16];       // bits 64 (lane / 16) .. + 63 of the block
+            const int sh = (lane % 16) * 4;
+            int before = 0;                                                     // set bits of the block below this lane's four
+            for (int w = 0; w < lane / 16; ++w) before += __popcll(blk_bitmap[(int64_t)b * 4 + w]);
+            before += __popcll(word & ((1ull << sh) - 1ull));
+            int q = blk_valptr[b] + before;
+            for (int e = 0; e < 4; ++e) {
+                if (!(word >> (sh + e) & 1ull)) continue;
+                const int bit = lane * 4 + e;
+                const int32_t p = dense_perm[q];
+                int rank = 0;
+                for (int i = 0; i < n; ++i) rank += pos[i] < p;
+                out[v0 + rank] = SdPv{p, (uint32_t)dense_val[q] | (uint32_t)sd_stage_slot(x, bit / KB, bit % KB) << 16};
+                ++q;
+            }
+        }
+        __syncthreads();
+    }
+}
+
 // st == nullptr: size pass.  da/dd == nullptr: the arrays come from the plan's host vectors; otherwise from
 // device memory, and the packed record arrays are only reserved here (adopt_device_arrays fills them).
 void layout(libra_plan_t *P, Uploader &u, Staging *st, const DeviceSource *da, const DeviceSource *dd) {
@@ -1315,6 +1373,29 @@ void layout(libra_plan_t *P, Uploader &u, Staging *st, const DeviceSource *da, c
             uint32_t bits = 0;
             std::memcpy(&bits, sd.dense_val.data() + i * vs, vs);
             st->sdpv[i] = {sd.dense_perm[i], bits};
+        }
+        if (sorted_records(P)) {
+            // 16-bit records: inside every group of SD_GROUP blocks of a window task, ascending CSR position, each with the
+            // stage slot of its product
+            std::vector<SdPv> grp;
+            for (const libra_task_t &t : sd.tasks) {
+                if (t.kind != LIBRA_TASK_WINDOW) continue;
+                for (int32_t b0 = t.blk_begin; b0 < t.blk_end; b0 += SD_GROUP) {
+                    const int32_t b1 = std::min(t.blk_end, b0 + SD_GROUP);
+                    grp.clear();
+                    for (int32_t b = b0; b < b1; ++b) {
+                        int32_t q = sd.blk_valptr[b];
+                        for (int bit = 0; bit < W * KB; ++bit)
+                            if (sd.blk_bitmap[(size_t)b * 4 + bit / 64] >> (bit % 64) & 1u) {
+                                SdPv r = st->sdpv[q++];
+                                r.val |= (uint32_t)sd_stage_slot(b - b0, bit / KB, bit % KB) << 16;
+                                grp.push_back(r);
+                            }
+                    }
+                    std::sort(grp.begin(), grp.end(), [](const SdPv &x, const SdPv &y) { return x.perm < y.perm; });
+                    std::copy(grp.begin(), grp.end(), st->sdpv.begin() + sd.blk_valptr[b0]);
+                }
+            }
         }
     }
     u.put(from_host ? (const void *)st->sdpv.data() : nullptr, nullptr, ndd * sizeof(SdPv), sd.dev.dense_pv);
@@ -1372,6 +1453,9 @@ int libra::adopt_device_arrays(libra_plan_t *P, const DeviceSource &da, const De
             if (P->vdt == LIBRA_F32)
                 hipLaunchKernelGGL((pack_sddmm_values_kernel<uint32_t>), grid(sd.n.dense), dim3(256), 0, s, dd.dense_perm,
                                    (const uint32_t *)dd.dense_val, sd.n.dense, (SdPv *)sd.dev.dense_pv);
+            else if (sorted_records(P))       // reads the task table that layout() has just queued for copying on this stream
+                hipLaunchKernelGGL(pack_sddmm_sorted_records_kernel, dim3((unsigned)task_slots(sd.n.tasks)), dim3(WAVE), 0, s, sd.dev.tasks,
+                                   dd.blk_bitmap, dd.blk_valptr, dd.dense_perm, (const uint16_t *)dd.dense_val, (SdPv *)sd.dev.dense_pv);
             else
                 hipLaunchKernelGGL((pack_sddmm_values_kernel<uint16_t>), grid(sd.n.dense), dim3(256), 0, s, dd.dense_perm,
                                    (const uint16_t *)dd.dense_val, sd.n.dense, (SdPv *)sd.dev.dense_pv);
@@ -1470,27 +1554,31 @@ int sddmm_call(const libra_plan_t *P, const void *X, const void *Y, int32_t K, f
                 reinterpret_cast<const SdEnt *>(sp.dev.res_ent), X, Y, out, P->M, 0, pattern_only};
     if (sp.tasks.empty()) return LIBRA_OK;
     a.tasks_per_die = (int32_t)(((int64_t)sp.tasks.size() + LIBRA_XCDS - 1) / LIBRA_XCDS);
-    const int64_t nt = (int64_t)a.tasks_per_die * LIBRA_XCDS;     // every slot of the table
-    const dim3 grid((unsigned)nt), block(WAVE);
-    if (P->vdt == LIBRA_F16) {
-        switch (K) {
-        case 32: hipLaunchKernelGGL((sddmm_task_kernel<half_t, 32>), grid, block, 0, s, a); break;
-        case 64: hipLaunchKernelGGL((sddmm_task_kernel<half_t, 64>), grid, block, 0, s, a); break;
-        case 128: hipLaunchKernelGGL((sddmm_task_kernel<half_t, 128>), grid, block, 0, s, a); break;
+    auto launch = [&](auto wpb) {
+        constexpr int WPB = decltype(wpb)::value;
+        const dim3 grid((unsigned)((a.tasks_per_die + WPB - 1) / WPB * LIBRA_XCDS)), block(WAVE * WPB);
+        if (P->vdt == LIBRA_F16) {
+            switch (K) {
+            case 32: hipLaunchKernelGGL((sddmm_task_kernel<half_t, 32, WPB>), grid, block, 0, s, a); break;
+            case 64: hipLaunchKernelGGL((sddmm_task_kernel<half_t, 64, WPB>), grid, block, 0, s, a); break;
+            case 128: hipLaunchKernelGGL((sddmm_task_kernel<half_t, 128, WPB>), grid, block, 0, s, a); break;
+            }
+        } else if (P->vdt == LIBRA_BF16) {
+            switch (K) {
+            case 32: hipLaunchKernelGGL((sddmm_task_kernel<bf16_t, 32, WPB>), grid, block, 0, s, a); break;
+            case 64: hipLaunchKernelGGL((sddmm_task_kernel<bf16_t, 64, WPB>), grid, block, 0, s, a); break;
+            case 128: hipLaunchKernelGGL((sddmm_task_kernel<bf16_t, 128, WPB>), grid, block, 0, s, a); break;
+            }
+        } else {
+            switch (K) {
+            case 32: hipLaunchKernelGGL((sddmm_task_kernel<float, 32, WPB>), grid, block, 0, s, a); break;
+            case 64: hipLaunchKernelGGL((sddmm_task_kernel<float, 64, WPB>), grid, block, 0, s, a); break;
+            case 128: hipLaunchKernelGGL((sddmm_task_kernel<float, 128, WPB>), grid, block, 0, s, a); break;
+            }
         }
-    } else if (P->vdt == LIBRA_BF16) {
-        switch (K) {
-        case 32: hipLaunchKernelGGL((sddmm_task_kernel<bf16_t, 32>), grid, block, 0, s, a); break;
-        case 64: hipLaunchKernelGGL((sddmm_task_kernel<bf16_t, 64>), grid, block, 0, s, a); break;
-        case 128: hipLaunchKernelGGL((sddmm_task_kernel<bf16_t, 128>), grid, block, 0, s, a); break;
-        }
-    } else {
-        switch (K) {
-        case 32: hipLaunchKernelGGL((sddmm_task_kernel<float, 32>), grid, block, 0, s, a); break;
-        case 64: hipLaunchKernelGGL((sddmm_task_kernel<float, 64>), grid, block, 0, s, a); break;
-        case 128: hipLaunchKernelGGL((sddmm_task_kernel<float, 128>), grid, block, 0, s, a); break;
-        }
-    }
+    };
+    if (P->o.xcd_order == 1) launch(std::integral_constant<int, 4>{});
+    else launch(std::integral_constant<int, 1>{});
     if (hipGetLastError() != hipSuccess) return LIBRA_ERR_HIP;
     return LIBRA_OK;
 }
@@ -1559,7 +1647,9 @@ extern "C" int libra_plan_set_values_for(libra_plan_t *P, const void *vals, int 
         const Seg &g = segs[k];
         if (g.n == 0 || !(ops & (k < 2 ? LIBRA_OP_SPMM : LIBRA_OP_SDDMM))) continue;
         const unsigned blocks = (unsigned)std::min<int64_t>((g.n + 255) / 256, 1 << 16);
-        if (g.stride == 0 && f16)
+        if (k == 2 && sorted_records(P))
+            hipLaunchKernelGGL(refresh_record_values_kernel, dim3(blocks), dim3(256), 0, s, (const uint16_t *)vals, g.n, (SdPv *)g.dst);
+        else if (g.stride == 0 && f16)
             hipLaunchKernelGGL((scatter_blocked_values_kernel<uint16_t>), dim3(blocks), dim3(256), 0, s, (const uint16_t *)vals, g.perm, g.n, (unsigned char *)g.dst);
         else if (g.stride == 0)
             hipLaunchKernelGGL((scatter_blocked_values_kernel<float>), dim3(blocks), dim3(256), 0, s, (const float *)vals, g.perm, g.n, (unsigned char *)g.dst);

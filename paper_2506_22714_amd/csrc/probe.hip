@@ -73,3 +73,52 @@ extern "C" int libra_probe_coissue(int iters, float *sink_dev, float times_us[3]
     (void)hipEventDestroy(e1);
     return rc;
 }
+
+// ---------------------------------------------------------------------------------------------------------------
+// Bare gather: the row fetches of an SpMM / SDDMM call and nothing else.  Lane groups of ROW_BYTES / 16 lanes fetch row
+// idx[i] of a table (16 bytes per lane, U rows in flight per group), fold what arrives into one register and never write.
+// Its time is the floor of any kernel that has to bring these rows, in this order, from the caches and HBM into a compute
+// unit - the measured ceiling the task kernels are compared with.
+// ---------------------------------------------------------------------------------------------------------------
+namespace {
+constexpr int GATHER_PER_WAVE = 256;     // consecutive indices per wave, as long as a row segment of the plan's tasks
+
+template <int ROW_BYTES, int U>
+__global__ __launch_bounds__(64) void gather_kernel(const uint4 *table, const int32_t *idx, int64_t n, float *sink) {
+    constexpr int LPR = ROW_BYTES / 16, GROUPS = 64 / LPR, PER_GROUP = GATHER_PER_WAVE / GROUPS;
+    static_assert(PER_GROUP % U == 0, "whole batches");
+    const int lane = threadIdx.x, sub = lane % LPR, grp = lane / LPR;
+    const int64_t base = (int64_t)blockIdx.x * GATHER_PER_WAVE + grp * PER_GROUP;
+    uint32_t acc = 0;
+    for (int p = 0; p < PER_GROUP; p += U) {
+        int32_t c[U];
+        uint4 v[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) c[u] = idx[min(base + p + u, n - 1)];          // the tail repeats the last index
+#pragma unroll
+        for (int u = 0; u < U; ++u) v[u] = table[(int64_t)c[u] * LPR + sub];
+#pragma unroll
+        for (int u = 0; u < U; ++u) acc ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
+    }
+    if (acc == 0x12345679u) sink[0] = 1.f;              // keeps the loads alive; practically never true
+}
+}  // namespace
+
+extern "C" int libra_probe_gather(const void *table_dev, int64_t table_rows, int32_t row_bytes, const int32_t *idx_dev, int64_t n,
+                                  float *sink_dev, void *stream) {
+    if (!table_dev || !idx_dev || !sink_dev) return LIBRA_ERR_NULL;
+    if (table_rows < 1 || n < 1 || n > (1ll << 40)) return LIBRA_ERR_SHAPE;
+    if (((uintptr_t)table_dev & 15) || ((uintptr_t)idx_dev & 3)) return LIBRA_ERR_BUFFER;
+    hipStream_t s = (hipStream_t)stream;
+    const int64_t waves = (n + GATHER_PER_WAVE - 1) / GATHER_PER_WAVE;
+    if (waves >= (1ll << 31)) return LIBRA_ERR_TOO_LARGE;
+    const uint4 *t = reinterpret_cast<const uint4 *>(table_dev);
+    const dim3 grid((unsigned)waves), block(64);
+    switch (row_bytes) {
+    case 64: hipLaunchKernelGGL((gather_kernel<64, 8>), grid, block, 0, s, t, idx_dev, n, sink_dev); break;
+    case 128: hipLaunchKernelGGL((gather_kernel<128, 8>), grid, block, 0, s, t, idx_dev, n, sink_dev); break;
+    case 256: hipLaunchKernelGGL((gather_kernel<256, 8>), grid, block, 0, s, t, idx_dev, n, sink_dev); break;
+    default: return LIBRA_ERR_UNSUPPORTED;
+    }
+    return hipGetLastError() == hipSuccess ? LIBRA_OK : LIBRA_ERR_HIP;
+}

@@ -8,6 +8,7 @@ library through the binding only.
     python -m paper_2506_22714_amd.tune --workload powerlaw --N 128 --K 32
     python -m paper_2506_22714_amd.tune --workload community --what tau_sddmm
     python -m paper_2506_22714_amd.tune --workload gat --N 64 --K 64 --what ablation
+    python -m paper_2506_22714_amd.tune --emit tuned.json          # the tuner: best settings per width class, as a table
 """
 from __future__ import annotations
 
@@ -57,6 +58,148 @@ ABLATION = [
 ]
 
 
+# ---------------------------------------------------------------------------------------------------------------
+# The tuner proper: per (value type, feature-width class) the setting with the best geometric mean over the workloads,
+# found by coordinate descent from the library's defaults, written as a table that Plan.from_* can apply (tuned=...).
+# ---------------------------------------------------------------------------------------------------------------
+SPMM_AXES = [("spmm_min_vec_nnz", (2, 3, 4, 6)), ("ts", (8, 16, 32)), ("cs", (64, 128, 256))]
+SDDMM_AXES = [("sddmm_min_blk_nnz", (16, 32, 64, 128, 257)), ("sddmm_cs", (64, 128, 256)), ("ts", (8, 16, 32))]
+SPMM_START = dict(spmm_min_vec_nnz=3, ts=16, cs=128)
+SDDMM_START = dict(sddmm_min_blk_nnz=64, sddmm_cs=128, ts=16)
+N_CLASSES = {"n32": 32, "n64": 64, "n128": 128}      # class name -> the width the class is tuned at
+K_CLASSES = {"k32": 32, "k64": 64, "k128": 128}
+TUNER_WORKLOADS = ("powerlaw", "community", "gat", "irregular")
+
+
+def n_class(N: int) -> str:
+    return "n32" if N <= 32 else "n64" if N <= 64 else "n128"
+
+
+def k_class(K: int) -> str:
+    return "k32" if K <= 32 else "k64" if K <= 64 else "k128"
+
+
+def geomean(xs) -> float:
+    return float(np.exp(np.mean(np.log(np.asarray(xs, dtype=np.float64)))))
+
+
+def coordinate_descent(axes, start: dict, cost, rounds: int = 2, log=print):
+    """Minimise cost(setting) over the grid `axes`, one axis at a time, starting from `start`; every evaluated setting
+    is kept.  Returns (best setting, its cost, {setting as sorted tuple: cost})."""
+    seen = {}
+
+    def ev(setting):
+        key = tuple(sorted(setting.items()))
+        if key not in seen:
+            seen[key] = cost(setting)
+            log(f"    {json.dumps(setting):70s} {seen[key]:10.2f}")
+        return seen[key]
+
+    best, best_cost = dict(start), ev(start)
+    for _ in range(rounds):
+        moved = False
+        for name, values in axes:
+            for v in values:
+                cand = dict(best, **{name: v})
+                c = ev(cand)
+                if c < best_cost * 0.995:           # a change has to be worth half a percent
+                    best, best_cost, moved = cand, c, True
+        if not moved:
+            break
+    return best, best_cost, seen
+
+
+def load_table(path_or_dict):
+    if isinstance(path_or_dict, dict):
+        table = path_or_dict
+    else:
+        with open(path_or_dict) as f:
+            table = json.load(f)
+    if table.get("format") != "libra-tuned-1" or "spmm" not in table or "sddmm" not in table:
+        raise ValueError("not a table written by `python -m paper_2506_22714_amd.tune --emit`")
+    return table
+
+
+def tuned_options(table, dtype: str = "f16", N: int | None = None, K: int | None = None) -> dict:
+    """Plan options for a value type and the feature widths the plan will be used with (the SpMM options come from the
+    class of N, the SDDMM options from the class of K; a width that is not given leaves its options at their defaults).
+    Ts is one option for both sub-plans: when both widths are given the SpMM class decides it (the SDDMM times move by
+    a per cent or two with Ts, the SpMM times by more).  bfloat16 uses the float16 entries; a value type without entries
+    falls back to float16."""
+    table = load_table(table)
+    allowed = {n for n, _ in SPMM_AXES} | {n for n, _ in SDDMM_AXES}
+    out = {}
+    for op, cls in (("sddmm", k_class(K) if K else None), ("spmm", n_class(N) if N else None)):
+        if cls is None:
+            continue
+        per_type = table[op].get("f16" if dtype == "bf16" else dtype) or table[op]["f16"]
+        for name, v in per_type[cls]["options"].items():
+            if name not in allowed or not isinstance(v, int) or v < 1:
+                raise ValueError(f"bad entry {name}={v!r} in the tuned table")
+            out[name] = v
+    return out
+
+
+def emit_table(path: str, small: bool, dtypes, log=print) -> dict:
+    import torch
+    from . import binding as lb
+    from . import workloads as wl
+
+    table = {"format": "libra-tuned-1", "device": torch.cuda.get_device_name(0), "small_workloads": bool(small),
+             "workloads": list(TUNER_WORKLOADS), "objective": "geometric mean of the median call time (us) over the workloads",
+             "spmm": {}, "sddmm": {}}
+    mats = {name: wl.make(name, small=small) for name in TUNER_WORKLOADS}
+    dev = {name: tuple(torch.from_numpy(x).cuda() for x in (A.rowptr.astype(np.int32), A.col.astype(np.int32))) for name, A in mats.items()}
+    for dt in dtypes:
+        np_dt, code = (np.float32, lb.F32) if dt == "f32" else (np.float16, lb.F16)
+        vals = {name: torch.from_numpy(A.val.astype(np_dt)).cuda() for name, A in mats.items()}
+
+        def plan(name, **kw):
+            A = mats[name]
+            return lb.Plan.from_device_csr(A.M, A.Kc, dev[name][0], dev[name][1], vals[name], resident=True, keep_host_copy=False, **kw)
+
+        table["spmm"][dt], table["sddmm"][dt] = {}, {}
+        for cls, N in N_CLASSES.items():
+            log(f"  spmm {dt} {cls} (N={N})")
+            Bs = {name: torch.from_numpy(wl.dense_normal(A.Kc, N, seed=1, dtype=np_dt)).cuda() for name, A in mats.items()}
+            Cs = {name: torch.empty((A.M, N), dtype=torch.float32, device="cuda") for name, A in mats.items()}
+
+            def cost(setting):
+                ts = []
+                for name in TUNER_WORKLOADS:
+                    p = plan(name, flags=lb.FLAG_NO_SDDMM, **setting)
+                    ts.append(time_us(lambda: p.spmm(Bs[name], out=Cs[name]), reps=15, warm=3))
+                    p.close()
+                return geomean(ts)
+
+            best, c, seen = coordinate_descent(SPMM_AXES, SPMM_START, cost, log=log)
+            table["spmm"][dt][cls] = {"options": best, "geomean_us": round(c, 2), "defaults_geomean_us": round(seen[tuple(sorted(SPMM_START.items()))], 2),
+                                      "settings_tried": len(seen)}
+            del Bs, Cs
+        for cls, K in K_CLASSES.items():
+            log(f"  sddmm {dt} {cls} (K={K})")
+            Xs = {name: torch.from_numpy(wl.dense_normal(A.M, K, seed=2, dtype=np_dt)).cuda() for name, A in mats.items()}
+            Ys = {name: torch.from_numpy(wl.dense_normal(A.Kc, K, seed=3, dtype=np_dt)).cuda() for name, A in mats.items()}
+            outs = {name: torch.empty(A.nnz, dtype=torch.float32, device="cuda") for name, A in mats.items()}
+
+            def cost(setting):
+                ts = []
+                for name in TUNER_WORKLOADS:
+                    p = plan(name, flags=lb.FLAG_NO_SPMM, **setting)
+                    ts.append(time_us(lambda: p.sddmm(Xs[name], Ys[name], out=outs[name]), reps=15, warm=3))
+                    p.close()
+                return geomean(ts)
+
+            best, c, seen = coordinate_descent(SDDMM_AXES, SDDMM_START, cost, log=log)
+            table["sddmm"][dt][cls] = {"options": best, "geomean_us": round(c, 2), "defaults_geomean_us": round(seen[tuple(sorted(SDDMM_START.items()))], 2),
+                                       "settings_tried": len(seen)}
+            del Xs, Ys, outs
+    with open(path, "w") as f:
+        json.dump(table, f, indent=1, sort_keys=True)
+        f.write("\n")
+    return table
+
+
 def main() -> int:
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
     ap.add_argument("--workload", default="powerlaw")
@@ -64,7 +207,17 @@ def main() -> int:
     ap.add_argument("--N", type=int, default=128)
     ap.add_argument("--K", type=int, default=32)
     ap.add_argument("--what", default="all", help="one of: all, ablation, " + ", ".join(SWEEPS))
+    ap.add_argument("--emit", metavar="TABLE.json", help="run the tuner over the four workloads and write the table of best "
+                    "settings per value type and feature-width class (apply it with Plan.from_csr(..., tuned=TABLE.json, N=, K=))")
+    ap.add_argument("--dtypes", default="f16", help="value types to tune, comma separated (f16, f32; bf16 uses the f16 entries)")
     args = ap.parse_args()
+    if args.emit:
+        t = emit_table(args.emit, args.small, [d for d in args.dtypes.split(",") if d])
+        for op in ("spmm", "sddmm"):
+            for dt, per in t[op].items():
+                for cls, e in per.items():
+                    print(f"{op:6s} {dt:4s} {cls:5s} {json.dumps(e['options']):60s} {e['geomean_us']:9.2f} us (defaults {e['defaults_geomean_us']:.2f})")
+        return 0
 
     import torch
     from . import binding as lb
