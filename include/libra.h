@@ -99,12 +99,14 @@ typedef struct {
     int32_t  block_cols;         /* k (SpMM) / n (SDDMM) of Section 2.2. default 16; planner accepts 1..64, kernels need 16 */
     int32_t  spmm_min_vec_nnz;   /* tau_spmm = ceil(eta_thr * m), Eq. 6: vector is dense iff NNZ_vector >= tau. default 3 */
     int32_t  sddmm_min_blk_nnz;  /* tau_sddmm = ceil(eta_thr * m * n), Eq. 6: block is dense iff NNZ_block >= tau. default 64 */
-    int32_t  ts;                 /* Ts of Section 4.3: a window's dense part is decomposed iff it has more than ts blocks. default 16 */
+    int32_t  ts;                 /* Ts of Section 4.3 (SpMM sub-plan): a window's dense part is decomposed iff it has more than ts blocks. default 16 */
     int32_t  cs;                 /* Cs of Section 4.3: a residual row is decomposed iff it has more than cs nonzeros. default 128 */
     int32_t  short_len;          /* Short_len of Section 4.3: a residual row with fewer nonzeros is "short". default 3 */
     int32_t  sddmm_cs;           /* SDDMM residual nonzeros per scalar segment. default 128 */
     uint32_t flags;              /* LIBRA_FLAG_* */
     int32_t  threads;            /* host threads for planning; 0 = hardware concurrency */
+    int32_t  sddmm_ts;           /* SDDMM: dense blocks of a window per task (Ts of Section 4.3 for the SDDMM sub-plan; its tasks
+                                    write disjoint outputs, so cutting a window costs no atomics). default 4 */
 } libra_plan_opts_t;
 
 /* ---- task table entry (Section 4.3: WindowOffset/RowOffset, CurWindow/CurRow, Atomic) ---- */

@@ -49,6 +49,7 @@ class Opts:
     short_len: int = 3
     fill_padding: bool = True
     sddmm_Cs: int = 128
+    sddmm_Ts: int = 4
 
 
 @dataclass
@@ -235,11 +236,12 @@ def plan_sddmm(M, rowptr, col, o: Opts) -> SubPlan:
     sp.res_perm = [int(p) for p in np.flatnonzero(sp.label == 0)]
     rows_of = np.repeat(np.arange(M), np.diff(np.asarray(rowptr[:M + 1], dtype=np.int64)))
     sp.res_row = [int(rows_of[p]) for p in sp.res_perm]
-    # load balancing: groups of Ts blocks per window; residual list in groups of sddmm_Cs nonzeros
+    # load balancing: groups of sddmm_Ts blocks per window (Ts of Section 4.3 for this sub-plan: its tasks write disjoint
+    # outputs, so the limit is its own); residual list in groups of sddmm_Cs nonzeros
     for w in range(nwin):
         b0, b1 = sp.win_blkptr[w], sp.win_blkptr[w + 1]
-        for g0 in range(b0, b1, o.Ts):
-            sp.tasks.append((TASK_WINDOW, w, g0, min(b1, g0 + o.Ts), 0, 0, 0, 0, 0))
+        for g0 in range(b0, b1, o.sddmm_Ts):
+            sp.tasks.append((TASK_WINDOW, w, g0, min(b1, g0 + o.sddmm_Ts), 0, 0, 0, 0, 0))
     for c0 in range(0, len(sp.res_perm), o.sddmm_Cs):
         sp.tasks.append((TASK_CHUNK, 0, 0, 0, c0, min(len(sp.res_perm), c0 + o.sddmm_Cs), 0, 0, 0))
     dense_nnz = int(sp.label.sum())

@@ -247,8 +247,8 @@ void plan_range(const Ctx &c, int64_t w0, int64_t w1, Part &out) {
             }
             const int32_t b1 = (int32_t)sd.n_blocks();
             sd.win_blkptr.push_back(b1);
-            for (int32_t g0 = b0; g0 < b1; g0 += o.Ts) {
-                int32_t g1 = std::min(b1, g0 + o.Ts);
+            for (int32_t g0 = b0; g0 < b1; g0 += o.sddmm_Ts) {
+                int32_t g1 = std::min(b1, g0 + o.sddmm_Ts);
                 uint32_t ncols = 0;
                 for (int32_t b = g0; b < g1; ++b)
                     for (int s = 0; s < KB; ++s) ncols += sd.blk_cols[(size_t)b * KB + s] >= 0;
@@ -523,9 +523,10 @@ int libra::resolve_options(const libra_plan_opts_t *in, int vdt, Resolved &o) {
     o.Cs = z.cs ? z.cs : 128;
     o.short_len = z.short_len ? z.short_len : 3;
     o.sddmm_Cs = z.sddmm_cs ? z.sddmm_cs : 128;
+    o.sddmm_Ts = z.sddmm_ts ? z.sddmm_ts : 4;
     o.threads = z.threads;
     if (o.W < 1 || o.W > 32 || o.KB < 1 || o.KB > 64 || o.tau_spmm < 1 || o.tau_sddmm < 1 || o.Ts < 1 ||
-        o.Cs < 1 || o.short_len < 1 || o.sddmm_Cs < 1 || o.threads < 0)
+        o.Cs < 1 || o.short_len < 1 || o.sddmm_Cs < 1 || o.sddmm_Ts < 1 || o.threads < 0)
         return LIBRA_ERR_OPTION;
     o.fill = !(z.flags & LIBRA_FLAG_NO_FILL_PADDING);
     o.build_spmm = !(z.flags & LIBRA_FLAG_NO_SPMM);

@@ -68,7 +68,7 @@ Sizes make_sizes(int64_t M, int64_t n, const Resolved &o) {
     z.nw = (M + W - 1) / W;
     z.nbmax = n / KB + z.nw + 1;
     z.tasks_a_max = z.nbmax / o.Ts + 2 * z.nw + 2 * (n / o.Cs) + 8;
-    z.tasks_d_max = z.nbmax / o.Ts + z.nw + 8;
+    z.tasks_d_max = z.nbmax / o.sddmm_Ts + z.nw + 8;
     z.segs_d_max = n / o.sddmm_Cs + 2;
     return z;
 }
@@ -317,7 +317,7 @@ __global__ __launch_bounds__(256) void k_share(const int32_t *win_vptr, const in
 }
 
 struct Rule {
-    int mode, fill, tau_d, Ts, Cs, short_len, build_a, build_d;
+    int mode, fill, tau_d, Ts, Cs, short_len, build_a, build_d, Ts_d;
 };
 
 // Per window: dense vectors and blocks of both sub-plans (Section 4.2).
@@ -554,11 +554,11 @@ __global__ __launch_bounds__(128) void k_window_tasks(const int32_t *rowptr, con
     if (R.build_d) {
         const int b0 = blkptr_d[t], b1 = blkptr_d[t + 1];
         if (!FILL) {
-            ntasks_d[t] = (b1 - b0 + R.Ts - 1) / R.Ts;
+            ntasks_d[t] = (b1 - b0 + R.Ts_d - 1) / R.Ts_d;
         } else {
             libra_task_t *out = tasks_d + tbase_d[t];
-            for (int g0 = b0; g0 < b1; g0 += R.Ts) {
-                const int g1 = min(b1, g0 + R.Ts);
+            for (int g0 = b0; g0 < b1; g0 += R.Ts_d) {
+                const int g1 = min(b1, g0 + R.Ts_d);
                 unsigned c = 0;
                 for (int b = g0; b < g1; ++b) c += (unsigned)blkncols_d[b];
                 put_task(out++, LIBRA_TASK_WINDOW, t, g0, g1, 0, 0, 0u, 0u, 0u, c + (unsigned)W);
@@ -749,7 +749,7 @@ extern "C" int libra_plan_device(int64_t M, int64_t Kc, int64_t nnz, const int32
         const uint8_t *val = reinterpret_cast<const uint8_t *>(d_val);
         int colbits = 1;
         while ((1ll << colbits) < Kc) ++colbits;
-        Rule R{o.mode, o.fill && o.mode == LIBRA_MODE_HYBRID ? 1 : 0, o.tau_sddmm, o.Ts, o.Cs, o.short_len, o.build_spmm ? 1 : 0, o.build_sddmm ? 1 : 0};
+        Rule R{o.mode, o.fill && o.mode == LIBRA_MODE_HYBRID ? 1 : 0, o.tau_sddmm, o.Ts, o.Cs, o.short_len, o.build_spmm ? 1 : 0, o.build_sddmm ? 1 : 0, o.sddmm_Ts};
         const int tau_a = o.mode == LIBRA_MODE_DENSE_ONLY ? 1 : o.mode == LIBRA_MODE_SCALAR_ONLY ? W + 1 : o.tau_spmm;
 
         // ---- 1. census: sort the nonzeros of every window by (column, row) ----

@@ -108,7 +108,7 @@ struct SubPlan {
 };
 
 struct Resolved {
-    int mode, W, KB, tau_spmm, tau_sddmm, Ts, Cs, short_len, sddmm_Cs, threads;
+    int mode, W, KB, tau_spmm, tau_sddmm, Ts, Cs, short_len, sddmm_Cs, sddmm_Ts, threads;
     bool fill, build_spmm, build_sddmm, heavy_first, segments_by_column, two_kernels;
     int xcd_order;       // 1 on, 0 off, -1 decide from the matrix
 };

@@ -37,6 +37,7 @@ SWEEPS = {
     "tau_spmm": [dict(spmm_min_vec_nnz=t) for t in (1, 2, 3, 4, 6, 8, 12, 16)],
     "tau_sddmm": [dict(sddmm_min_blk_nnz=t) for t in (16, 20, 24, 32, 48, 64, 96, 128)],
     "ts": [dict(ts=t) for t in (2, 4, 8, 16, 64)],
+    "sddmm_ts": [dict(sddmm_ts=t) for t in (1, 2, 4, 8, 16)],
     "cs": [dict(cs=c) for c in (32, 64, 96, 128, 192, 256, 512)],
     "sddmm_cs": [dict(sddmm_cs=c) for c in (64, 128, 256, 512, 1024)],
 }
@@ -63,9 +64,9 @@ ABLATION = [
 # found by coordinate descent from the library's defaults, written as a table that Plan.from_* can apply (tuned=...).
 # ---------------------------------------------------------------------------------------------------------------
 SPMM_AXES = [("spmm_min_vec_nnz", (2, 3, 4, 6)), ("ts", (8, 16, 32)), ("cs", (64, 128, 256))]
-SDDMM_AXES = [("sddmm_min_blk_nnz", (16, 32, 64, 128, 257)), ("sddmm_cs", (64, 128, 256)), ("ts", (8, 16, 32))]
+SDDMM_AXES = [("sddmm_min_blk_nnz", (16, 32, 64, 128, 257)), ("sddmm_cs", (64, 128, 256)), ("sddmm_ts", (2, 4, 8, 16))]
 SPMM_START = dict(spmm_min_vec_nnz=3, ts=16, cs=128)
-SDDMM_START = dict(sddmm_min_blk_nnz=64, sddmm_cs=128, ts=16)
+SDDMM_START = dict(sddmm_min_blk_nnz=64, sddmm_cs=128, sddmm_ts=4)
 N_CLASSES = {"n32": 32, "n64": 64, "n128": 128}      # class name -> the width the class is tuned at
 K_CLASSES = {"k32": 32, "k64": 64, "k128": 128}
 TUNER_WORKLOADS = ("powerlaw", "community", "gat", "irregular")
@@ -123,13 +124,12 @@ def load_table(path_or_dict):
 def tuned_options(table, dtype: str = "f16", N: int | None = None, K: int | None = None) -> dict:
     """Plan options for a value type and the feature widths the plan will be used with (the SpMM options come from the
     class of N, the SDDMM options from the class of K; a width that is not given leaves its options at their defaults).
-    Ts is one option for both sub-plans: when both widths are given the SpMM class decides it (the SDDMM times move by
-    a per cent or two with Ts, the SpMM times by more).  bfloat16 uses the float16 entries; a value type without entries
+    bfloat16 uses the float16 entries; a value type without entries
     falls back to float16."""
     table = load_table(table)
     allowed = {n for n, _ in SPMM_AXES} | {n for n, _ in SDDMM_AXES}
     out = {}
-    for op, cls in (("sddmm", k_class(K) if K else None), ("spmm", n_class(N) if N else None)):
+    for op, cls in (("spmm", n_class(N) if N else None), ("sddmm", k_class(K) if K else None)):
         if cls is None:
             continue
         per_type = table[op].get("f16" if dtype == "bf16" else dtype) or table[op]["f16"]

@@ -54,9 +54,9 @@ def assert_same_plan(ph, pd, flags=0):
 
 CASES = [
     dict(),
-    dict(spmm_min_vec_nnz=3, sddmm_min_blk_nnz=20, ts=2, cs=7, sddmm_cs=33),
+    dict(spmm_min_vec_nnz=3, sddmm_min_blk_nnz=20, ts=2, cs=7, sddmm_cs=33, sddmm_ts=3),
     dict(spmm_min_vec_nnz=2, sddmm_min_blk_nnz=17, ts=1, cs=2, short_len=4),
-    dict(mode=lb.MODE_DENSE_ONLY, ts=3),
+    dict(mode=lb.MODE_DENSE_ONLY, ts=3, sddmm_ts=1),
     dict(mode=lb.MODE_SCALAR_ONLY, cs=5),
     dict(flags=lb.FLAG_NO_FILL_PADDING, ts=1, cs=3),
     dict(flags=lb.FLAG_NATURAL_ORDER, ts=2, cs=6),
@@ -119,7 +119,7 @@ def test_device_planner_random_options():
             A = wl.with_long_rows(A, [M // 2], min(Kc, 200), seed=it)
         kw = dict(mode=int(rng.integers(0, 3)), spmm_min_vec_nnz=int(rng.integers(1, 8)), sddmm_min_blk_nnz=int(rng.integers(1, 80)),
                   ts=int(rng.integers(1, 6)), cs=int(rng.integers(1, 40)), short_len=int(rng.integers(1, 5)),
-                  sddmm_cs=int(rng.integers(1, 60)), flags=int(rng.choice([0, 1, 8, 9, 16, 32, 256, 288])))
+                  sddmm_cs=int(rng.integers(1, 60)), sddmm_ts=int(rng.integers(1, 9)), flags=int(rng.choice([0, 1, 8, 9, 16, 32, 256, 288])))
         print("random case", it, M, Kc, A.nnz, kw, flush=True)
         ph = lb.Plan.from_csr(A, **kw)
         pd = device_plan(A, **kw)

@@ -137,8 +137,8 @@ def check_subplan(A: wl.Csr, ex: dict, ref: pr.SubPlan, spmm: bool):
 
 CASES = [
     dict(),                                                     # defaults
-    dict(spmm_min_vec_nnz=3, sddmm_min_blk_nnz=20, ts=2, cs=7, sddmm_cs=33),
-    dict(mode=lb.MODE_DENSE_ONLY, ts=3),
+    dict(spmm_min_vec_nnz=3, sddmm_min_blk_nnz=20, ts=2, cs=7, sddmm_cs=33, sddmm_ts=3),
+    dict(mode=lb.MODE_DENSE_ONLY, ts=3, sddmm_ts=1),
     dict(mode=lb.MODE_SCALAR_ONLY, cs=5),
     dict(flags=lb.FLAG_NO_FILL_PADDING, ts=1, cs=3),
     dict(window_rows=4, block_cols=4, spmm_min_vec_nnz=2, sddmm_min_blk_nnz=4, ts=2, cs=5, short_len=2),
@@ -153,7 +153,8 @@ def ref_opts(kw: dict) -> pr.Opts:
     return pr.Opts(mode=kw.get("mode", 0), W=kw.get("window_rows", 16), KB=kw.get("block_cols", 16),
                    tau_spmm=kw.get("spmm_min_vec_nnz", 3), tau_sddmm=kw.get("sddmm_min_blk_nnz", 64),
                    Ts=kw.get("ts", 16), Cs=kw.get("cs", 128), short_len=kw.get("short_len", 3),
-                   fill_padding=not (fl & lb.FLAG_NO_FILL_PADDING), sddmm_Cs=kw.get("sddmm_cs", 128))
+                   fill_padding=not (fl & lb.FLAG_NO_FILL_PADDING), sddmm_Cs=kw.get("sddmm_cs", 128),
+                   sddmm_Ts=kw.get("sddmm_ts", 4))
 
 
 def matrices():

@@ -188,10 +188,17 @@ def test_spmm_plan_invariants(seed, W, KB, tau, fill):
 @pytest.mark.parametrize("seed,W,KB,tau", [(1, 16, 16, 24), (2, 8, 16, 24), (3, 4, 4, 4)])
 def test_sddmm_plan_invariants(seed, W, KB, tau):
     A = wl.random_pattern(90, 120, 0.1, seed=seed, empty_rows=0.1)
-    o = pr.Opts(W=W, KB=KB, tau_sddmm=tau, Ts=2, sddmm_Cs=50)
+    o = pr.Opts(W=W, KB=KB, tau_sddmm=tau, Ts=7, sddmm_Ts=2, sddmm_Cs=50)
     sp = pr.plan_sddmm(A.M, A.rowptr, A.col, o)
     allp = [p for b in sp.blocks for p in b.perm] + sp.res_perm
     assert sorted(allp) == list(range(A.nnz))
+    # the window tasks tile each window's blocks in groups of at most sddmm_Ts (the SpMM limit Ts plays no part here)
+    wt = [(i, a, b) for (k, i, a, b, *_r) in sp.tasks if k == pr.TASK_WINDOW]
+    assert all(0 < b - a <= 2 for _i, a, b in wt) and any(b - a == 2 for _i, a, b in wt)
+    for w in range(sp.stats["n_windows"]):
+        mine = sorted((a, b) for i, a, b in wt if i == w)
+        assert [a for a, _b in mine] == list(range(sp.win_blkptr[w], sp.win_blkptr[w + 1], 2))
+        assert not mine or mine[-1][1] == sp.win_blkptr[w + 1]
     for w in range(sp.stats["n_windows"]):
         blks = sp.blocks[sp.win_blkptr[w]:sp.win_blkptr[w + 1]]
         nn = [b.nnz for b in blks]

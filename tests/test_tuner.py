@@ -42,13 +42,13 @@ def test_width_classes():
 def test_table_is_parsed_checked_and_applied_to_a_plan(tmp_path):
     t = _table({"n32": dict(spmm_min_vec_nnz=2, ts=8, cs=64), "n64": dict(spmm_min_vec_nnz=4, ts=16, cs=128),
                 "n128": dict(spmm_min_vec_nnz=6, ts=32, cs=256)},
-               {"k32": dict(sddmm_min_blk_nnz=257, sddmm_cs=64, ts=8), "k64": dict(sddmm_min_blk_nnz=32, sddmm_cs=128, ts=8),
-                "k128": dict(sddmm_min_blk_nnz=16, sddmm_cs=256, ts=16)})
+               {"k32": dict(sddmm_min_blk_nnz=257, sddmm_cs=64, sddmm_ts=8), "k64": dict(sddmm_min_blk_nnz=32, sddmm_cs=128, sddmm_ts=2),
+                "k128": dict(sddmm_min_blk_nnz=16, sddmm_cs=256, sddmm_ts=4)})
     path = tmp_path / "tuned.json"
     path.write_text(json.dumps(t))
-    assert tune.tuned_options(str(path), "f16", N=128, K=32) == dict(spmm_min_vec_nnz=6, ts=32, cs=256, sddmm_min_blk_nnz=257, sddmm_cs=64)
+    assert tune.tuned_options(str(path), "f16", N=128, K=32) == dict(spmm_min_vec_nnz=6, ts=32, cs=256, sddmm_min_blk_nnz=257, sddmm_cs=64, sddmm_ts=8)
     assert tune.tuned_options(t, "bf16", N=48) == dict(spmm_min_vec_nnz=4, ts=16, cs=128)        # bfloat16 -> float16 entries; no K: no SDDMM options
-    assert tune.tuned_options(t, "f32", K=64) == dict(sddmm_min_blk_nnz=32, sddmm_cs=128, ts=8)   # a type without entries falls back; Ts from the SDDMM class when no N is given
+    assert tune.tuned_options(t, "f32", K=64) == dict(sddmm_min_blk_nnz=32, sddmm_cs=128, sddmm_ts=2)       # a type without entries falls back
     with pytest.raises(ValueError):
         tune.load_table({"format": "something else"})
     bad = json.loads(json.dumps(t))
@@ -58,9 +58,9 @@ def test_table_is_parsed_checked_and_applied_to_a_plan(tmp_path):
     # a plan built with the table equals the plan built with the same options spelled out; explicit options win
     A = wl.community(n_blocks=8, seed=4)
     a = lb.Plan.from_csr(A, tuned=str(path), N=128, K=64)
-    b = lb.Plan.from_csr(A, spmm_min_vec_nnz=6, ts=32, cs=256, sddmm_min_blk_nnz=32, sddmm_cs=128)
+    b = lb.Plan.from_csr(A, spmm_min_vec_nnz=6, ts=32, cs=256, sddmm_min_blk_nnz=32, sddmm_cs=128, sddmm_ts=2)
     c = lb.Plan.from_csr(A, tuned=t, N=128, K=64, spmm_min_vec_nnz=2)
-    d = lb.Plan.from_csr(A, spmm_min_vec_nnz=2, ts=32, cs=256, sddmm_min_blk_nnz=32, sddmm_cs=128)
+    d = lb.Plan.from_csr(A, spmm_min_vec_nnz=2, ts=32, cs=256, sddmm_min_blk_nnz=32, sddmm_cs=128, sddmm_ts=2)
     for x, y in ((a, b), (c, d)):
         for which in (0, 1):
             ex, ey = x.export(which), y.export(which)
