@@ -638,6 +638,39 @@ def test_full_powerlaw_config_as_benchmarked():
     p.close()
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_full_powerlaw_config_other_value_types_all_outputs(dtype):
+    """Config 2 at full size in the two other storage types (the fp32 mode to its own bar of 1e-5): every output of both
+    operators, on the plan the device planner writes."""
+    A = _full("powerlaw")
+    N, K = 128, 32
+    B32 = wl.dense_normal(A.Kc, N, seed=wl.BASE_SEED + 211, dtype=np.float32)
+    X32 = wl.dense_normal(A.M, K, seed=wl.BASE_SEED + 212, dtype=np.float32)
+    Y32 = wl.dense_normal(A.Kc, K, seed=wl.BASE_SEED + 213, dtype=np.float32)
+    v32 = wl.uniform_values(np.random.default_rng(214), A.nnz).astype(np.float32) * 1.37      # not exact in 8 bits
+    rp, col = dev(A.rowptr.astype(np.int32)), dev(A.col.astype(np.int32))
+    if dtype == "bf16":
+        val, B, X, Y = (wl.to_bf16_bits(a) for a in (v32, B32, X32, Y32))
+        p = lb.Plan.from_device_csr(A.M, A.Kc, rp, col, dev_bf16(val), resident=True, keep_host_copy=False)
+        Bd, Xd, Yd, tol, bf = dev_bf16(B), dev_bf16(X), dev_bf16(Y), TOL_F16, True
+    else:
+        val, B, X, Y = v32, B32, X32, Y32
+        p = lb.Plan.from_device_csr(A.M, A.Kc, rp, col, dev(val), resident=True, keep_host_copy=False)
+        Bd, Xd, Yd, tol, bf = dev(B), dev(X), dev(Y), TOL_F32, False
+    st = p.stats()
+    assert 0 < st["spmm_dense_nnz"] < A.nnz and st["spmm_zero_rows"] > 0
+    C = p.spmm(Bd)
+    torch.cuda.synchronize()
+    check_spmm_all_rows(A, B, C, tol, val=val, bf16=bf)
+    out = torch.full((A.nnz,), float("nan"), dtype=torch.float32, device="cuda")
+    p.sddmm(Xd, Yd, out=out)
+    ref, S = oracle.sddmm(A.rowptr, A.col, val, X, Y, bf16=bf)
+    got = out.cpu().numpy()
+    assert np.all(np.isfinite(got))
+    assert oracle.graded_error(got, ref, S, K) <= bound(tol, K)
+    p.close()
+
+
 @pytest.mark.parametrize("N", [64, 128, 256])
 def test_full_community_config_spmm_all_rows(N):
     """Config 3 at each of its three widths (N = 256 writes a 1 GiB C in one launch of two column pieces per task):
