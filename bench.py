@@ -266,14 +266,41 @@ def main() -> int:
         sink = torch.zeros(1, dtype=torch.float32, device="cuda")
         rb = N * 2
         if rb in (64, 128, 256) and Bd.is_contiguous():
-            gev = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(12)]
-            for e in gev:
-                e[0].record()
-                lb.libra_probe_gather(Bd.data_ptr(), A.Kc, rb, col_d.data_ptr(), A.nnz, sink.data_ptr(), torch.cuda.current_stream().cuda_stream)
-                e[1].record()
-            torch.cuda.synchronize()
-            g_us = float(np.median([e[0].elapsed_time(e[1]) for e in gev[2:]])) * 1e3
+            stream = torch.cuda.current_stream().cuda_stream
+
+            def probe_us(call):
+                gev = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(12)]
+                for e in gev:
+                    e[0].record()
+                    call()
+                    e[1].record()
+                torch.cuda.synchronize()
+                return float(np.median([e[0].elapsed_time(e[1]) for e in gev[2:]])) * 1e3
+
+            g_us = probe_us(lambda: lb.libra_probe_gather(Bd.data_ptr(), A.Kc, rb, col_d.data_ptr(), A.nnz, sink.data_ptr(), stream))
             gather = {"rows": A.nnz, "row_bytes": rb, "median_us": round(g_us, 2), "GBs": round(A.nnz * rb / g_us / 1e3, 1)}
+            # the same number of fetches from the first 4 MiB of the operand only (every fetch hits in an L2): what the
+            # L2 -> L1 path alone allows
+            hit_rows = max(1, min(A.Kc, (4 << 20) // rb))
+            col_hit = col_d % hit_rows
+            h_us = probe_us(lambda: lb.libra_probe_gather(Bd.data_ptr(), A.Kc, rb, col_hit.data_ptr(), A.nnz, sink.data_ptr(), stream))
+            gather["all_l2_hits_us"] = round(h_us, 2)
+            del col_hit
+            # ... and with the most referenced rows (96 KB of them) resident in LDS, persistent workgroups
+            if A.Kc * rb < (1 << 32) - 16:
+                n_hub = min(A.Kc, (96 << 10) // rb)
+                popularity = np.bincount(A.col, minlength=A.Kc)
+                hub_rows = np.argsort(-popularity, kind="stable")[:n_hub].astype(np.int32)
+                slot = np.full(A.Kc, -1, dtype=np.int64)
+                slot[hub_rows] = np.arange(n_hub)
+                s_of = slot[A.col]
+                enc = torch.from_numpy(np.where(s_of >= 0, -1 - s_of, A.col).astype(np.int32)).cuda()
+                hub_d = torch.from_numpy(hub_rows).cuda()
+                p_us = probe_us(lambda: lb.libra_probe_gather_hub(Bd.data_ptr(), A.Kc, rb, col_d.data_ptr(), A.nnz, hub_d.data_ptr(), 0, sink.data_ptr(), stream))
+                l_us = probe_us(lambda: lb.libra_probe_gather_hub(Bd.data_ptr(), A.Kc, rb, enc.data_ptr(), A.nnz, hub_d.data_ptr(), n_hub, sink.data_ptr(), stream))
+                gather["hub_rows_in_lds"] = {"rows_in_lds": int(n_hub), "share_of_fetches": round(float((s_of >= 0).mean()), 4),
+                                             "persistent_no_hub_us": round(p_us, 2), "persistent_hub_us": round(l_us, 2)}
+                del enc, hub_d
     scratch = torch.zeros(1 << 28 if not args.no_probes else 1 << 10, dtype=torch.float32, device="cuda")
     n_cold = 15 if not args.no_probes else 3
     cev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(n_cold)]

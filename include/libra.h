@@ -341,6 +341,23 @@ int libra_probe_gather(const void *table_dev, int64_t table_rows, int32_t row_by
                        float *sink_dev, void *stream);
 
 /*
+ * libra_probe_gather_hub - the same fetches with the most referenced rows held in LDS (measurement aid): what the data
+ * reuse of Section 4.2.1 (Eq. 2-3) would gain if the rows of the dense operand that many nonzeros share were kept in a
+ * compute unit's own memory instead of coming out of the L2 each time.  One persistent workgroup of 1024 threads per
+ * compute unit copies rows hub_rows[0 .. n_hub) of the table into LDS once; then, as in libra_probe_gather, every wave
+ * walks 256 consecutive indices at a time: idx[i] >= 0 is fetched from the table, idx[i] < 0 reads slot ~idx[i] of the
+ * LDS copy (a slot >= n_hub reads the last slot; a row index outside the table reads zeros - the table is addressed
+ * through range-checked buffer loads, so no index can leave it).
+ *   table_dev     device, table_rows x row_bytes (64, 128 or 256), 16-byte aligned, smaller than 4 GiB
+ *   idx_dev       device, int32[n];   hub_rows_dev  device, int32[n_hub] table rows (may be NULL when n_hub = 0)
+ *   n_hub         n_hub * row_bytes <= LIBRA_PROBE_HUB_MAX_BYTES (LDS of one compute unit, less what the waves need)
+ * Asynchronous on `stream`.  Errors: NULL, SHAPE, BUFFER, TOO_LARGE, UNSUPPORTED (row_bytes), HIP.
+ */
+#define LIBRA_PROBE_HUB_MAX_BYTES (128 * 1024)
+int libra_probe_gather_hub(const void *table_dev, int64_t table_rows, int32_t row_bytes, const int32_t *idx_dev, int64_t n,
+                           const int32_t *hub_rows_dev, int32_t n_hub, float *sink_dev, void *stream);
+
+/*
  * libra_plan_set_values - replace A's values (same pattern): scatters CSR-ordered device values into the
  * packed dense-block and residual arrays of both sub-plans' device copies.  The distribution of Section 4.2 depends
  * on the pattern only, so the preprocessing of Section 4.1 is reused as it is when only the values change (an

@@ -108,6 +108,7 @@ def lib() -> C.CDLL:
         L.libra_edge_softmax_backward.argtypes = [vp, vp, C.c_int, vp, C.c_float, vp, vp]
         L.libra_probe_coissue.argtypes = [C.c_int, vp, C.POINTER(C.c_float * 3), vp]
         L.libra_probe_gather.argtypes = [vp, i64, i32, vp, i64, vp, vp]
+        L.libra_probe_gather_hub.argtypes = [vp, i64, i32, vp, i64, vp, i32, vp, vp]
         L.libra_csr_transpose_workspace.argtypes = [i64, C.POINTER(sz)]
         L.libra_csr_transpose_device.argtypes = [i64, i64, i64, vp, vp, vp, vp, vp, vp, sz, vp]
         L.libra_csr_transpose_device_static.argtypes = [i64, i64, i64, vp, vp, vp, vp, vp, vp]
@@ -232,6 +233,12 @@ def libra_probe_coissue(iters: int, sink_ptr: int, stream: int = 0):
 def libra_probe_gather(table_ptr: int, table_rows: int, row_bytes: int, idx_ptr: int, n: int, sink_ptr: int, stream: int = 0):
     _check(lib().libra_probe_gather(C.c_void_p(table_ptr), table_rows, row_bytes, C.c_void_p(idx_ptr), n, C.c_void_p(sink_ptr),
                                     C.c_void_p(stream)), "libra_probe_gather")
+
+
+def libra_probe_gather_hub(table_ptr: int, table_rows: int, row_bytes: int, idx_ptr: int, n: int, hub_rows_ptr: int, n_hub: int,
+                           sink_ptr: int, stream: int = 0):
+    _check(lib().libra_probe_gather_hub(C.c_void_p(table_ptr), table_rows, row_bytes, C.c_void_p(idx_ptr), n,
+                                        C.c_void_p(hub_rows_ptr), n_hub, C.c_void_p(sink_ptr), C.c_void_p(stream)), "libra_probe_gather_hub")
 
 
 def libra_csr_transpose_workspace(nnz: int) -> int:

@@ -102,6 +102,66 @@ __global__ __launch_bounds__(64) void gather_kernel(const uint4 *table, const in
     }
     if (acc == 0x12345679u) sink[0] = 1.f;              // keeps the loads alive; practically never true
 }
+
+// The same fetches with the most popular rows resident in LDS (the data-reuse argument of Section 4.2.1 taken to the
+// compute unit's own memory): persistent workgroups of 1024 threads, one per compute unit, copy rows hub_rows[0 .. H) of
+// the table into LDS once; an index c >= 0 is fetched from the table as before, an index c < 0 reads slot ~c of the LDS
+// copy.  Table rows go through buffer loads whose range is the table, so an index outside it reads zeros.
+template <int ROW_BYTES, int U>
+__global__ __launch_bounds__(1024) void gather_hub_kernel(const void *table, uint32_t table_bytes, const int32_t *idx, int64_t n,
+                                                          const int32_t *hub_rows, int H, float *sink) {
+    constexpr int LPR = ROW_BYTES / 16, GROUPS = 64 / LPR, PER_GROUP = GATHER_PER_WAVE / GROUPS;
+    static_assert(PER_GROUP % U == 0, "whole batches");
+    extern __shared__ uint4 hub[];
+    const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(table), 0, (int)table_bytes, 0x00020000);
+    const int tid = threadIdx.x;
+    for (int i = tid; i < H * LPR; i += (int)blockDim.x) {
+        const uint32_t hr = (uint32_t)hub_rows[i / LPR];
+        const uint32_t off = hr < table_bytes / ROW_BYTES ? hr * (uint32_t)ROW_BYTES + (uint32_t)(i % LPR) * 16u : 0xfffffff0u;
+        hub[i] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)off, 0, 0));
+    }
+    __syncthreads();
+    const int lane = tid & 63, sub = lane % LPR, grp = lane / LPR, wave = tid >> 6, waves = (int)blockDim.x >> 6;
+    const int64_t nchunks = (n + GATHER_PER_WAVE - 1) / GATHER_PER_WAVE;
+    uint32_t acc = 0;
+    for (int64_t ch = (int64_t)blockIdx.x * waves + wave; ch < nchunks; ch += (int64_t)gridDim.x * waves) {
+        const int64_t base = ch * GATHER_PER_WAVE + grp * PER_GROUP;
+#pragma unroll 1
+        for (int p = 0; p < PER_GROUP; p += U) {
+            int32_t c[U];
+            uint4 v[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) c[u] = idx[min(base + p + u, n - 1)];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                // a hub entry gets an offset past the table: the load returns zeros and moves nothing
+                const uint32_t off = (uint32_t)c[u] < table_bytes / ROW_BYTES ? (uint32_t)c[u] * (uint32_t)ROW_BYTES + (uint32_t)sub * 16u : 0xfffffff0u;
+                v[u] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)off, 0, 0));
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                if (c[u] < 0 && H > 0) {
+                    const uint4 h = hub[min(~c[u], H - 1) * LPR + sub];
+                    v[u].x |= h.x; v[u].y |= h.y; v[u].z |= h.z; v[u].w |= h.w;
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) acc ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
+        }
+    }
+    if (acc == 0x12345679u) sink[0] = 1.f;
+}
+
+template <int ROW_BYTES>
+int launch_gather_hub(const void *table, uint32_t table_bytes, const int32_t *idx, int64_t n, const int32_t *hub_rows, int H,
+                      float *sink, int cus, hipStream_t s) {
+    const size_t lds = (size_t)H * ROW_BYTES;
+    auto kernel = gather_hub_kernel<ROW_BYTES, 8>;
+    if (lds > 48 * 1024 && hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+        return LIBRA_ERR_HIP;
+    hipLaunchKernelGGL(kernel, dim3((unsigned)cus), dim3(1024), lds, s, table, table_bytes, idx, n, hub_rows, H, sink);
+    return hipGetLastError() == hipSuccess ? LIBRA_OK : LIBRA_ERR_HIP;
+}
 }  // namespace
 
 extern "C" int libra_probe_gather(const void *table_dev, int64_t table_rows, int32_t row_bytes, const int32_t *idx_dev, int64_t n,
@@ -121,4 +181,23 @@ extern "C" int libra_probe_gather(const void *table_dev, int64_t table_rows, int
     default: return LIBRA_ERR_UNSUPPORTED;
     }
     return hipGetLastError() == hipSuccess ? LIBRA_OK : LIBRA_ERR_HIP;
+}
+
+extern "C" int libra_probe_gather_hub(const void *table_dev, int64_t table_rows, int32_t row_bytes, const int32_t *idx_dev, int64_t n,
+                                      const int32_t *hub_rows_dev, int32_t n_hub, float *sink_dev, void *stream) {
+    if (!table_dev || !idx_dev || !sink_dev || (n_hub > 0 && !hub_rows_dev)) return LIBRA_ERR_NULL;
+    if (table_rows < 1 || n < 1 || n > (1ll << 40) || n_hub < 0) return LIBRA_ERR_SHAPE;
+    if (row_bytes != 64 && row_bytes != 128 && row_bytes != 256) return LIBRA_ERR_UNSUPPORTED;
+    if (((uintptr_t)table_dev & 15) || ((uintptr_t)idx_dev & 3)) return LIBRA_ERR_BUFFER;
+    if (table_rows * row_bytes >= (1ll << 32) - 16 || (int64_t)n_hub * row_bytes > LIBRA_PROBE_HUB_MAX_BYTES) return LIBRA_ERR_TOO_LARGE;
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
+        return LIBRA_ERR_HIP;
+    hipStream_t s = (hipStream_t)stream;
+    const uint32_t bytes = (uint32_t)(table_rows * row_bytes);
+    switch (row_bytes) {
+    case 64: return launch_gather_hub<64>(table_dev, bytes, idx_dev, n, hub_rows_dev, n_hub, sink_dev, cus, s);
+    case 128: return launch_gather_hub<128>(table_dev, bytes, idx_dev, n, hub_rows_dev, n_hub, sink_dev, cus, s);
+    default: return launch_gather_hub<256>(table_dev, bytes, idx_dev, n, hub_rows_dev, n_hub, sink_dev, cus, s);
+    }
 }

@@ -222,3 +222,29 @@ def test_matrix_cores_and_vector_alus_run_side_by_side():
     print(f"coissue probe: MFMA only {a:.1f} us, FMA only {b:.1f} us, both {both:.1f} us", flush=True)
     assert a > 50 and b > 50
     assert both < 0.8 * (a + b)            # far from exclusive
+
+
+def test_gather_probes_run_on_every_row_width_with_and_without_resident_rows():
+    """The bare-gather measurement aids: plain fetches, fetches from a table small enough to hit in the L2s, and the variant
+    that keeps the most referenced rows in LDS (negative indices are LDS slots; indices outside the table or the slots
+    are clamped or read as zeros by construction, so a wrong index cannot fault)."""
+    A = wl.make("powerlaw", small=True)
+    stream = torch.cuda.current_stream().cuda_stream
+    sink = torch.zeros(1, dtype=torch.float32, device="cuda")
+    col = torch.from_numpy(A.col.astype(np.int32)).cuda()
+    popularity = np.bincount(A.col, minlength=A.Kc)
+    for rb in (64, 128, 256):
+        table = torch.randn(A.Kc, rb // 2, device="cuda").half()
+        n_hub = min(A.Kc, (96 << 10) // rb)
+        hub = np.argsort(-popularity, kind="stable")[:n_hub].astype(np.int32)
+        slot = np.full(A.Kc, -1, dtype=np.int64)
+        slot[hub] = np.arange(n_hub)
+        s_of = slot[A.col]
+        enc = np.where(s_of >= 0, -1 - s_of, A.col).astype(np.int32)
+        enc[:3] = [A.Kc + 5, -1 - n_hub - 7, np.iinfo(np.int32).max]      # outside the table / the slots: harmless
+        enc_d, hub_d = torch.from_numpy(enc).cuda(), torch.from_numpy(hub).cuda()
+        lb.libra_probe_gather(table.data_ptr(), A.Kc, rb, col.data_ptr(), A.nnz, sink.data_ptr(), stream)
+        lb.libra_probe_gather_hub(table.data_ptr(), A.Kc, rb, col.data_ptr(), A.nnz, 0, 0, sink.data_ptr(), stream)
+        lb.libra_probe_gather_hub(table.data_ptr(), A.Kc, rb, enc_d.data_ptr(), A.nnz, hub_d.data_ptr(), n_hub, sink.data_ptr(), stream)
+        torch.cuda.synchronize()
+        assert float(sink.item()) in (0.0, 1.0)

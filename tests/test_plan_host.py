@@ -67,6 +67,24 @@ def test_invalid_inputs_are_rejected_with_codes():
     assert _plan_rc(3, 3, np.zeros(4, dtype=np.int32), None, None) == 0
 
 
+def test_gather_probes_check_their_arguments_before_any_launch():
+    """The measurement aids refuse bad arguments on the host: nothing here reaches the GPU."""
+    import ctypes as C
+    L = lb.lib()
+    null, some = C.c_void_p(0), C.c_void_p(256)           # `some`: a non-null, 16-byte aligned value that is never dereferenced
+    assert L.libra_probe_gather(null, 10, 256, some, 5, some, null) == lb.ERR["NULL"]
+    assert L.libra_probe_gather(some, 10, 96, some, 5, some, null) == lb.ERR["UNSUPPORTED"]
+    assert L.libra_probe_gather(some, 0, 256, some, 5, some, null) == lb.ERR["SHAPE"]
+    assert L.libra_probe_gather_hub(null, 10, 256, some, 5, some, 2, some, null) == lb.ERR["NULL"]
+    assert L.libra_probe_gather_hub(some, 10, 256, some, 5, null, 2, some, null) == lb.ERR["NULL"]          # hub rows announced, none given
+    assert L.libra_probe_gather_hub(some, 10, 256, some, 0, some, 2, some, null) == lb.ERR["SHAPE"]
+    assert L.libra_probe_gather_hub(some, 10, 256, some, 5, some, -1, some, null) == lb.ERR["SHAPE"]
+    assert L.libra_probe_gather_hub(some, 10, 48, some, 5, some, 2, some, null) == lb.ERR["UNSUPPORTED"]
+    assert L.libra_probe_gather_hub(C.c_void_p(264), 10, 256, some, 5, some, 2, some, null) == lb.ERR["BUFFER"]
+    assert L.libra_probe_gather_hub(some, 10, 256, some, 5, some, 513, some, null) == lb.ERR["TOO_LARGE"]    # 513 rows of 256 bytes > 128 KB of LDS
+    assert L.libra_probe_gather_hub(some, 1 << 24, 256, some, 5, some, 2, some, null) == lb.ERR["TOO_LARGE"]  # table of 4 GiB
+
+
 def test_compute_calls_without_device_copy_fail_cleanly():
     A = wl.random_pattern(40, 40, 0.1, seed=1)
     p = lb.Plan.from_csr(A)
