@@ -330,3 +330,23 @@ def test_binding_rejects_operands_of_the_wrong_size_before_any_launch():
                                              torch.zeros(3, dtype=h)), "rowptr: .* elements")
     rejected(lambda: lb.transpose_csr(A.M, A.Kc, torch.zeros(A.M + 1, dtype=torch.int64), torch.zeros(3, dtype=torch.int32)), "rowptr: expected")
     p.close()
+
+
+def test_locality_model_counts_fetches_and_compulsory_misses():
+    """The L2 replay of a plan's task table: every fetch of Eq. 2 is counted once, an unbounded cache misses exactly the
+    distinct rows of each die, and a smaller cache never misses less."""
+    from paper_2506_22714_amd import locality
+    A = wl.make("powerlaw", small=True)
+    p = lb.Plan.from_csr(A, ts=32, cs=128, spmm_min_vec_nnz=3)
+    e = p.export(0)
+    cols = locality.task_columns(e)
+    st = p.stats()
+    assert sum(len(c) for c in cols) == st["spmm_gather_rows"]
+    per_die = sum(len(np.unique(np.concatenate([cols[i] for i in range(d, len(cols), 8)] + [np.zeros(0, np.int32)]))) for d in range(8))
+    big = locality.replay(cols, e["tasks"]["kind"], 1 << 40)
+    assert sum(big["fetches"].values()) == st["spmm_gather_rows"]
+    assert sum(big["misses"].values()) == per_die == big["distinct_rows_summed_over_dies"]
+    small = locality.replay(cols, e["tasks"]["kind"], 64)
+    tiny = locality.replay(cols, e["tasks"]["kind"], 1)
+    assert sum(big["misses"].values()) <= sum(small["misses"].values()) <= sum(tiny["misses"].values()) <= st["spmm_gather_rows"]
+    p.close()
