@@ -8,6 +8,7 @@ library through the binding only.
     python -m paper_2506_22714_amd.tune --workload powerlaw --N 128 --K 32
     python -m paper_2506_22714_amd.tune --workload community --what tau_sddmm
     python -m paper_2506_22714_amd.tune --workload gat --N 64 --K 64 --what ablation
+    python -m paper_2506_22714_amd.tune --workload powerlaw --what row_order       # rows permuted before planning
     python -m paper_2506_22714_amd.tune --emit tuned.json          # the tuner: best settings per width class, as a table
 """
 from __future__ import annotations
@@ -70,6 +71,28 @@ SDDMM_START = dict(sddmm_min_blk_nnz=64, sddmm_cs=128, sddmm_ts=4)
 N_CLASSES = {"n32": 32, "n64": 64, "n128": 128}      # class name -> the width the class is tuned at
 K_CLASSES = {"k32": 32, "k64": 64, "k128": 128}
 TUNER_WORKLOADS = ("powerlaw", "community", "gat", "irregular")
+
+
+def permute_rows(A, order):
+    """The matrix with row order[k] as its row k (columns untouched): what a plan-time row reordering would hand the planner.
+    C = A B then comes out in the permuted row order."""
+    from . import workloads as wl
+    deg = np.diff(A.rowptr).astype(np.int64)[order]
+    rp = np.zeros(A.M + 1, dtype=np.int64)
+    np.cumsum(deg, out=rp[1:])
+    idx = np.repeat(A.rowptr[:-1].astype(np.int64)[order] - rp[:-1], deg) + np.arange(rp[-1])
+    return wl.Csr(A.M, A.Kc, rp.astype(np.int32), A.col[idx], A.val[idx])
+
+
+def row_orders(A) -> dict:
+    """Row orders tried by `--what row_order`: as given; by descending length (long rows share windows, so their common
+    columns become vectors with several nonzeros); by descending length inside classes of 16 consecutive windows only
+    (the same idea without moving rows far)."""
+    deg = np.diff(A.rowptr)
+    ident = np.arange(A.M)
+    block = 256
+    local = np.concatenate([s + np.argsort(-deg[s:s + block], kind="stable") for s in range(0, A.M, block)])
+    return {"as given": ident, "descending length": np.argsort(-deg, kind="stable"), "descending length inside 256 rows": local}
 
 
 def n_class(N: int) -> str:
@@ -206,7 +229,7 @@ def main() -> int:
     ap.add_argument("--small", action="store_true")
     ap.add_argument("--N", type=int, default=128)
     ap.add_argument("--K", type=int, default=32)
-    ap.add_argument("--what", default="all", help="one of: all, ablation, " + ", ".join(SWEEPS))
+    ap.add_argument("--what", default="all", help="one of: all, ablation, row_order, " + ", ".join(SWEEPS))
     ap.add_argument("--emit", metavar="TABLE.json", help="run the tuner over the four workloads and write the table of best "
                     "settings per value type and feature-width class (apply it with Plan.from_csr(..., tuned=TABLE.json, N=, K=))")
     ap.add_argument("--dtypes", default="f16", help="value types to tune, comma separated (f16, f32; bf16 uses the f16 entries)")
@@ -240,6 +263,20 @@ def main() -> int:
             print(f"  {label:42s} {t_spmm:9.1f} {st['spmm_dense_nnz'] / max(A.nnz, 1):6.3f} {st['spmm_tasks']:8d} | "
                   f"{t_sddmm:9.1f} {st['sddmm_dense_nnz'] / max(A.nnz, 1):6.3f} {st['sddmm_tasks']:8d}", flush=True)
             p.close()
+        return 0
+    if args.what == "row_order":
+        # plan-time row reordering: rows with similar columns in one window give vectors with more nonzeros, i.e. fewer
+        # fetched rows (Eq. 2) - at the price of windows of long rows only
+        for label, order in row_orders(A).items():
+            P = permute_rows(A, order)
+            rp, cl, vl = (torch.from_numpy(x).cuda() for x in (P.rowptr, P.col.astype(np.int32), P.val))
+            for kw in (dict(ts=32), dict(ts=32, spmm_min_vec_nnz=2)):
+                p = lb.Plan.from_device_csr(P.M, P.Kc, rp, cl, vl, resident=True, keep_host_copy=False, **kw)
+                st = p.stats()
+                t_spmm, t_sddmm = time_us(lambda: p.spmm(B, out=C)), time_us(lambda: p.sddmm(X, Y, out=out))
+                print(f"  {label + ' ' + json.dumps(kw):62s} {t_spmm:9.1f} {st['spmm_dense_nnz'] / max(A.nnz, 1):6.3f} {st['spmm_tasks']:8d} | "
+                      f"{t_sddmm:9.1f} {st['sddmm_dense_nnz'] / max(A.nnz, 1):6.3f} {st['sddmm_tasks']:8d}  fetched rows {st['spmm_gather_rows']}", flush=True)
+                p.close()
         return 0
     names = list(SWEEPS) if args.what == "all" else [args.what]
     for name in names:
