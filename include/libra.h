@@ -107,6 +107,10 @@ typedef struct {
     int32_t  threads;            /* host threads for planning; 0 = hardware concurrency */
     int32_t  sddmm_ts;           /* SDDMM: dense blocks of a window per task (Ts of Section 4.3 for the SDDMM sub-plan; its tasks
                                     write disjoint outputs, so cutting a window costs no atomics). default 4 */
+    int32_t  sddmm_min_dense_pct;/* SDDMM, hybrid mode: the utilisation argument of Section 4.2.2 applied to the whole matrix.  If the
+                                    blocks that pass tau_sddmm hold less than this percentage of the nonzeros, the sub-plan sends
+                                    every nonzero to the scalar path (a few dense blocks cost more in outputs written twice, once
+                                    by each kind of task, than they save).  1..100; default 0 = rule off */
 } libra_plan_opts_t;
 
 /* ---- task table entry (Section 4.3: WindowOffset/RowOffset, CurWindow/CurRow, Atomic) ---- */

@@ -11,7 +11,11 @@ It follows, in the paper's order and notation:
   slots of a window's last block may be filled with vectors that would
   otherwise go to the scalar path.  SDDMM: vectors are sorted by descending
   NNZ_vector, condensed into m x n blocks, and a block goes to the matrix unit
-  iff NNZ_block >= tau_sddmm.
+  iff NNZ_block >= tau_sddmm.  A whole-matrix form of the same utilisation
+  argument sits on top (a reading of this build, an option): in the hybrid mode
+  the SDDMM sub-plan keeps its dense blocks only if together they hold at least
+  `sddmm_min_dense_pct` percent of the nonzeros; otherwise every nonzero takes
+  the scalar path.
 * Section 4.3 - the dense part of a window is decomposed into groups of Ts
   blocks only if it holds more than Ts; a residual row with fewer than
   Short_len nonzeros is short, otherwise long, and a long row is decomposed
@@ -50,6 +54,7 @@ class Opts:
     fill_padding: bool = True
     sddmm_Cs: int = 128
     sddmm_Ts: int = 4
+    sddmm_min_dense_pct: int = 0      # 0: the rule is off
 
 
 @dataclass
@@ -233,6 +238,10 @@ def plan_sddmm(M, rowptr, col, o: Opts) -> SubPlan:
             n_dense_vec += len(cols)
             n_pad += KB - len(cols)
         sp.win_blkptr.append(len(sp.blocks))
+    if o.mode == HYBRID and o.sddmm_min_dense_pct > 0 and 100 * int(sp.label.sum()) < o.sddmm_min_dense_pct * nnz:
+        # too small a share for the matrix units to pay: the whole sub-plan goes to the scalar path
+        from dataclasses import replace
+        return plan_sddmm(M, rowptr, col, replace(o, mode=SCALAR_ONLY))
     sp.res_perm = [int(p) for p in np.flatnonzero(sp.label == 0)]
     rows_of = np.repeat(np.arange(M), np.diff(np.asarray(rowptr[:M + 1], dtype=np.int64)))
     sp.res_row = [int(rows_of[p]) for p in sp.res_perm]

@@ -38,7 +38,7 @@ class PlanOpts(C.Structure):
     _fields_ = [("struct_size", C.c_uint32), ("mode", C.c_int32), ("window_rows", C.c_int32),
                 ("block_cols", C.c_int32), ("spmm_min_vec_nnz", C.c_int32), ("sddmm_min_blk_nnz", C.c_int32),
                 ("ts", C.c_int32), ("cs", C.c_int32), ("short_len", C.c_int32), ("sddmm_cs", C.c_int32),
-                ("flags", C.c_uint32), ("threads", C.c_int32), ("sddmm_ts", C.c_int32)]
+                ("flags", C.c_uint32), ("threads", C.c_int32), ("sddmm_ts", C.c_int32), ("sddmm_min_dense_pct", C.c_int32)]
 
     def __init__(self, **kw):
         super().__init__(**kw)

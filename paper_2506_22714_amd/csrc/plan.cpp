@@ -524,6 +524,8 @@ int libra::resolve_options(const libra_plan_opts_t *in, int vdt, Resolved &o) {
     o.short_len = z.short_len ? z.short_len : 3;
     o.sddmm_Cs = z.sddmm_cs ? z.sddmm_cs : 128;
     o.sddmm_Ts = z.sddmm_ts ? z.sddmm_ts : 4;
+    o.sddmm_min_dense_pct = z.sddmm_min_dense_pct;
+    if (o.sddmm_min_dense_pct < 0 || o.sddmm_min_dense_pct > 100) return LIBRA_ERR_OPTION;
     o.threads = z.threads;
     if (o.W < 1 || o.W > 32 || o.KB < 1 || o.KB > 64 || o.tau_spmm < 1 || o.tau_sddmm < 1 || o.Ts < 1 ||
         o.Cs < 1 || o.short_len < 1 || o.sddmm_Cs < 1 || o.sddmm_Ts < 1 || o.threads < 0)
@@ -747,6 +749,20 @@ extern "C" int libra_plan(int64_t M, int64_t Kc, const int32_t *rowptr, const in
             if (o.build_sddmm) concat(sd, pt.sddmm, false);
         }
         parts.clear();
+        if (o.build_sddmm && share_rule_fires(o, (int64_t)sd.dense_perm.size(), nnz)) {
+            // the dense blocks hold too small a share of the nonzeros to pay: every nonzero takes the scalar path, i.e.
+            // the sub-plan is what LIBRA_MODE_SCALAR_ONLY builds - the residual list is the matrix in CSR order
+            SubPlan all;
+            all.win_blkptr.assign((size_t)nwin + 1, 0);
+            all.blk_valptr.push_back(0);
+            all.res_perm.resize((size_t)nnz);
+            all.res_row.resize((size_t)nnz);
+            for (int64_t i = 0; i < M; ++i)
+                for (int32_t q = rowptr[i]; q < rowptr[i + 1]; ++q) { all.res_perm[q] = q; all.res_row[q] = (int32_t)i; }
+            all.res_col.assign(col, col + nnz);
+            all.res_val.assign((const uint8_t *)val, (const uint8_t *)val + (size_t)nnz * P->vsize);
+            sd = std::move(all);
+        }
         finish_plan(P, [col](int64_t p0, int64_t) { return col + p0; });
         st.plan_seconds = std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count();
     } catch (...) {

@@ -41,7 +41,7 @@ namespace {
 constexpr int W = 16, KB = 16;
 typedef unsigned long long u64;
 
-enum Counter { C_NV = 0, C_NNZ1, C_SHORT, C_LONG, C_SPLIT, C_DV_A, C_PAD_A, C_DV_D, C_PAD_D, C_ERR, C_TOGETHER, C_APART, C_COUNT };
+enum Counter { C_NV = 0, C_NNZ1, C_SHORT, C_LONG, C_SPLIT, C_DV_A, C_PAD_A, C_DV_D, C_PAD_D, C_ERR, C_TOGETHER, C_APART, C_DNNZ_D, C_COUNT };
 
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
@@ -359,6 +359,7 @@ __global__ __launch_bounds__(256) void k_window_counts(const int32_t *win_vptr, 
     if (ndv) { atomicAdd(&ctr[C_DV_A], (u64)ndv); }
     if (nb * KB - ndv) atomicAdd(&ctr[C_PAD_A], (u64)(nb * KB - ndv));
     if (ndvd) atomicAdd(&ctr[C_DV_D], (u64)ndvd);
+    if (ndvd) atomicAdd(&ctr[C_DNNZ_D], (u64)(cum[base + ndvd] - cum[base]));       // nonzeros in the window's dense SDDMM blocks
     if (nbd * KB - ndvd) atomicAdd(&ctr[C_PAD_D], (u64)(nbd * KB - ndvd));
 }
 
@@ -791,6 +792,17 @@ extern "C" int libra_plan_device(int64_t M, int64_t Kc, int64_t nnz, const int32
         // ---- 3. per window: dense vectors and blocks ----
         hipLaunchKernelGGL(k_window_counts, dim3(blocks_for(nw, 256)), dim3(256), 0, s, L.win_vptr, L.taud, L.cum, nw, R,
                            L.ntau, L.a.ndv, L.a.nb, L.d.ndv, L.d.nb, L.ctr);
+        if (o.build_sddmm && o.mode == LIBRA_MODE_HYBRID && o.sddmm_min_dense_pct > 0) {
+            // the whole-matrix utilisation rule: too small a dense share sends the whole SDDMM sub-plan to the scalar path
+            u64 dense_d = 0;
+            hip_ok(hipMemcpyAsync(&dense_d, L.ctr + C_DNNZ_D, sizeof dense_d, hipMemcpyDeviceToHost, s));
+            hip_ok(hipStreamSynchronize(s));
+            if (share_rule_fires(o, (int64_t)dense_d, nnz)) {
+                fill_bytes(L.d.nb, 0, (size_t)nw * sizeof(int32_t), s);
+                fill_bytes(L.d.ndv, 0, (size_t)nw * sizeof(int32_t), s);
+                fill_bytes(L.ctr + C_DV_D, 0, 2 * sizeof(u64), s);              // C_DV_D and C_PAD_D are neighbours
+            }
+        }
         fill_bytes(L.a.nb + nw, 0, sizeof(int32_t), s);
         fill_bytes(L.d.nb + nw, 0, sizeof(int32_t), s);
         scan(L, L.a.nb, L.a.blkptr, (size_t)nw + 1, s);

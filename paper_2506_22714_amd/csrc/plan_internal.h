@@ -109,9 +109,16 @@ struct SubPlan {
 
 struct Resolved {
     int mode, W, KB, tau_spmm, tau_sddmm, Ts, Cs, short_len, sddmm_Cs, sddmm_Ts, threads;
+    int sddmm_min_dense_pct = 0;        // 0: off
     bool fill, build_spmm, build_sddmm, heavy_first, segments_by_column, two_kernels;
     int xcd_order;       // 1 on, 0 off, -1 decide from the matrix
 };
+
+// The whole-matrix form of the utilisation rule for the SDDMM sub-plan (hybrid mode only): its dense blocks are kept only
+// if they hold at least sddmm_min_dense_pct percent of the nonzeros.
+inline bool share_rule_fires(const Resolved &o, int64_t dense_nnz, int64_t nnz) {
+    return o.mode == LIBRA_MODE_HYBRID && o.sddmm_min_dense_pct > 0 && 100 * dense_nnz < (int64_t)o.sddmm_min_dense_pct * nnz;
+}
 
 }  // namespace libra
 

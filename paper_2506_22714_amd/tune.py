@@ -41,6 +41,7 @@ SWEEPS = {
     "sddmm_ts": [dict(sddmm_ts=t) for t in (1, 2, 4, 8, 16)],
     "cs": [dict(cs=c) for c in (32, 64, 96, 128, 192, 256, 512)],
     "sddmm_cs": [dict(sddmm_cs=c) for c in (64, 128, 256, 512, 1024)],
+    "sddmm_share": [dict(sddmm_min_blk_nnz=32, sddmm_min_dense_pct=c) for c in (0, 25, 50, 75, 100)],
 }
 
 # The parts of the method switched off one at a time (the paper's ablations, Section 5.4): not part of "all".
@@ -65,9 +66,10 @@ ABLATION = [
 # found by coordinate descent from the library's defaults, written as a table that Plan.from_* can apply (tuned=...).
 # ---------------------------------------------------------------------------------------------------------------
 SPMM_AXES = [("spmm_min_vec_nnz", (2, 3, 4, 6)), ("ts", (8, 16, 32)), ("cs", (64, 128, 256))]
-SDDMM_AXES = [("sddmm_min_blk_nnz", (16, 32, 64, 128, 257)), ("sddmm_cs", (64, 128, 256)), ("sddmm_ts", (2, 4, 8, 16))]
+SDDMM_AXES = [("sddmm_min_blk_nnz", (16, 32, 64, 128, 257)), ("sddmm_cs", (64, 128, 256)), ("sddmm_ts", (2, 4, 8, 16)),
+              ("sddmm_min_dense_pct", (0, 50))]       # 0: the share rule is off
 SPMM_START = dict(spmm_min_vec_nnz=3, ts=16, cs=128)
-SDDMM_START = dict(sddmm_min_blk_nnz=64, sddmm_cs=128, sddmm_ts=4)
+SDDMM_START = dict(sddmm_min_blk_nnz=64, sddmm_cs=128, sddmm_ts=4, sddmm_min_dense_pct=0)
 N_CLASSES = {"n32": 32, "n64": 64, "n128": 128}      # class name -> the width the class is tuned at
 K_CLASSES = {"k32": 32, "k64": 64, "k128": 128}
 TUNER_WORKLOADS = ("powerlaw", "community", "gat", "irregular")
@@ -157,7 +159,7 @@ def tuned_options(table, dtype: str = "f16", N: int | None = None, K: int | None
             continue
         per_type = table[op].get("f16" if dtype == "bf16" else dtype) or table[op]["f16"]
         for name, v in per_type[cls]["options"].items():
-            if name not in allowed or not isinstance(v, int) or v < 1:
+            if name not in allowed or not isinstance(v, int) or v < (0 if name == "sddmm_min_dense_pct" else 1):
                 raise ValueError(f"bad entry {name}={v!r} in the tuned table")
             out[name] = v
     return out
@@ -284,7 +286,7 @@ def main() -> int:
             # a plan per setting, built on the GPU straight into device memory
             p = lb.Plan.from_device_csr(A.M, A.Kc, rowptr, col, val, resident=True, keep_host_copy=False, **kw)
             st = p.stats()
-            t_spmm = time_us(lambda: p.spmm(B, out=C)) if name not in ("tau_sddmm", "sddmm_cs") else float("nan")
+            t_spmm = time_us(lambda: p.spmm(B, out=C)) if name not in ("tau_sddmm", "sddmm_cs", "sddmm_share") else float("nan")
             t_sddmm = time_us(lambda: p.sddmm(X, Y, out=out)) if name not in ("tau_spmm", "cs") else float("nan")
             print(f"  {json.dumps(kw):34s} {t_spmm:9.1f} {st['spmm_dense_nnz'] / max(A.nnz, 1):6.3f} {st['spmm_tasks']:8d} | "
                   f"{t_sddmm:9.1f} {st['sddmm_dense_nnz'] / max(A.nnz, 1):6.3f} {st['sddmm_tasks']:8d}", flush=True)

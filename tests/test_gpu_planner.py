@@ -63,6 +63,8 @@ CASES = [
     dict(flags=lb.FLAG_NO_SDDMM | lb.FLAG_XCD_ORDER, spmm_min_vec_nnz=1),
     dict(flags=lb.FLAG_NO_SPMM | lb.FLAG_NO_XCD_ORDER, sddmm_min_blk_nnz=64),
     dict(spmm_min_vec_nnz=16, sddmm_min_blk_nnz=200),
+    dict(sddmm_min_blk_nnz=20, sddmm_min_dense_pct=30),
+    dict(sddmm_min_blk_nnz=20, sddmm_min_dense_pct=85),
 ]
 
 
@@ -119,7 +121,8 @@ def test_device_planner_random_options():
             A = wl.with_long_rows(A, [M // 2], min(Kc, 200), seed=it)
         kw = dict(mode=int(rng.integers(0, 3)), spmm_min_vec_nnz=int(rng.integers(1, 8)), sddmm_min_blk_nnz=int(rng.integers(1, 80)),
                   ts=int(rng.integers(1, 6)), cs=int(rng.integers(1, 40)), short_len=int(rng.integers(1, 5)),
-                  sddmm_cs=int(rng.integers(1, 60)), sddmm_ts=int(rng.integers(1, 9)), flags=int(rng.choice([0, 1, 8, 9, 16, 32, 256, 288])))
+                  sddmm_cs=int(rng.integers(1, 60)), sddmm_ts=int(rng.integers(1, 9)), flags=int(rng.choice([0, 1, 8, 9, 16, 32, 256, 288])),
+                  sddmm_min_dense_pct=int(rng.choice([0, 0, 25, 60, 100])))
         print("random case", it, M, Kc, A.nnz, kw, flush=True)
         ph = lb.Plan.from_csr(A, **kw)
         pd = device_plan(A, **kw)

@@ -60,6 +60,8 @@ def test_invalid_inputs_are_rejected_with_codes():
     assert _plan_rc(2, 3, rp, col, val.view(np.uint16), dtype=lb.BF16) == 0
     assert _plan_rc(2, 3, rp, col, val, opts=lb.PlanOpts(window_rows=33)) == lb.ERR["OPTION"]
     assert _plan_rc(2, 3, rp, col, val, opts=lb.PlanOpts(mode=5)) == lb.ERR["OPTION"]
+    assert _plan_rc(2, 3, rp, col, val, opts=lb.PlanOpts(sddmm_min_dense_pct=101)) == lb.ERR["OPTION"]
+    assert _plan_rc(2, 3, rp, col, val, opts=lb.PlanOpts(sddmm_min_dense_pct=-1)) == lb.ERR["OPTION"]
     bad = lb.PlanOpts()
     bad.struct_size = 8
     assert _plan_rc(2, 3, rp, col, val, opts=bad) == lb.ERR["OPTION"]
@@ -163,6 +165,8 @@ CASES = [
     dict(window_rows=8, block_cols=16, sddmm_min_blk_nnz=24, spmm_min_vec_nnz=3, ts=4, cs=16),
     dict(window_rows=32, block_cols=64, ts=1, cs=9),
     dict(flags=lb.FLAG_NATURAL_ORDER, ts=2, cs=6),
+    dict(sddmm_min_blk_nnz=20, sddmm_min_dense_pct=30),         # the dense-share rule: fires on some of the matrices
+    dict(sddmm_min_blk_nnz=20, sddmm_min_dense_pct=85),
 ]
 
 
@@ -172,7 +176,7 @@ def ref_opts(kw: dict) -> pr.Opts:
                    tau_spmm=kw.get("spmm_min_vec_nnz", 3), tau_sddmm=kw.get("sddmm_min_blk_nnz", 64),
                    Ts=kw.get("ts", 16), Cs=kw.get("cs", 128), short_len=kw.get("short_len", 3),
                    fill_padding=not (fl & lb.FLAG_NO_FILL_PADDING), sddmm_Cs=kw.get("sddmm_cs", 128),
-                   sddmm_Ts=kw.get("sddmm_ts", 4))
+                   sddmm_Ts=kw.get("sddmm_ts", 4), sddmm_min_dense_pct=kw.get("sddmm_min_dense_pct", 0))
 
 
 def matrices():

@@ -211,6 +211,26 @@ def test_sddmm_plan_invariants(seed, W, KB, tau):
     assert sum(sizes) == len(sp.res_perm) and all(0 < s <= 50 for s in sizes)
 
 
+def test_sddmm_dense_share_rule():
+    """The whole-matrix form of the utilisation rule: in the hybrid mode the SDDMM sub-plan keeps its dense blocks only if they
+    hold at least the given percentage of the nonzeros; below it the plan is the scalar-only plan.  Off (0), and in the
+    two single-path modes, nothing changes."""
+    A = wl.community(n_blocks=6, seed=2)
+    base = pr.plan_sddmm(A.M, A.rowptr, A.col, pr.Opts(tau_sddmm=40))
+    share = 100.0 * base.stats["dense_nnz"] / A.nnz
+    assert 5 < share < 95
+    scalar = pr.plan_sddmm(A.M, A.rowptr, A.col, pr.Opts(mode=pr.SCALAR_ONLY))
+    just_below, just_above = int(np.floor(share)), int(np.floor(share)) + 1        # share is not a whole number here
+    assert just_below < share < just_above
+    kept = pr.plan_sddmm(A.M, A.rowptr, A.col, pr.Opts(tau_sddmm=40, sddmm_min_dense_pct=just_below))
+    dropped = pr.plan_sddmm(A.M, A.rowptr, A.col, pr.Opts(tau_sddmm=40, sddmm_min_dense_pct=just_above))
+    assert kept.stats == base.stats and kept.res_perm == base.res_perm and kept.tasks == base.tasks
+    assert dropped.stats["dense_nnz"] == 0 and not dropped.blocks
+    assert dropped.res_perm == scalar.res_perm == list(range(A.nnz)) and dropped.tasks == scalar.tasks
+    dense_only = pr.plan_sddmm(A.M, A.rowptr, A.col, pr.Opts(mode=pr.DENSE_ONLY, sddmm_min_dense_pct=100))
+    assert dense_only.stats["dense_nnz"] == A.nnz                                  # the rule belongs to the hybrid mode
+
+
 # ------------------------------------------------- three decomposition cases
 def test_three_decomposition_cases():
     """Section 4.3: (0) dense part and a long row both decomposed -> every
