@@ -65,7 +65,7 @@ ABLATION = [
 # The tuner proper: per (value type, feature-width class) the setting with the best geometric mean over the workloads,
 # found by coordinate descent from the library's defaults, written as a table that Plan.from_* can apply (tuned=...).
 # ---------------------------------------------------------------------------------------------------------------
-SPMM_AXES = [("spmm_min_vec_nnz", (2, 3, 4, 6)), ("ts", (8, 16, 32)), ("cs", (64, 128, 256))]
+SPMM_AXES = [("spmm_min_vec_nnz", (2, 3, 4, 6)), ("ts", (8, 16, 32, 64)), ("cs", (64, 96, 128, 192, 256))]
 SDDMM_AXES = [("sddmm_min_blk_nnz", (16, 32, 64, 128, 257)), ("sddmm_cs", (64, 128, 256)), ("sddmm_ts", (2, 4, 8, 16)),
               ("sddmm_min_dense_pct", (0, 50))]       # 0: the share rule is off
 SPMM_START = dict(spmm_min_vec_nnz=3, ts=16, cs=128)
