@@ -809,6 +809,7 @@ def test_seeded_sweep_of_shapes_types_modes_and_planners():
         mode = int(rng.choice([lb.MODE_HYBRID, lb.MODE_HYBRID, lb.MODE_DENSE_ONLY, lb.MODE_SCALAR_ONLY]))
         flags = int(rng.choice([0, lb.FLAG_XCD_ORDER, lb.FLAG_NO_XCD_ORDER, lb.FLAG_SEGMENTS_BY_COST, lb.FLAG_TWO_KERNELS]))
         dt, tol = (np.float32, TOL_F32) if f32 else (np.float16, TOL_F16)
+        share = (0, 40, 80)[it % 3]             # the dense-share rule of the SDDMM sub-plan: off, and two thresholds
         val = A.val.astype(dt)
         B, X, Y = (wl.dense_normal(r, c, seed=it + s).astype(dt) for r, c, s in ((A.Kc, N, 100), (A.M, K, 200), (A.Kc, K, 300)))
         new_val = wl.uniform_values(np.random.default_rng(it), A.nnz).astype(dt)
@@ -816,11 +817,11 @@ def test_seeded_sweep_of_shapes_types_modes_and_planners():
             if planner == "device" and A.nnz == 0:
                 continue
             if planner == "host":
-                p = lb.Plan(A.M, A.Kc, A.rowptr, A.col, val, mode=mode, flags=flags).upload()
+                p = lb.Plan(A.M, A.Kc, A.rowptr, A.col, val, mode=mode, flags=flags, sddmm_min_dense_pct=share).upload()
             else:
                 rp, col, v = (dev(x) for x in (A.rowptr.astype(np.int32), A.col.astype(np.int32), val))
-                p = lb.Plan.from_device_csr(A.M, A.Kc, rp, col, v, resident=True, keep_host_copy=False, mode=mode, flags=flags)
-            where = f"case {it} ({planner} planner): M={M} Kc={Kc} nnz={A.nnz} f32={f32} N={N} K={K} mode={mode} flags={flags}"
+                p = lb.Plan.from_device_csr(A.M, A.Kc, rp, col, v, resident=True, keep_host_copy=False, mode=mode, flags=flags, sddmm_min_dense_pct=share)
+            where = f"case {it} ({planner} planner): M={M} Kc={Kc} nnz={A.nnz} f32={f32} N={N} K={K} mode={mode} flags={flags} share={share}"
             out = torch.full((A.nnz,), float("nan"), dtype=torch.float32, device="cuda")
             for values in (val, new_val):
                 if values is new_val:
