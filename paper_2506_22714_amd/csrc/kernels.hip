@@ -1143,6 +1143,25 @@ __global__ __launch_bounds__(256) void refresh_record_values_kernel(const uint16
 }
 
 // the same into the value runs of the blocked entry layout
+// 16-bit values, eight consecutive destinations per thread: the permutation arrives as two 16-byte loads and the values
+// leave as one 16-byte store (a group of eight never straddles a block of the blocked layout: 64 values per block).
+// BLOCKED: the value runs of the blocked SpMM entries; otherwise a plain array of 16-bit values.
+template <bool BLOCKED>
+__global__ __launch_bounds__(256) void scatter_values16_x8_kernel(const uint16_t *src, const int32_t *perm, int64_t n, unsigned char *dst) {
+    static_assert(RES_BLOCK % 8 == 0, "a group of eight values stays inside one block");
+    const int64_t groups = n / 8;
+    const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x, nthreads = (int64_t)gridDim.x * blockDim.x;
+    auto where = [&](int64_t i) {
+        return BLOCKED ? dst + (i / RES_BLOCK) * (RES_BLOCK * 6) + RES_BLOCK * 4 + (i % RES_BLOCK) * 2 : dst + i * 2;
+    };
+    for (int64_t g = tid; g < groups; g += nthreads) {
+        const int4 p0 = reinterpret_cast<const int4 *>(perm)[2 * g], p1 = reinterpret_cast<const int4 *>(perm)[2 * g + 1];
+        const uint32_t v0 = src[p0.x], v1 = src[p0.y], v2 = src[p0.z], v3 = src[p0.w];
+        const uint32_t v4 = src[p1.x], v5 = src[p1.y], v6 = src[p1.z], v7 = src[p1.w];
+        *reinterpret_cast<uint4 *>(where(g * 8)) = uint4{v0 | v1 << 16, v2 | v3 << 16, v4 | v5 << 16, v6 | v7 << 16};
+    }
+    for (int64_t i = groups * 8 + tid; i < n; i += nthreads) *reinterpret_cast<uint16_t *>(where(i)) = src[perm[i]];
+}
 template <class T>
 __global__ __launch_bounds__(256) void scatter_blocked_values_kernel(const T *src, const int32_t *perm, int64_t n, unsigned char *dst) {
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x)
@@ -1647,10 +1666,13 @@ extern "C" int libra_plan_set_values_for(libra_plan_t *P, const void *vals, int 
         const Seg &g = segs[k];
         if (g.n == 0 || !(ops & (k < 2 ? LIBRA_OP_SPMM : LIBRA_OP_SDDMM))) continue;
         const unsigned blocks = (unsigned)std::min<int64_t>((g.n + 255) / 256, 1 << 16);
+        const unsigned blocks8 = (unsigned)std::min<int64_t>((g.n / 8 + 255) / 256 + 1, 1 << 16);
         if (k == 2 && sorted_records(P))
             hipLaunchKernelGGL(refresh_record_values_kernel, dim3(blocks), dim3(256), 0, s, (const uint16_t *)vals, g.n, (SdPv *)g.dst);
         else if (g.stride == 0 && f16)
-            hipLaunchKernelGGL((scatter_blocked_values_kernel<uint16_t>), dim3(blocks), dim3(256), 0, s, (const uint16_t *)vals, g.perm, g.n, (unsigned char *)g.dst);
+            hipLaunchKernelGGL((scatter_values16_x8_kernel<true>), dim3(blocks8), dim3(256), 0, s, (const uint16_t *)vals, g.perm, g.n, (unsigned char *)g.dst);
+        else if (g.stride == 2 && g.offset == 0 && f16)
+            hipLaunchKernelGGL((scatter_values16_x8_kernel<false>), dim3(blocks8), dim3(256), 0, s, (const uint16_t *)vals, g.perm, g.n, (unsigned char *)g.dst);
         else if (g.stride == 0)
             hipLaunchKernelGGL((scatter_blocked_values_kernel<float>), dim3(blocks), dim3(256), 0, s, (const float *)vals, g.perm, g.n, (unsigned char *)g.dst);
         else if (f16)
