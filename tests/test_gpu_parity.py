@@ -351,6 +351,21 @@ def test_edge_softmax_at_every_row_length_class_boundary():
     assert np.all(np.abs(sums[np.asarray(lengths) > 0] - 1.0) < 1e-5)
     a16 = p.edge_softmax(dev(scores), scale).cpu().numpy().astype(np.float64)
     assert np.max(np.abs(a16 - ref) / np.maximum(ref, 2.0 ** -14)) < 1e-3
+    # the arrays need no more than their element alignment: views that start one element into a larger buffer are 4-byte
+    # (scores, fp32 output) or 2-byte (fp16 output) aligned only and must give the same results to the same bars
+    sbuf = torch.zeros(A.nnz + 1, dtype=torch.float32, device="cuda")
+    sbuf[1:] = dev(scores)
+    for dt in (torch.float32, torch.float16):
+        obuf = torch.full((A.nnz + 1,), float("nan"), dtype=dt, device="cuda")
+        assert sbuf[1:].data_ptr() % 16 != 0 and obuf[1:].data_ptr() % 16 != 0
+        odd = p.edge_softmax(sbuf[1:], scale, out=obuf[1:]).cpu().numpy().astype(np.float64)
+        even = p.edge_softmax(dev(scores), scale, out=torch.empty(A.nnz, dtype=dt, device="cuda"))
+        assert even.data_ptr() % 16 == 0 and bool(torch.isnan(obuf[0]))           # nothing written in front of the view
+        for got_x in (odd, even.cpu().numpy().astype(np.float64)):
+            if dt == torch.float32:
+                assert np.max(np.abs(got_x - ref) / ref) < 2e-5
+            else:
+                assert np.max(np.abs(got_x - ref) / np.maximum(ref, 2.0 ** -14)) < 1e-3
     ds = p.edge_softmax_backward(a32, dev(dalpha), scale).cpu().numpy().astype(np.float64)
     dot = np.bincount(rows, weights=got * dalpha, minlength=A.M)
     sabs = np.bincount(rows, weights=np.abs(got * dalpha), minlength=A.M)
